@@ -1,0 +1,176 @@
+"""TEST INFRASTRUCTURE: ctypes front end of the sequential CPU oracle (tent_oracle.c).
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import
+this package.  It shares nothing with the HIP engine; inputs are the plain
+numpy arrays produced by the workload generator.
+
+Every function is a thin call into the C file; the comments there cite the
+passages of the paper each step follows.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboracle.so")
+_SRC_PATH = os.path.join(_HERE, "tent_oracle.c")
+
+OK, DEFER = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile tent_oracle.c with gcc (plain -O2, no vectorisation flags beyond the default)."""
+    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC_PATH):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
+                               "-o", _LIB_PATH, _SRC_PATH])
+    return _LIB_PATH
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB_PATH)
+        L.ora_count_slices.restype = C.c_uint64
+        L.ora_cost.restype = C.c_uint64
+        L.ora_cost.argtypes = [C.c_uint64] * 4
+        L.ora_bind.restype = C.c_int
+        L.ora_retire.restype = C.c_uint64
+        L.ora_split.restype = None
+        L.ora_coeffs.restype = None
+        L.ora_stage_bases.restype = None
+        L.ora_execute.restype = None
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(C.c_void_p)
+
+
+@dataclass
+class Slices:
+    first: np.ndarray      # uint64[D+1]
+    desc: np.ndarray       # uint32[N]
+    off: np.ndarray        # uint64[N]
+    len: np.ndarray        # uint32[N]
+
+    @property
+    def n(self) -> int:
+        return int(self.desc.shape[0])
+
+
+@dataclass
+class Binding:
+    status: int
+    rail: np.ndarray       # uint32[N]   (only entries of bound ids are meaningful)
+    stage_off: np.ndarray  # uint64[N]
+    T: np.ndarray          # uint64[R]   bytes bound per rail in this call
+    n_slices: np.ndarray   # uint64[R]
+    A_after: np.ndarray    # uint64[R]   queued bytes after this call
+    base: np.ndarray       # uint64[R]   staging region bases
+
+
+def split(src_ptr, src_ext, slice_bytes: int) -> Slices:
+    L = lib()
+    D = src_ptr.shape[0] - 1
+    first = np.zeros(D + 1, dtype=np.uint64)
+    n = L.ora_count_slices(C.c_uint32(D), _p(src_ptr), _p(src_ext), C.c_uint64(slice_bytes), _p(first))
+    desc = np.zeros(n, dtype=np.uint32)
+    off = np.zeros(n, dtype=np.uint64)
+    ln = np.zeros(n, dtype=np.uint32)
+    L.ora_split(C.c_uint32(D), _p(src_ptr), _p(src_ext), C.c_uint64(slice_bytes), _p(desc), _p(off), _p(ln))
+    return Slices(first, desc, off, ln)
+
+
+def coeffs(rails):
+    L = lib()
+    R = rails.shape[0]
+    c0 = np.zeros(R, dtype=np.uint64)
+    c1 = np.zeros(R, dtype=np.uint64)
+    ex = np.zeros(R, dtype=np.uint8)
+    A = np.zeros(R, dtype=np.uint64)
+    L.ora_coeffs(_p(np.ascontiguousarray(rails)), C.c_uint32(R), _p(c0), _p(c1), _p(ex), _p(A))
+    return c0, c1, ex, A
+
+
+def cost(c0: int, c1: int, A: int, Lbytes: int) -> int:
+    return int(lib().ora_cost(c0, c1, A, Lbytes))
+
+
+def bind(slice_len, rails, ids=None, rail=None, stage_off=None) -> Binding:
+    """Bind slices (all, or those listed in ids) under the given telemetry."""
+    L = lib()
+    R = rails.shape[0]
+    N = slice_len.shape[0]
+    c0, c1, ex, A = coeffs(rails)
+    T = np.zeros(R, dtype=np.uint64)
+    cnt = np.zeros(R, dtype=np.uint64)
+    if rail is None:
+        rail = np.full(N, 0xFFFFFFFF, dtype=np.uint32)
+    if stage_off is None:
+        stage_off = np.zeros(N, dtype=np.uint64)
+    n = N if ids is None else ids.shape[0]
+    st = L.ora_bind(C.c_uint64(n), _p(ids), _p(slice_len), C.c_uint32(R), _p(c0), _p(c1), _p(ex),
+                    _p(A), _p(T), _p(cnt), _p(rail), _p(stage_off))
+    base = np.zeros(R, dtype=np.uint64)
+    L.ora_stage_bases(_p(T), C.c_uint32(R), _p(base))
+    return Binding(int(st), rail, stage_off, T, cnt, A, base)
+
+
+def execute(w, s: Slices, b: Binding, pools, staging: np.ndarray, ids=None) -> None:
+    """Move the listed slices: paged source -> per-rail staging -> destination."""
+    L = lib()
+    n = s.n if ids is None else ids.shape[0]
+    seg = (C.c_void_p * len(pools))(*[p.ctypes.data for p in pools])
+    L.ora_execute(C.c_uint64(n), _p(ids), _p(s.desc), _p(s.off), _p(s.len), _p(b.rail), _p(b.stage_off),
+                  _p(b.base), _p(w.src_ptr), _p(w.src_ext), _p(w.dst_ptr), _p(w.dst_ext), seg, _p(staging))
+
+
+def retire(s: Slices, b: Binding, queued, budget, ids=None) -> np.ndarray:
+    L = lib()
+    n = s.n if ids is None else ids.shape[0]
+    done = np.zeros(n, dtype=np.uint8)
+    L.ora_retire(C.c_uint64(n), _p(ids), _p(s.len), _p(b.rail), _p(b.stage_off),
+                 _p(np.ascontiguousarray(queued, dtype=np.uint64)),
+                 _p(np.ascontiguousarray(budget, dtype=np.uint64)), _p(done))
+    return done
+
+
+def run_epochs(w, s: Slices, pools=None, staging=None):
+    """Re-planning workload: per epoch bind the pending slices under that epoch's
+    telemetry, retire what the rails' byte budgets allow, move the retired slices,
+    and carry the rest over; a final drain pass with unlimited budget finishes.
+    Returns one record per pass."""
+    pending = np.arange(s.n, dtype=np.uint32)
+    records = []
+    for ep in list(w.epochs) + [w.drain]:
+        if pending.shape[0] == 0:
+            records.append(dict(pending=pending, status=OK, rail=None, stage_off=None, done_ids=pending,
+                                T=None, base=None))
+            continue
+        b = bind(s.len, ep.rails, ids=pending)
+        if b.status != OK:
+            records.append(dict(pending=pending, status=b.status, rail=None, stage_off=None,
+                                done_ids=pending[:0], T=b.T, base=b.base))
+            continue
+        done = retire(s, b, ep.rails["queued_bytes"], ep.budget, ids=pending).astype(bool)
+        done_ids = np.ascontiguousarray(pending[done])
+        if pools is not None and done_ids.shape[0]:
+            execute(w, s, b, pools, staging, ids=done_ids)
+        records.append(dict(pending=pending, status=OK, rail=b.rail[pending].copy(),
+                            stage_off=b.stage_off[pending].copy(), done_ids=done_ids, T=b.T, base=b.base))
+        pending = np.ascontiguousarray(pending[~done])
+    return records, pending

@@ -1,0 +1,223 @@
+/*
+ * TEST INFRASTRUCTURE -- sequential CPU oracle for the slice-spraying hot path.
+ *
+ * This file is the checker, not the product.  It is plain, single-threaded C
+ * written for legibility against the paper, and shares no code, header, table
+ * or helper with the HIP engine.  Only tests, the smoke check and the
+ * benchmark's "cpu_baseline" leg may load it.
+ *
+ * What it follows (TENT, Section 4.2 "Telemetry-Driven Slice Spraying"):
+ *   - Slice decomposition: every declared transfer is cut into slices of a
+ *     fixed size S; each slice carries its absolute offset inside the transfer
+ *     so that it can be written straight to its final place (Section 4.2,
+ *     "Slice Decomposition"; the task triple <path, offset, length> of
+ *     Algorithm 1).
+ *   - Predictive cost: t_d = beta0_d + beta1_d * (A_d + L) / B_d, scaled by the
+ *     topology penalty P_d (Eq. 1; Algorithm 1, Stage 2).
+ *   - Late binding: each slice goes to the admitted rail with the smallest
+ *     predicted completion cost (Section 4.2 opening paragraph); a rail that is
+ *     excluded behaves as if its cost were infinite (Section 4.3, "Health
+ *     Monitoring"); with no admitted rail the request is deferred (Algorithm 1,
+ *     Stage 1).
+ *   - Bytes in flight feed back into A_d (Eq. 1's definition of A_d; Section
+ *     4.3 "Link-Level Resilience": every issued slice counts in the queue
+ *     statistics).
+ *   - Staged movement through an intermediate buffer, then a direct write at the
+ *     slice's absolute destination offset (Section 4.1 "Autonomous Path
+ *     Synthesis"; Section 4.4).
+ *
+ * Readings where the paper is silent (all integer, no floating point):
+ *   c1_d   = floor(1e6 * beta1_q8 * penalty_q8 / bw_MBps)   picoseconds per byte, Q16
+ *   c0_d   = (lat_ns * 1000 * penalty_q8) >> 8              picoseconds
+ *   cost_d = c0_d + (((A_d + L) * c1_d) >> 16)
+ *   ties go to the lowest rail index; slices are bound in ascending index order;
+ *   a rail's staging region packs its slices in bind order; region bases are the
+ *   exclusive sum of the rails' byte totals, each rounded up to 256 bytes.
+ */
+#include <stdint.h>
+#include <string.h>
+
+typedef struct { uint32_t seg; uint32_t len; uint64_t off; } ora_extent;
+
+typedef struct {
+    uint32_t bw_MBps;
+    uint32_t lat_ns;
+    uint64_t queued_bytes;
+    uint16_t beta1_q8;
+    uint16_t penalty_q8;
+    uint8_t  health;      /* 2 = excluded */
+} ora_rail;
+
+enum { ORA_OK = 0, ORA_DEFER = 1, ORA_BAD = -1 };
+
+/* ---- slice decomposition (Section 4.2, "Slice Decomposition") ------------- */
+
+static uint64_t desc_len(const uint32_t *ptr, const ora_extent *ext, uint32_t j)
+{
+    uint64_t total = 0;
+    for (uint32_t e = ptr[j]; e < ptr[j + 1]; ++e) total += ext[e].len;
+    return total;
+}
+
+/* first[j] = index of descriptor j's first slice; first[D] = total slice count. */
+uint64_t ora_count_slices(uint32_t D, const uint32_t *ptr, const ora_extent *ext,
+                          uint64_t S, uint64_t *first)
+{
+    uint64_t n = 0;
+    for (uint32_t j = 0; j < D; ++j) {
+        first[j] = n;
+        uint64_t len = desc_len(ptr, ext, j);
+        n += (len + S - 1) / S;
+    }
+    first[D] = n;
+    return n;
+}
+
+/* Slice k of descriptor j covers bytes [k*S, min((k+1)*S, len_j)) of the transfer. */
+void ora_split(uint32_t D, const uint32_t *ptr, const ora_extent *ext, uint64_t S,
+               uint32_t *s_desc, uint64_t *s_off, uint32_t *s_len)
+{
+    uint64_t i = 0;
+    for (uint32_t j = 0; j < D; ++j) {
+        uint64_t len = desc_len(ptr, ext, j);
+        for (uint64_t off = 0; off < len; off += S, ++i) {
+            uint64_t rest = len - off;
+            s_desc[i] = j;
+            s_off[i]  = off;
+            s_len[i]  = (uint32_t)(rest < S ? rest : S);
+        }
+    }
+}
+
+/* ---- rail telemetry -> integer cost coefficients (Eq. 1 with penalty) ------ */
+
+void ora_coeffs(const ora_rail *rails, uint32_t R,
+                uint64_t *c0, uint64_t *c1, uint8_t *excluded, uint64_t *A)
+{
+    for (uint32_t d = 0; d < R; ++d) {
+        uint64_t bp = (uint64_t)rails[d].beta1_q8 * rails[d].penalty_q8;
+        c1[d] = rails[d].bw_MBps ? (1000000ull * bp) / rails[d].bw_MBps : ~0ull;
+        c0[d] = ((uint64_t)rails[d].lat_ns * 1000ull * rails[d].penalty_q8) >> 8;
+        excluded[d] = (rails[d].health == 2);
+        A[d] = rails[d].queued_bytes;
+    }
+}
+
+uint64_t ora_cost(uint64_t c0, uint64_t c1, uint64_t A, uint64_t L)
+{
+    return c0 + (((A + L) * c1) >> 16);
+}
+
+/* ---- late binding (Algorithm 1 Stage 1-2, per-slice earliest completion) ---
+ * ids == NULL binds slices 0..n-1; otherwise slices ids[0..n-1] in that order.
+ * A[] is read and updated (bytes in flight); T[] receives the per-rail byte
+ * totals of this call; slices[] receives the per-rail slice counts. */
+int ora_bind(uint64_t n, const uint32_t *ids, const uint32_t *s_len, uint32_t R,
+             const uint64_t *c0, const uint64_t *c1, const uint8_t *excluded,
+             uint64_t *A, uint64_t *T, uint64_t *slices,
+             uint32_t *s_rail, uint64_t *s_stage_off)
+{
+    int admitted = 0;
+    for (uint32_t d = 0; d < R; ++d) {
+        T[d] = 0;
+        slices[d] = 0;
+        if (!excluded[d]) admitted = 1;
+    }
+    if (!admitted) return ORA_DEFER;
+
+    for (uint64_t q = 0; q < n; ++q) {
+        uint64_t i = ids ? ids[q] : q;
+        int best = -1;
+        uint64_t best_cost = 0;
+        for (uint32_t d = 0; d < R; ++d) {
+            if (excluded[d]) continue;
+            uint64_t cost = ora_cost(c0[d], c1[d], A[d], s_len[i]);
+            if (best < 0 || cost < best_cost) { best = (int)d; best_cost = cost; }
+        }
+        s_rail[i] = (uint32_t)best;
+        s_stage_off[i] = T[best];
+        T[best] += s_len[i];
+        A[best] += s_len[i];
+        slices[best] += 1;
+    }
+    return ORA_OK;
+}
+
+/* Staging region of rail d starts where the regions of rails < d end (256-byte aligned). */
+void ora_stage_bases(const uint64_t *T, uint32_t R, uint64_t *base)
+{
+    uint64_t at = 0;
+    for (uint32_t d = 0; d < R; ++d) {
+        base[d] = at;
+        at += (T[d] + 255) / 256 * 256;
+    }
+}
+
+/* ---- staged movement (Section 4.1 staging hop; Section 4.4 direct-to-offset) */
+
+/* Copy bytes [off, off+len) of the byte string formed by concatenating the
+ * extents ext[lo..hi) between that string and a flat buffer.  to_flat != 0:
+ * extents -> flat; otherwise flat -> extents. */
+static void move_range(uint8_t *const *seg_base, const ora_extent *ext, uint32_t lo, uint32_t hi,
+                       uint64_t off, uint64_t len, uint8_t *flat, int to_flat)
+{
+    uint64_t pos = 0;                    /* logical position of ext[e]'s first byte */
+    for (uint32_t e = lo; e < hi && len > 0; ++e) {
+        uint64_t end = pos + ext[e].len;
+        if (off < end) {
+            uint64_t within = off - pos;
+            uint64_t n = end - off;
+            if (n > len) n = len;
+            uint8_t *paged = seg_base[ext[e].seg] + ext[e].off + within;
+            if (to_flat) memcpy(flat, paged, n); else memcpy(paged, flat, n);
+            flat += n; off += n; len -= n;
+        }
+        pos = end;
+    }
+}
+
+/* Pass 1: every listed slice is gathered from its paged source into its rail's
+ * staging region.  Pass 2: every listed slice is written from staging to its
+ * absolute offset in the destination.  ids == NULL means slices 0..n-1. */
+void ora_execute(uint64_t n, const uint32_t *ids,
+                 const uint32_t *s_desc, const uint64_t *s_off, const uint32_t *s_len,
+                 const uint32_t *s_rail, const uint64_t *s_stage_off, const uint64_t *rail_base,
+                 const uint32_t *src_ptr, const ora_extent *src_ext,
+                 const uint32_t *dst_ptr, const ora_extent *dst_ext,
+                 uint8_t *const *seg_base, uint8_t *staging)
+{
+    for (uint64_t q = 0; q < n; ++q) {
+        uint64_t i = ids ? ids[q] : q;
+        uint32_t j = s_desc[i];
+        uint8_t *st = staging + rail_base[s_rail[i]] + s_stage_off[i];
+        move_range(seg_base, src_ext, src_ptr[j], src_ptr[j + 1], s_off[i], s_len[i], st, 1);
+    }
+    for (uint64_t q = 0; q < n; ++q) {
+        uint64_t i = ids ? ids[q] : q;
+        uint32_t j = s_desc[i];
+        uint8_t *st = staging + rail_base[s_rail[i]] + s_stage_off[i];
+        move_range(seg_base, dst_ext, dst_ptr[j], dst_ptr[j + 1], s_off[i], s_len[i], st, 0);
+    }
+}
+
+/* ---- rail simulator for the re-planning workload ---------------------------
+ * A rail drains its queue in order: the bytes that were already queued
+ * (queued[d]) go first, then this plan's slices in staging order.  A slice
+ * completes in the epoch iff its last byte fits the rail's byte budget;
+ * everything else returns to the pending set and is re-planned (Section 4.3,
+ * idempotent retry).  done[q] is written for the q-th listed slice. */
+uint64_t ora_retire(uint64_t n, const uint32_t *ids, const uint32_t *s_len,
+                    const uint32_t *s_rail, const uint64_t *s_stage_off,
+                    const uint64_t *queued, const uint64_t *budget, uint8_t *done)
+{
+    uint64_t n_done = 0;
+    for (uint64_t q = 0; q < n; ++q) {
+        uint64_t i = ids ? ids[q] : q;
+        uint32_t d = s_rail[i];
+        uint64_t last = queued[d] + s_stage_off[i] + s_len[i];
+        int fits = last >= queued[d] /* no wrap */ && last <= budget[d];
+        done[q] = (uint8_t)fits;
+        n_done += (uint64_t)fits;
+    }
+    return n_done;
+}
