@@ -1,0 +1,217 @@
+/*
+ * tent.h -- C ABI of the MI355X slice-spraying engine.
+ *
+ * The engine implements the data-parallel hot path of TENT's data plane on one
+ * GPU: declared transfer intents are cut into fixed-size slices, every slice is
+ * late-bound to a rail by the predicted-completion cost model, and the slice
+ * bytes move paged source -> per-rail contiguous staging region -> destination,
+ * all in device memory.  Rails are simulated: a rail is a staging region plus a
+ * telemetry record.
+ *
+ * Conventions for every call
+ *   - Return value: TENT_OK (0) or a negative tent_status.  TENT_DEFER (+1) is
+ *     returned by tent_plan when no rail is admitted.  Nothing is printed, no
+ *     exception crosses the boundary, the process is never aborted.
+ *   - "host" pointers are ordinary process memory and are copied before the call
+ *     returns.  "device" pointers are HIP device memory owned by the caller; the
+ *     library borrows them until tent_destroy.
+ *   - A context is bound to the HIP device that was current in tent_create and
+ *     must be used by one host thread at a time.
+ *   - `stream` arguments are hipStream_t values passed as void* (NULL = the
+ *     default stream).  Calls that take a stream only enqueue work unless stated.
+ */
+#ifndef TENT_H
+#define TENT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tent_ctx tent_ctx;     /* opaque engine instance                                   */
+typedef uint64_t tent_batch_t;        /* opaque batch handle (Section 3, "opaque batch handle")   */
+
+typedef enum {
+    TENT_OK          =  0,
+    TENT_DEFER       =  1,   /* no admitted rail: nothing bound (Algorithm 1, Stage 1)          */
+    TENT_ERR_INVALID = -1,   /* null pointer, malformed descriptor list, unknown handle          */
+    TENT_ERR_RANGE   = -2,   /* fixed-point precondition, rail count, arena or table capacity    */
+    TENT_ERR_STATE   = -3,   /* call out of order (e.g. execute before plan)                     */
+    TENT_ERR_NOMEM   = -4,   /* host or device allocation failed                                 */
+    TENT_ERR_HIP     = -5    /* a HIP runtime call failed                                        */
+} tent_status;
+
+enum { TENT_MAX_RAILS = 64 };
+
+/* tent_config.flags */
+enum {
+    TENT_FLAG_SKIP_OVERLAP_CHECK = 1u << 0,   /* tent_declare does not test extents for overlap  */
+    TENT_FLAG_PROFILE            = 1u << 1,   /* record HIP events around every kernel (see tent_get_timings) */
+    TENT_FLAG_SERIAL_BINDING     = 1u << 2    /* bind slice by slice on one wavefront instead of run-parallel  */
+};
+
+typedef struct {
+    uint64_t slice_bytes;      /* S > 0: fixed slice size (Section 4.2, "Slice Decomposition")    */
+    void    *staging_arena;    /* device: per-rail staging regions are carved from this           */
+    uint64_t staging_bytes;    /* capacity of the arena                                           */
+    uint32_t flags;
+    uint32_t copy_chunk_bytes; /* tuning, 0 = default: bytes of one slice that one workgroup moves  */
+    uint32_t copy_grid_cap;    /* tuning, 0 = default: upper bound on workgroups per copy launch    */
+    uint32_t reserved;
+} tent_config;
+
+/* One contiguous byte range of a registered segment (Section 3.1: a segment is a
+ * named memory range; here it is reduced to a device base pointer and a length). */
+typedef struct {
+    uint32_t seg;              /* id returned by tent_register_segment                            */
+    uint32_t len;              /* bytes, > 0                                                      */
+    uint64_t off;              /* byte offset inside the segment                                  */
+} tent_extent;
+
+/* Telemetry of one rail: the quantities of Eq. 1 (Section 4.2) in integer units. */
+typedef struct {
+    uint32_t bw_MBps;          /* B_d: bandwidth estimate in 10^6 bytes/s, > 0                    */
+    uint32_t lat_ns;           /* beta0_d: fixed latency                                          */
+    uint64_t queued_bytes;     /* A_d: bytes already in flight on the rail                        */
+    uint16_t beta1_q8;         /* beta1_d in Q8.8 (256 = 1.0)                                     */
+    uint16_t penalty_q8;       /* topology penalty P_d in Q8.8 (256 = 1.0)                        */
+    uint8_t  health;           /* 0 healthy, 1 degraded (treated as healthy), 2 excluded          */
+} tent_rail_state;
+
+typedef struct {
+    uint64_t n_slices;                       /* slices bound by this call                          */
+    uint64_t n_pending_before;               /* slices that were not DONE when the call started    */
+    uint64_t rail_bytes[TENT_MAX_RAILS];     /* bytes bound per rail by this call                  */
+    uint64_t rail_slices[TENT_MAX_RAILS];    /* slices bound per rail by this call                 */
+    uint64_t queued_after[TENT_MAX_RAILS];   /* A_d after this call = queued_bytes + rail_bytes    */
+    uint64_t stage_base[TENT_MAX_RAILS];     /* byte offset of each rail's region in the arena     */
+} tent_plan_info;
+
+enum { TENT_SLICE_PENDING = 0, TENT_SLICE_BOUND = 1, TENT_SLICE_DONE = 2 };
+
+/* One row of the slice table: the task triple <path, offset, length> of
+ * Algorithm 1 plus the bookkeeping of the staging hop. */
+typedef struct {
+    uint32_t desc;             /* descriptor (transfer) the slice belongs to                      */
+    uint32_t len;              /* bytes                                                           */
+    uint64_t off;              /* absolute byte offset inside the transfer                        */
+    uint64_t stage_off;        /* byte offset inside the rail's staging region                    */
+    uint32_t rail;             /* rail index; 0xFFFFFFFF while never bound                        */
+    uint32_t state;            /* TENT_SLICE_*                                                    */
+} tent_slice;
+
+/* Stage indices of tent_get_timings. */
+enum {
+    TENT_T_EXTENT_SCAN = 0,    /* prefix sums over extent lengths (source and destination)        */
+    TENT_T_SLICE_SCAN  = 1,    /* per-descriptor slice counts and their exclusive scan            */
+    TENT_T_EXPAND      = 2,    /* slice-table expansion                                           */
+    TENT_T_COMPACT     = 3,    /* pending-list compaction (re-planning only)                      */
+    TENT_T_BIND        = 4,    /* rail assignment                                                 */
+    TENT_T_GATHER      = 5,    /* paged source -> staging                                         */
+    TENT_T_SCATTER     = 6,    /* staging -> destination                                          */
+    TENT_T_COUNT       = 7
+};
+
+/* Create an engine on the current HIP device.  `cfg` is host memory. */
+int tent_create(tent_ctx **out, const tent_config *cfg);
+
+/* Release every batch and all device memory the library allocated.  Waits for the device. */
+int tent_destroy(tent_ctx *ctx);
+
+/* Register a device memory range as a segment.  *seg_out receives its id (0, 1, ...). */
+int tent_register_segment(tent_ctx *ctx, void *dev_base, uint64_t len, uint32_t *seg_out);
+
+/*
+ * Declare a batch of transfers (Section 3: the application states what to move
+ * and receives a handle).  Transfer j moves the byte string formed by
+ * concatenating src_ext[src_ptr[j] .. src_ptr[j+1]) onto the byte string formed
+ * by dst_ext[dst_ptr[j] .. dst_ptr[j+1]); both strings must have the same
+ * length.  All four arrays are host memory in CSR form (ptr arrays have
+ * n_desc+1 entries, ptr[0] = 0, nondecreasing).
+ * Errors: TENT_ERR_INVALID for null pointers, n_desc = 0, an empty transfer, a
+ * zero-length extent, an extent outside its segment, unequal source and
+ * destination lengths, or (unless TENT_FLAG_SKIP_OVERLAP_CHECK) a destination
+ * extent that overlaps another destination extent or any source extent of the
+ * batch; TENT_ERR_RANGE when the batch holds more than 2^32-2 slices.
+ * Device tables for the batch are allocated here, not in plan or execute.
+ */
+int tent_declare(tent_ctx *ctx, uint32_t n_desc,
+                 const uint32_t *src_ptr, const tent_extent *src_ext,
+                 const uint32_t *dst_ptr, const tent_extent *dst_ext,
+                 tent_batch_t *out);
+
+/*
+ * Split and bind (Section 4.2; Algorithm 1 Stages 1-2; Eq. 1).
+ * On a batch without DONE slices the slice table is (re)built on the device:
+ * slice k of transfer j covers bytes [k*S, min((k+1)*S, len_j)).  Then every
+ * slice that is not DONE is bound, in ascending slice index, to the admitted
+ * rail (health != 2) with the smallest
+ *     c0_d + (((A_d + len) * c1_d) >> 16),
+ *     c1_d = floor(1e6 * beta1_q8 * penalty_q8 / bw_MBps),  c0_d = (lat_ns*1000*penalty_q8) >> 8
+ * (picoseconds; ties to the lowest rail index), after which A_d += len.  The
+ * slice's staging offset is the number of bytes bound to that rail earlier in
+ * this call.  Rail d's staging region starts at the sum over d' < d of the
+ * rail totals rounded up to 256 bytes.
+ * `rails` is host memory (n_rails <= TENT_MAX_RAILS).  `info` is host memory or
+ * NULL; when it is non-NULL the call waits for the stream and fills it, when it
+ * is NULL the call only enqueues work on `stream`.
+ * Returns TENT_DEFER (and binds nothing) when every rail is excluded;
+ * TENT_ERR_RANGE when bw_MBps = 0, c1_d >= 2^32, (max A_d + pending bytes) *
+ * max c1_d >= 2^63, or the arena is smaller than pending bytes + 256*n_rails.
+ */
+int tent_plan(tent_ctx *ctx, tent_batch_t batch, const tent_rail_state *rails, uint32_t n_rails,
+              tent_plan_info *info, void *stream);
+
+/*
+ * Rail simulator used by the re-planning workload (not an operation of the
+ * paper): rail d drains, in order, its queued_bytes and then the slices bound
+ * to it by the last tent_plan.  A BOUND slice stays BOUND iff
+ * queued_bytes_d + stage_off + len <= budget_bytes[d]; otherwise it returns to
+ * PENDING and will be re-planned (Section 4.3, idempotent retry).
+ * `budget_bytes` is host memory with n_rails entries.  Waits for the stream;
+ * *n_done (host, may be NULL) receives the number of slices that stayed BOUND.
+ */
+int tent_sim_advance(tent_ctx *ctx, tent_batch_t batch, const uint64_t *budget_bytes,
+                     uint64_t *n_done, void *stream);
+
+/*
+ * Move every BOUND slice: gather its bytes from the paged source extents into
+ * its rail's staging region, then scatter from staging to the destination
+ * extents at the slice's absolute offset (Section 4.1 staging hop; Section 4.4
+ * direct-to-offset writes), and mark it DONE.  Enqueues on `stream` and
+ * returns; the caller synchronises the stream.  TENT_ERR_STATE if the batch was
+ * never planned.  A batch with no BOUND slice is a no-op.
+ */
+int tent_execute(tent_ctx *ctx, tent_batch_t batch, void *stream);
+
+/* Batch-level completion (Section 4.4): *remaining (host) receives the number of
+ * slices not DONE.  Waits for `stream`. */
+int tent_poll(tent_ctx *ctx, tent_batch_t batch, uint64_t *remaining, void *stream);
+
+/* Return every slice of the batch to PENDING (the next tent_plan rebuilds the table). */
+int tent_reset(tent_ctx *ctx, tent_batch_t batch, void *stream);
+
+/* Number of slices of the batch (known after tent_declare). */
+int tent_slice_count(tent_ctx *ctx, tent_batch_t batch, uint64_t *n_slices);
+
+/* Copy the slice table to host memory for verification.  `cap` = entries available in
+ * host_out; TENT_ERR_RANGE if too small.  Waits for the device. */
+int tent_get_plan(tent_ctx *ctx, tent_batch_t batch, tent_slice *host_out, uint64_t cap);
+
+/* With TENT_FLAG_PROFILE: milliseconds spent in each stage (TENT_T_*) during the
+ * most recent tent_plan / tent_execute on the batch's context; stages that did
+ * not run report 0.  Waits for the recorded events.  `ms_out` is host memory
+ * with TENT_T_COUNT entries. */
+int tent_get_timings(tent_ctx *ctx, float *ms_out);
+
+/* Free the batch's device tables.  Waits for the device. */
+int tent_release(tent_ctx *ctx, tent_batch_t batch);
+
+/* Static description of a status code. */
+const char *tent_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TENT_H */

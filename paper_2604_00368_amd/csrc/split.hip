@@ -1,0 +1,196 @@
+// Slice splitter: prefix sums over extent lengths, per-transfer slice counts and their
+// exclusive scan, slice-table expansion, and the pending-list compaction used when a
+// batch is re-planned.  Follows the paper's slice decomposition (Section 4.2): a
+// transfer of len bytes becomes ceil(len / S) slices; slice k covers [k*S, min((k+1)*S, len))
+// and keeps that absolute offset so it can be written straight to its destination.
+#include "scan.h"
+
+namespace tent {
+
+uint64_t scan_partials_capacity(uint64_t n) { return (n + kScanTile - 1) / kScanTile + 2; }
+
+// ---- S1: exclusive prefix of extent lengths over the whole batch -----------------------------
+struct ExtentLen {
+    const tent_extent* ext;
+    __device__ uint64_t operator()(uint64_t e) const { return ext[e].len; }
+};
+
+hipError_t launch_extent_scan(const tent_extent* ext, uint64_t n_ext, uint64_t* pre, uint64_t* partials,
+                              hipStream_t s)
+{
+    return exclusive_scan(ExtentLen{ext}, n_ext, pre, partials, s);
+}
+
+// ---- S2: slices per transfer, exclusive scan -> first slice index of every transfer ---------
+struct SliceCount {
+    const uint32_t* ptr;
+    const uint64_t* pre;
+    uint64_t S;
+    __device__ uint64_t operator()(uint64_t j) const
+    {
+        uint64_t len = pre[ptr[j + 1]] - pre[ptr[j]];
+        return (len + S - 1) / S;
+    }
+};
+
+hipError_t launch_slice_scan(const BatchDev& b, hipStream_t s)
+{
+    return exclusive_scan(SliceCount{b.src_ptr, b.src_pre, b.slice_bytes}, b.n_desc, b.first, b.scan_partials, s);
+}
+
+// ---- S3: slice table expansion ---------------------------------------------------------------
+// Largest index i in [lo, hi) with a[i] <= key (a is nondecreasing and a[lo] <= key).
+__device__ __forceinline__ uint64_t last_not_above(const uint64_t* a, uint64_t lo, uint64_t hi, uint64_t key)
+{
+    while (hi - lo > 1) {
+        uint64_t mid = lo + ((hi - lo) >> 1);
+        if (a[mid] <= key) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void __launch_bounds__(256) expand_kernel(BatchDev b)
+{
+    const uint64_t n = b.first[b.n_desc];
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        // owning transfer: transfers without slices cannot occur (every transfer has len > 0)
+        const uint32_t j = (uint32_t)last_not_above(b.first, 0, b.n_desc, i);
+        const uint32_t slo = b.src_ptr[j], shi = b.src_ptr[j + 1];
+        const uint32_t dlo = b.dst_ptr[j], dhi = b.dst_ptr[j + 1];
+        const uint64_t len_j = b.src_pre[shi] - b.src_pre[slo];
+        const uint64_t off = (i - b.first[j]) * b.slice_bytes;
+        const uint64_t rest = len_j - off;
+        b.s_desc[i] = j;
+        b.s_off[i] = off;
+        b.s_len[i] = (uint32_t)(rest < b.slice_bytes ? rest : b.slice_bytes);
+        b.s_src_e0[i] = (uint32_t)last_not_above(b.src_pre, slo, shi, b.src_pre[slo] + off);
+        b.s_dst_e0[i] = (uint32_t)last_not_above(b.dst_pre, dlo, dhi, b.dst_pre[dlo] + off);
+        b.s_rail[i] = 0xFFFFFFFFu;
+        b.s_stage_off[i] = 0;
+        b.s_state[i] = TENT_SLICE_PENDING;
+    }
+}
+
+hipError_t launch_expand(const BatchDev& b, hipStream_t s)
+{
+    uint64_t blocks = (b.n_slices + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(expand_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    return hipGetLastError();
+}
+
+// ---- E1: ascending list of slices that are not DONE -----------------------------------------
+struct NotDone {
+    const uint8_t* state;
+    __device__ uint64_t operator()(uint64_t i) const { return state[i] != TENT_SLICE_DONE; }
+};
+
+__global__ void __launch_bounds__(256) compact_kernel(BatchDev b)
+{
+    const uint64_t n = b.n_slices;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        if (b.s_state[i] != TENT_SLICE_DONE) b.pending[b.scan_tmp[i]] = (uint32_t)i;
+    if (blockIdx.x == 0 && threadIdx.x == 0) b.plan->n_pending = b.scan_tmp[n];
+}
+
+hipError_t launch_compact(const BatchDev& b, hipStream_t s)
+{
+    hipError_t e = exclusive_scan(NotDone{b.s_state}, b.n_slices, b.scan_tmp, b.scan_partials, s);
+    if (e != hipSuccess) return e;
+    uint64_t blocks = (b.n_slices + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(compact_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    return hipGetLastError();
+}
+
+// ---- slice state bookkeeping ------------------------------------------------------------------
+__global__ void __launch_bounds__(256) mark_done_kernel(BatchDev b)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slices; i += stride)
+        if (b.s_state[i] == TENT_SLICE_BOUND) b.s_state[i] = TENT_SLICE_DONE;
+}
+
+hipError_t launch_mark_done(const BatchDev& b, hipStream_t s)
+{
+    uint64_t blocks = (b.n_slices + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(mark_done_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256) reset_kernel(BatchDev b)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slices; i += stride)
+        b.s_state[i] = TENT_SLICE_PENDING;
+}
+
+hipError_t launch_reset(const BatchDev& b, hipStream_t s)
+{
+    uint64_t blocks = (b.n_slices + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(reset_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    return hipGetLastError();
+}
+
+// Rail simulator: a bound slice completes iff the rail's byte budget covers the bytes queued
+// ahead of the plan, the slices staged before it, and the slice itself; otherwise it returns to
+// the pending set.  The count of completed slices is an integer sum, so its value does not
+// depend on the order of the atomic adds.
+__global__ void __launch_bounds__(256) retire_kernel(BatchDev b, BudgetParams bp)
+{
+    __shared__ unsigned long long block_done;
+    if (threadIdx.x == 0) block_done = 0;
+    __syncthreads();
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    unsigned long long mine = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slices; i += stride) {
+        if (b.s_state[i] != TENT_SLICE_BOUND) continue;
+        const uint32_t d = b.s_rail[i];
+        const uint64_t last = bp.queued[d] + b.s_stage_off[i] + b.s_len[i];
+        const bool fits = last >= bp.queued[d] && last <= bp.budget[d];
+        if (fits) ++mine; else b.s_state[i] = TENT_SLICE_PENDING;
+    }
+    if (mine) atomicAdd(&block_done, mine);
+    __syncthreads();
+    if (threadIdx.x == 0 && block_done) atomicAdd((unsigned long long*)&b.plan->n_done, block_done);
+}
+
+__global__ void zero_counter_kernel(uint64_t* p) { *p = 0; }
+
+hipError_t launch_retire(const BatchDev& b, const BudgetParams& bp, hipStream_t s)
+{
+    hipLaunchKernelGGL(zero_counter_kernel, dim3(1), dim3(1), 0, s, &b.plan->n_done);
+    uint64_t blocks = (b.n_slices + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(retire_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, bp);
+    return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256) count_remaining_kernel(BatchDev b)
+{
+    __shared__ unsigned long long block_cnt;
+    if (threadIdx.x == 0) block_cnt = 0;
+    __syncthreads();
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    unsigned long long mine = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slices; i += stride)
+        mine += b.s_state[i] != TENT_SLICE_DONE;
+    if (mine) atomicAdd(&block_cnt, mine);
+    __syncthreads();
+    if (threadIdx.x == 0 && block_cnt) atomicAdd((unsigned long long*)&b.plan->n_remaining, block_cnt);
+}
+
+hipError_t launch_count_remaining(const BatchDev& b, hipStream_t s)
+{
+    hipLaunchKernelGGL(zero_counter_kernel, dim3(1), dim3(1), 0, s, &b.plan->n_remaining);
+    uint64_t blocks = (b.n_slices + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(count_remaining_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    return hipGetLastError();
+}
+
+}  // namespace tent

@@ -1,0 +1,553 @@
+// Host runtime behind the C ABI: argument validation, device tables, rail-state conversion and
+// kernel sequencing.  Every step of the hot path itself runs in the HIP kernels of this library.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "tent_internal.h"
+
+using namespace tent;
+
+namespace {
+
+struct Segment { uint8_t* base; uint64_t len; };
+
+struct Batch {
+    bool alive = false;
+    bool planned = false;        // a plan has been enqueued since declare / reset
+    bool has_done = false;       // execute ran since declare / reset: DONE slices may exist
+    uint32_t generation = 0;
+    uint64_t payload = 0;
+    RailParams last_rails{};     // telemetry of the last plan (for the rail simulator)
+    BatchDev dev{};
+    std::vector<void*> allocs;
+};
+
+struct Timing { hipEvent_t start = nullptr, stop = nullptr; bool used = false; };
+
+}  // namespace
+
+struct tent_ctx {
+    int device = 0;
+    tent_config cfg{};
+    std::vector<Segment> segments;
+    uint64_t* seg_base_dev = nullptr;       // device table of segment base addresses
+    uint32_t seg_capacity = 0;
+    std::vector<Batch> batches;
+    PlanState* host_plan = nullptr;         // pinned read-back buffer
+    Timing timing[TENT_T_COUNT];
+};
+
+namespace {
+
+constexpr uint32_t kMaxSegments = 4096;
+
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return TENT_ERR_HIP; } while (0)
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+        target = dev;
+    }
+    ~DeviceGuard() { if (prev >= 0 && prev != target) (void)hipSetDevice(prev); }
+    int target = -1;
+};
+
+Batch* find_batch(tent_ctx* ctx, tent_batch_t h)
+{
+    const uint64_t idx = (h & 0xFFFFFFFFull);
+    const uint32_t gen = (uint32_t)(h >> 32);
+    if (idx == 0 || idx > ctx->batches.size()) return nullptr;
+    Batch* b = &ctx->batches[idx - 1];
+    return (b->alive && b->generation == gen) ? b : nullptr;
+}
+
+template <class T>
+int dev_alloc(Batch& b, T** out, uint64_t count)
+{
+    void* p = nullptr;
+    if (hipMalloc(&p, std::max<uint64_t>(count, 1) * sizeof(T)) != hipSuccess) {
+        (void)hipGetLastError();
+        return TENT_ERR_NOMEM;
+    }
+    b.allocs.push_back(p);
+    *out = static_cast<T*>(p);
+    return TENT_OK;
+}
+
+void free_batch(Batch& b)
+{
+    for (void* p : b.allocs) (void)hipFree(p);
+    b.allocs.clear();
+    b.alive = false;
+    b.dev = BatchDev{};
+}
+
+struct Interval { uint64_t lo, hi; uint32_t seg; uint32_t is_dst; };
+
+// Walk both extent lists of every transfer: structure, bounds, equal lengths.  Also returns
+// the payload and the number of slices the device splitter will produce.
+int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const tent_extent* se,
+             const uint32_t* dp, const tent_extent* de, uint64_t* payload, uint64_t* n_slices)
+{
+    if (sp[0] != 0 || dp[0] != 0) return TENT_ERR_INVALID;
+    const uint64_t S = ctx->cfg.slice_bytes;
+    uint64_t total = 0, slices = 0;
+    for (uint32_t j = 0; j < n_desc; ++j) {
+        if (sp[j + 1] <= sp[j] || dp[j + 1] <= dp[j]) return TENT_ERR_INVALID;   // empty or non-monotone
+        uint64_t ls = 0, ld = 0;
+        for (uint32_t e = sp[j]; e < sp[j + 1]; ++e) {
+            const tent_extent& x = se[e];
+            if (x.len == 0 || x.seg >= ctx->segments.size()) return TENT_ERR_INVALID;
+            const uint64_t seg_len = ctx->segments[x.seg].len;
+            if (x.off > seg_len || x.len > seg_len - x.off) return TENT_ERR_INVALID;
+            ls += x.len;
+        }
+        for (uint32_t e = dp[j]; e < dp[j + 1]; ++e) {
+            const tent_extent& x = de[e];
+            if (x.len == 0 || x.seg >= ctx->segments.size()) return TENT_ERR_INVALID;
+            const uint64_t seg_len = ctx->segments[x.seg].len;
+            if (x.off > seg_len || x.len > seg_len - x.off) return TENT_ERR_INVALID;
+            ld += x.len;
+        }
+        if (ls != ld) return TENT_ERR_INVALID;
+        total += ls;
+        slices += (ls + S - 1) / S;
+    }
+    *payload = total;
+    *n_slices = slices;
+    return TENT_OK;
+}
+
+// A destination extent may overlap neither another destination extent nor a source extent
+// (addresses compared, so aliasing segments are caught as well).
+int check_overlap(const tent_ctx* ctx, uint64_t ns, const tent_extent* se, uint64_t nd, const tent_extent* de)
+{
+    std::vector<Interval> iv;
+    try { iv.reserve(ns + nd); } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
+    for (uint64_t e = 0; e < ns; ++e) {
+        uint64_t a = (uint64_t)ctx->segments[se[e].seg].base + se[e].off;
+        iv.push_back({a, a + se[e].len, se[e].seg, 0});
+    }
+    for (uint64_t e = 0; e < nd; ++e) {
+        uint64_t a = (uint64_t)ctx->segments[de[e].seg].base + de[e].off;
+        iv.push_back({a, a + de[e].len, de[e].seg, 1});
+    }
+    std::sort(iv.begin(), iv.end(), [](const Interval& x, const Interval& y) { return x.lo < y.lo; });
+    // sweep: remember the furthest end seen so far among destinations and among all intervals
+    uint64_t far_any = 0, far_dst = 0;
+    for (const Interval& x : iv) {
+        if (x.is_dst) { if (x.lo < far_any) return TENT_ERR_INVALID; }
+        else          { if (x.lo < far_dst) return TENT_ERR_INVALID; }
+        far_any = std::max(far_any, x.hi);
+        if (x.is_dst) far_dst = std::max(far_dst, x.hi);
+    }
+    return TENT_OK;
+}
+
+struct StageTimer {
+    tent_ctx* ctx; int stage; hipStream_t s; bool on;
+    StageTimer(tent_ctx* c, int st, hipStream_t stream) : ctx(c), stage(st), s(stream)
+    {
+        on = (c->cfg.flags & TENT_FLAG_PROFILE) != 0;
+        if (on) { (void)hipEventRecord(c->timing[st].start, s); }
+    }
+    ~StageTimer()
+    {
+        if (on) { (void)hipEventRecord(ctx->timing[stage].stop, s); ctx->timing[stage].used = true; }
+    }
+};
+
+void clear_timings(tent_ctx* ctx, int lo, int hi)
+{
+    for (int t = lo; t <= hi; ++t) ctx->timing[t].used = false;
+}
+
+// Telemetry -> integer coefficients (Eq. 1 with the topology penalty folded in).
+int convert_rails(const tent_rail_state* rails, uint32_t n_rails, uint64_t pending_bytes, RailParams* rp)
+{
+    std::memset(rp, 0, sizeof(*rp));
+    rp->n_rails = n_rails;
+    uint64_t max_c1 = 0, max_A = 0;
+    for (uint32_t d = 0; d < n_rails; ++d) {
+        const tent_rail_state& r = rails[d];
+        if (r.bw_MBps == 0) return TENT_ERR_RANGE;
+        const uint64_t bp = (uint64_t)r.beta1_q8 * r.penalty_q8;
+        const uint64_t c1 = (1000000ull * bp) / r.bw_MBps;
+        if (c1 >= (1ull << 32)) return TENT_ERR_RANGE;
+        rp->c1[d] = c1;
+        rp->c0[d] = ((uint64_t)r.lat_ns * 1000ull * r.penalty_q8) >> 8;
+        rp->A[d] = r.queued_bytes;
+        if (r.health != 2) {
+            rp->admitted |= 1ull << d;
+            max_c1 = std::max(max_c1, c1);
+            max_A = std::max(max_A, r.queued_bytes);
+        }
+    }
+    // (max A + pending bytes) * max c1 must stay below 2^63 so that no cost wraps
+    const unsigned __int128 worst = ((unsigned __int128)max_A + pending_bytes) * max_c1;
+    if (worst >= ((unsigned __int128)1 << 63)) return TENT_ERR_RANGE;
+    return TENT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tent_strerror(int status)
+{
+    switch (status) {
+        case TENT_OK:          return "ok";
+        case TENT_DEFER:       return "deferred: no admitted rail";
+        case TENT_ERR_INVALID: return "invalid argument";
+        case TENT_ERR_RANGE:   return "value out of range";
+        case TENT_ERR_STATE:   return "call out of order";
+        case TENT_ERR_NOMEM:   return "out of memory";
+        case TENT_ERR_HIP:     return "HIP runtime error";
+        default:               return "unknown status";
+    }
+}
+
+int tent_create(tent_ctx** out, const tent_config* cfg)
+{
+    if (!out || !cfg) return TENT_ERR_INVALID;
+    *out = nullptr;
+    if (cfg->slice_bytes == 0 || cfg->slice_bytes > 0xFFFFFFFFull) return TENT_ERR_INVALID;
+    if (!cfg->staging_arena || cfg->staging_bytes == 0) return TENT_ERR_INVALID;
+    tent_ctx* ctx = new (std::nothrow) tent_ctx;
+    if (!ctx) return TENT_ERR_NOMEM;
+    ctx->cfg = *cfg;
+    if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return TENT_ERR_HIP; }
+    ctx->seg_capacity = kMaxSegments;
+    if (hipMalloc((void**)&ctx->seg_base_dev, sizeof(uint64_t) * ctx->seg_capacity) != hipSuccess ||
+        hipHostMalloc((void**)&ctx->host_plan, sizeof(PlanState), hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        if (ctx->seg_base_dev) (void)hipFree(ctx->seg_base_dev);
+        delete ctx;
+        return TENT_ERR_NOMEM;
+    }
+    if (cfg->flags & TENT_FLAG_PROFILE) {
+        for (Timing& t : ctx->timing) {
+            if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) {
+                tent_destroy(ctx);
+                return TENT_ERR_HIP;
+            }
+        }
+    }
+    *out = ctx;
+    return TENT_OK;
+}
+
+int tent_destroy(tent_ctx* ctx)
+{
+    if (!ctx) return TENT_ERR_INVALID;
+    DeviceGuard g(ctx->device);
+    (void)hipDeviceSynchronize();
+    for (Batch& b : ctx->batches) if (b.alive) free_batch(b);
+    for (Timing& t : ctx->timing) {
+        if (t.start) (void)hipEventDestroy(t.start);
+        if (t.stop) (void)hipEventDestroy(t.stop);
+    }
+    if (ctx->seg_base_dev) (void)hipFree(ctx->seg_base_dev);
+    if (ctx->host_plan) (void)hipHostFree(ctx->host_plan);
+    delete ctx;
+    return TENT_OK;
+}
+
+int tent_register_segment(tent_ctx* ctx, void* dev_base, uint64_t len, uint32_t* seg_out)
+{
+    if (!ctx || !dev_base || len == 0 || !seg_out) return TENT_ERR_INVALID;
+    if (ctx->segments.size() >= ctx->seg_capacity) return TENT_ERR_RANGE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    const uint32_t id = (uint32_t)ctx->segments.size();
+    const uint64_t addr = (uint64_t)dev_base;
+    HIP_TRY(hipMemcpy(ctx->seg_base_dev + id, &addr, sizeof(addr), hipMemcpyHostToDevice));
+    ctx->segments.push_back({static_cast<uint8_t*>(dev_base), len});
+    *seg_out = id;
+    return TENT_OK;
+}
+
+int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const tent_extent* src_ext,
+                 const uint32_t* dst_ptr, const tent_extent* dst_ext, tent_batch_t* out)
+{
+    if (!ctx || !src_ptr || !src_ext || !dst_ptr || !dst_ext || !out || n_desc == 0) return TENT_ERR_INVALID;
+    *out = 0;
+    uint64_t payload = 0, n_slices = 0;
+    int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, &payload, &n_slices);
+    if (rc != TENT_OK) return rc;
+    if (n_slices >= 0xFFFFFFFEull) return TENT_ERR_RANGE;
+    const uint64_t ns = src_ptr[n_desc], nd = dst_ptr[n_desc];
+    if (!(ctx->cfg.flags & TENT_FLAG_SKIP_OVERLAP_CHECK)) {
+        rc = check_overlap(ctx, ns, src_ext, nd, dst_ext);
+        if (rc != TENT_OK) return rc;
+    }
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+
+    // reuse a dead slot or append
+    size_t slot = ctx->batches.size();
+    for (size_t k = 0; k < ctx->batches.size(); ++k) if (!ctx->batches[k].alive) { slot = k; break; }
+    if (slot == ctx->batches.size()) {
+        try { ctx->batches.emplace_back(); } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
+    }
+    Batch& b = ctx->batches[slot];
+    const uint32_t gen = b.generation + 1;
+    b = Batch{};
+    b.generation = gen;
+    b.payload = payload;
+    BatchDev& d = b.dev;
+    d.n_desc = n_desc;
+    d.n_src_ext = ns;
+    d.n_dst_ext = nd;
+    d.n_slices = n_slices;
+    d.slice_bytes = ctx->cfg.slice_bytes;
+    d.seg_base = ctx->seg_base_dev;
+
+    uint32_t *sp = nullptr, *dp = nullptr;
+    tent_extent *se = nullptr, *de = nullptr;
+    const uint64_t scan_n = std::max<uint64_t>(std::max(ns, nd), std::max<uint64_t>(n_slices, n_desc));
+    rc = dev_alloc(b, &sp, (uint64_t)n_desc + 1);
+    if (rc == TENT_OK) rc = dev_alloc(b, &dp, (uint64_t)n_desc + 1);
+    if (rc == TENT_OK) rc = dev_alloc(b, &se, ns);
+    if (rc == TENT_OK) rc = dev_alloc(b, &de, nd);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.src_pre, ns + 1);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.dst_pre, nd + 1);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.first, (uint64_t)n_desc + 1);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_desc, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_off, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_len, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_src_e0, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_dst_e0, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_rail, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_stage_off, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_state, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.pending, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_tmp, scan_n + 1);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_partials, scan_partials_capacity(scan_n));
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.plan, 1);
+    if (rc != TENT_OK) { free_batch(b); return rc; }
+    d.src_ptr = sp; d.dst_ptr = dp; d.src_ext = se; d.dst_ext = de;
+
+    if (hipMemcpy(sp, src_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(dp, dst_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(se, src_ext, sizeof(tent_extent) * ns, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(de, dst_ext, sizeof(tent_extent) * nd, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemset(d.plan, 0, sizeof(PlanState)) != hipSuccess) {
+        (void)hipGetLastError();
+        free_batch(b);
+        return TENT_ERR_HIP;
+    }
+    b.alive = true;
+    *out = ((uint64_t)b.generation << 32) | (uint64_t)(slot + 1);
+    return TENT_OK;
+}
+
+int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, uint32_t n_rails,
+              tent_plan_info* info, void* stream)
+{
+    if (!ctx || !rails) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (n_rails == 0 || n_rails > TENT_MAX_RAILS) return TENT_ERR_RANGE;
+    RailParams rp;
+    int rc = convert_rails(rails, n_rails, b->payload, &rp);
+    if (rc != TENT_OK) return rc;
+    if (rp.admitted == 0) return TENT_DEFER;
+    if (b->payload + 256ull * n_rails > ctx->cfg.staging_bytes) return TENT_ERR_RANGE;
+
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const BatchDev& d = b->dev;
+    clear_timings(ctx, TENT_T_EXTENT_SCAN, TENT_T_BIND);
+
+    const bool replan = b->has_done;
+    if (!replan) {
+        {
+            StageTimer t(ctx, TENT_T_EXTENT_SCAN, s);
+            HIP_TRY(launch_extent_scan(d.src_ext, d.n_src_ext, d.src_pre, d.scan_partials, s));
+            HIP_TRY(launch_extent_scan(d.dst_ext, d.n_dst_ext, d.dst_pre, d.scan_partials, s));
+        }
+        {
+            StageTimer t(ctx, TENT_T_SLICE_SCAN, s);
+            HIP_TRY(launch_slice_scan(d, s));
+        }
+        {
+            StageTimer t(ctx, TENT_T_EXPAND, s);
+            HIP_TRY(launch_expand(d, s));
+        }
+    } else {
+        StageTimer t(ctx, TENT_T_COMPACT, s);
+        HIP_TRY(launch_compact(d, s));
+    }
+    {
+        StageTimer t(ctx, TENT_T_BIND, s);
+        HIP_TRY(launch_bind_serial(d, rp, replan, s));
+    }
+    b->planned = true;
+    b->last_rails = rp;
+
+    if (info) {
+        HIP_TRY(hipMemcpyAsync(ctx->host_plan, d.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        const PlanState& ps = *ctx->host_plan;
+        std::memset(info, 0, sizeof(*info));
+        info->n_slices = ps.n_bound;
+        info->n_pending_before = ps.n_pending;
+        for (uint32_t r = 0; r < TENT_MAX_RAILS; ++r) {
+            info->rail_bytes[r] = ps.T[r];
+            info->rail_slices[r] = ps.cnt[r];
+            info->queued_after[r] = r < n_rails ? ps.A_after[r] : 0;
+            info->stage_base[r] = r < n_rails ? ps.base[r] : 0;
+        }
+    }
+    return TENT_OK;
+}
+
+int tent_sim_advance(tent_ctx* ctx, tent_batch_t batch, const uint64_t* budget_bytes, uint64_t* n_done,
+                     void* stream)
+{
+    if (!ctx || !budget_bytes) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (!b->planned) return TENT_ERR_STATE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    BudgetParams bp;
+    std::memset(&bp, 0, sizeof(bp));
+    for (uint32_t d = 0; d < b->last_rails.n_rails; ++d) {
+        bp.queued[d] = b->last_rails.A[d];
+        bp.budget[d] = budget_bytes[d];
+    }
+    HIP_TRY(launch_retire(b->dev, bp, s));
+    HIP_TRY(hipMemcpyAsync(ctx->host_plan, b->dev.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (n_done) *n_done = ctx->host_plan->n_done;
+    return TENT_OK;
+}
+
+int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
+{
+    if (!ctx) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (!b->planned) return TENT_ERR_STATE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* arena = static_cast<uint8_t*>(ctx->cfg.staging_arena);
+    clear_timings(ctx, TENT_T_GATHER, TENT_T_SCATTER);
+    {
+        StageTimer t(ctx, TENT_T_GATHER, s);
+        HIP_TRY(launch_copy(b->dev, arena, true, ctx->cfg.copy_chunk_bytes, ctx->cfg.copy_grid_cap, s));
+    }
+    {
+        StageTimer t(ctx, TENT_T_SCATTER, s);
+        HIP_TRY(launch_copy(b->dev, arena, false, ctx->cfg.copy_chunk_bytes, ctx->cfg.copy_grid_cap, s));
+    }
+    HIP_TRY(launch_mark_done(b->dev, s));
+    b->has_done = true;
+    return TENT_OK;
+}
+
+int tent_poll(tent_ctx* ctx, tent_batch_t batch, uint64_t* remaining, void* stream)
+{
+    if (!ctx || !remaining) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (!b->planned) { *remaining = b->dev.n_slices; return TENT_OK; }
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(launch_count_remaining(b->dev, s));
+    HIP_TRY(hipMemcpyAsync(ctx->host_plan, b->dev.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    *remaining = ctx->host_plan->n_remaining;
+    return TENT_OK;
+}
+
+int tent_reset(tent_ctx* ctx, tent_batch_t batch, void* stream)
+{
+    if (!ctx) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    if (b->planned) HIP_TRY(launch_reset(b->dev, static_cast<hipStream_t>(stream)));
+    b->planned = false;
+    b->has_done = false;
+    return TENT_OK;
+}
+
+int tent_slice_count(tent_ctx* ctx, tent_batch_t batch, uint64_t* n_slices)
+{
+    if (!ctx || !n_slices) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    *n_slices = b->dev.n_slices;
+    return TENT_OK;
+}
+
+int tent_get_plan(tent_ctx* ctx, tent_batch_t batch, tent_slice* host_out, uint64_t cap)
+{
+    if (!ctx || !host_out) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (!b->planned) return TENT_ERR_STATE;
+    const BatchDev& d = b->dev;
+    const uint64_t n = d.n_slices;
+    if (cap < n) return TENT_ERR_RANGE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    HIP_TRY(hipDeviceSynchronize());
+    std::vector<uint32_t> desc, len, rail;
+    std::vector<uint64_t> off, stage;
+    std::vector<uint8_t> state;
+    try {
+        desc.resize(n); len.resize(n); rail.resize(n); off.resize(n); stage.resize(n); state.resize(n);
+    } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
+    HIP_TRY(hipMemcpy(desc.data(), d.s_desc, n * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(len.data(), d.s_len, n * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(rail.data(), d.s_rail, n * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(off.data(), d.s_off, n * 8, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(stage.data(), d.s_stage_off, n * 8, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(state.data(), d.s_state, n, hipMemcpyDeviceToHost));
+    for (uint64_t i = 0; i < n; ++i)
+        host_out[i] = tent_slice{desc[i], len[i], off[i], stage[i], rail[i], state[i]};
+    return TENT_OK;
+}
+
+int tent_get_timings(tent_ctx* ctx, float* ms_out)
+{
+    if (!ctx || !ms_out) return TENT_ERR_INVALID;
+    if (!(ctx->cfg.flags & TENT_FLAG_PROFILE)) return TENT_ERR_STATE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    for (int t = 0; t < TENT_T_COUNT; ++t) {
+        ms_out[t] = 0.0f;
+        if (!ctx->timing[t].used) continue;
+        HIP_TRY(hipEventSynchronize(ctx->timing[t].stop));
+        HIP_TRY(hipEventElapsedTime(&ms_out[t], ctx->timing[t].start, ctx->timing[t].stop));
+    }
+    return TENT_OK;
+}
+
+int tent_release(tent_ctx* ctx, tent_batch_t batch)
+{
+    if (!ctx) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    (void)hipDeviceSynchronize();
+    free_batch(*b);
+    return TENT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+// Internal declarations shared by the engine's translation units (host runtime + HIP kernels).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tent.h"
+
+namespace tent {
+
+// Rail cost coefficients and simulator inputs, passed to kernels by value (kernarg segment),
+// so that a plan needs no host-to-device upload.  Cost of rail d for a slice of L bytes
+// (Eq. 1 of the paper scaled by the topology penalty, in picoseconds):
+//     c0[d] + (((A[d] + L) * c1[d]) >> 16)
+struct RailParams {
+    uint64_t c0[TENT_MAX_RAILS];
+    uint64_t c1[TENT_MAX_RAILS];
+    uint64_t A[TENT_MAX_RAILS];      // queued bytes at the start of the plan
+    uint64_t admitted;               // bit d set: rail d may receive slices
+    uint32_t n_rails;
+    uint32_t pad;
+};
+
+struct BudgetParams {
+    uint64_t queued[TENT_MAX_RAILS];
+    uint64_t budget[TENT_MAX_RAILS];
+};
+
+// Device-resident result block of one plan (read back only when the caller asks for it).
+struct PlanState {
+    uint64_t n_pending;                   // slices considered by the plan
+    uint64_t n_bound;                     // slices bound by the plan
+    uint64_t T[TENT_MAX_RAILS];           // bytes bound per rail
+    uint64_t cnt[TENT_MAX_RAILS];         // slices bound per rail
+    uint64_t A_after[TENT_MAX_RAILS];     // queued bytes after the plan
+    uint64_t base[TENT_MAX_RAILS];        // staging region base of each rail (bytes into the arena)
+    uint64_t n_done;                      // tent_sim_advance: slices that stayed bound
+    uint64_t n_remaining;                 // tent_poll: slices not DONE
+};
+
+// Device view of one batch: descriptor tables, prefix sums and the slice table (SoA).
+struct BatchDev {
+    uint32_t n_desc;
+    uint64_t n_src_ext, n_dst_ext;
+    uint64_t n_slices;
+    uint64_t slice_bytes;
+
+    const uint32_t*    src_ptr;    // [n_desc+1]
+    const uint32_t*    dst_ptr;    // [n_desc+1]
+    const tent_extent* src_ext;    // [n_src_ext]
+    const tent_extent* dst_ext;    // [n_dst_ext]
+    uint64_t* src_pre;             // [n_src_ext+1] exclusive prefix of extent lengths over the whole batch
+    uint64_t* dst_pre;             // [n_dst_ext+1]
+    uint64_t* first;               // [n_desc+1] first slice index of each descriptor
+
+    uint32_t* s_desc;              // [n_slices]
+    uint64_t* s_off;
+    uint32_t* s_len;
+    uint32_t* s_src_e0;            // extent holding the slice's first source byte
+    uint32_t* s_dst_e0;
+    uint32_t* s_rail;
+    uint64_t* s_stage_off;
+    uint8_t*  s_state;
+
+    uint32_t* pending;             // [n_slices] ascending ids of slices not DONE (re-planning)
+    uint64_t* scan_tmp;            // [max(n_ext, n_slices, n_desc)+1] scan workspace
+    uint64_t* scan_partials;       // per-block partial sums of the scans
+    PlanState* plan;               // one result block
+    const uint64_t* seg_base;      // context-wide table of segment base addresses
+};
+
+enum : uint32_t { kScanBlock = 256, kScanItems = 8, kScanTile = kScanBlock * kScanItems };
+
+// ---- launch wrappers (each enqueues on `s` and returns the launch status) -------------------
+hipError_t launch_extent_scan(const tent_extent* ext, uint64_t n_ext, uint64_t* pre, uint64_t* partials,
+                              hipStream_t s);
+hipError_t launch_slice_scan(const BatchDev& b, hipStream_t s);
+hipError_t launch_expand(const BatchDev& b, hipStream_t s);
+hipError_t launch_compact(const BatchDev& b, hipStream_t s);
+hipError_t launch_bind_serial(const BatchDev& b, const RailParams& rp, bool use_pending, hipStream_t s);
+hipError_t launch_copy(const BatchDev& b, uint8_t* arena, bool gather, uint32_t chunk_bytes, uint32_t grid_cap,
+                       hipStream_t s);
+hipError_t launch_mark_done(const BatchDev& b, hipStream_t s);
+hipError_t launch_retire(const BatchDev& b, const BudgetParams& bp, hipStream_t s);
+hipError_t launch_count_remaining(const BatchDev& b, hipStream_t s);
+hipError_t launch_reset(const BatchDev& b, hipStream_t s);
+
+uint64_t scan_partials_capacity(uint64_t n);
+
+}  // namespace tent
