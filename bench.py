@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the slice-spraying hot path on one MI355X.
+
+One step = tent_plan (extent scans, slice scan, slice-table expansion, rail binding) followed by
+tent_execute (gather into per-rail staging, scatter to destination) over one freshly declared
+batch of the KVCache-migration workload; descriptor tables and byte pools are resident in HBM
+before the timed region starts.  Prints ONE JSON line.
+
+  value        read+write GB/s of the whole step: 4 * payload * steps / elapsed
+  roofline     the gather kernel (source pages -> staging): 2 * payload bytes per launch against
+               HBM peak, duration from HIP events recorded on the launch stream inside the timed region
+  cpu_baseline the sequential CPU oracle on a reduced instance of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="kv_migration",
+                    choices=["tiny", "kv_migration", "rl_params", "many_small", "many_small_x6"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--serial-binding", action="store_true")
+    ap.add_argument("--chunk", type=int, default=0, help="copy_chunk_bytes tuning knob (0 = library default)")
+    ap.add_argument("--grid-cap", type=int, default=0, help="copy_grid_cap tuning knob (0 = library default)")
+    return ap.parse_args()
+
+
+def make_workload(name):
+    from paper_2604_00368_amd import workloads as W
+    if name == "many_small_x6":
+        return W.many_small(layers=6)
+    return W.CONFIGS[name]()
+
+
+def cpu_baseline(name):
+    """Time the oracle as it stands on a reduced instance of the workload (host memory only)."""
+    import oracle
+    from paper_2604_00368_amd import workloads as W
+    oracle.build()
+    if name == "kv_migration":
+        w = W.kv_migration(n_req=3)
+        sample = "kv_migration generator with 3 of 32 requests (all 32 layers, 32 KiB pages, 256 KiB slices, 9 rails)"
+    elif name == "rl_params":
+        w = W.rl_params(layers=4)
+        sample = "rl_params generator with 4 of 32 layers plus the embedding (1 MiB slices, 8 rails)"
+    elif name.startswith("many_small"):
+        w = W.many_small()
+        sample = "many_small generator, 4096 requests, one layer (18 KiB pages, 16 KiB slices, 16 rails)"
+    else:
+        w = W.tiny()
+        sample = "tiny config as is"
+    rng = np.random.Generator(np.random.PCG64(99))
+    src = np.frombuffer(rng.bytes(w.seg_bytes[0]), dtype=np.uint8)
+    dst = np.zeros(w.seg_bytes[1], dtype=np.uint8)
+    staging = np.zeros(w.staging_bytes, dtype=np.uint8)
+    dst[::4096] = 1
+    staging[::4096] = 1                        # commit the pages before timing
+    reps = 0
+    t_plan = t_exec = 0.0
+    n_slices = 0
+    t_begin = time.perf_counter()
+    while reps < 1 or (time.perf_counter() - t_begin < 10.0 and reps < 20):
+        t0 = time.perf_counter()
+        s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+        b = oracle.bind(s.len, w.rails)
+        t1 = time.perf_counter()
+        oracle.execute(w, s, b, [src, dst], staging)
+        t2 = time.perf_counter()
+        t_plan += t1 - t0
+        t_exec += t2 - t1
+        n_slices = s.n
+        reps += 1
+    step = (t_plan + t_exec) / reps
+    return {
+        "value": round(4 * w.payload / step / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"{sample}; payload {w.payload / 2**30:.2f} GiB, {n_slices} slices, {reps} repetitions",
+        "plan_slices_per_s": round(n_slices / (t_plan / reps), 1),
+        "execute_GBps": round(4 * w.payload / (t_exec / reps) / 1e9, 3),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: the rails are simulated staging regions in one device's HBM; "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2604_00368_amd import binding as T
+    from paper_2604_00368_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    T.lib()                                            # fails loudly when the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = make_workload(args.workload)
+    src = W.fill_torch(w, 0, dev)
+    dst = torch.zeros(w.seg_bytes[1], dtype=torch.uint8, device=dev)
+    arena = torch.empty(w.staging_bytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev)
+    flags = T.TENT_FLAG_PROFILE | (T.TENT_FLAG_SERIAL_BINDING if args.serial_binding else 0)
+    ctx = T.tent_create(w.slice_bytes, arena.data_ptr(), arena.numel(), flags,
+                        copy_chunk_bytes=args.chunk, copy_grid_cap=args.grid_cap)
+    T.tent_register_segment(ctx, src.data_ptr(), src.numel())
+    T.tent_register_segment(ctx, dst.data_ptr(), dst.numel())
+
+    total = args.warmup + args.steps
+    t0 = time.perf_counter()
+    batches = [T.tent_declare(ctx, w.src_ptr, w.src_ext, w.dst_ptr, w.dst_ext) for _ in range(total)]
+    declare_ms = (time.perf_counter() - t0) * 1e3 / total
+    n_slices = T.tent_slice_count(ctx, batches[0])
+
+    def step(h):
+        T.tent_plan(ctx, h, w.rails, want_info=False, stream=stream)
+        T.tent_execute(ctx, h, stream)
+
+    for h in batches[:args.warmup]:
+        step(h)
+    torch.cuda.synchronize(dev)
+    T.tent_get_timings(ctx)                            # drop warm-up intervals
+
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    for h in batches[args.warmup:]:
+        step(h)
+    torch.cuda.synchronize(dev)
+    elapsed = time.perf_counter() - t0
+
+    tm = T.tent_get_timings(ctx)
+    remaining = T.tent_poll(ctx, batches[-1], stream)
+    assert remaining == 0, remaining
+
+    def avg_ms(*names):
+        return sum(tm[n][0] for n in names) / max(1, args.steps)
+
+    plan_ms = avg_ms("extent_scan", "slice_scan", "expand", "compact", "bind")
+    gather_ms, gather_n = tm["gather"]
+    scatter_ms, scatter_n = tm["scatter"]
+    gather_avg = gather_ms / max(1, gather_n)
+    scatter_avg = scatter_ms / max(1, scatter_n)
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = 4 * w.payload / (ms_per_step * 1e-3) / 1e9
+    achieved = 2 * w.payload / (gather_avg * 1e-3) / 1e9
+
+    out = {
+        "metric": "slice gather/scatter GB/s (read+write bytes, whole plan+execute step)",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": w.name, "payload_bytes": w.payload, "n_desc": w.n_desc,
+                   "n_extents": int(w.src_ext.shape[0]), "n_slices": n_slices, "slice_bytes": w.slice_bytes,
+                   "n_rails": int(w.rails.shape[0]), "binding": "serial" if args.serial_binding else "default"},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "slices_planned_per_s": round(n_slices / (plan_ms * 1e-3), 1) if plan_ms > 0 else None,
+        "stage_ms": {k: round(v[0] / max(1, args.steps), 4) for k, v in tm.items()},
+        "execute_GBps": round(4 * w.payload / ((gather_avg + scatter_avg) * 1e-3) / 1e9, 2),
+        "declare_ms": round(declare_ms, 3),
+        "roofline": {"bound": "hbm", "kernel": "copy_kernel<gather>", "achieved": round(achieved, 2),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": None,
+                     "scatter_achieved": round(2 * w.payload / (scatter_avg * 1e-3) / 1e9, 2)},
+    }
+    T.tent_destroy(ctx)
+    del src, dst, arena
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    main()

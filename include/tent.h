@@ -47,7 +47,7 @@ enum { TENT_MAX_RAILS = 64 };
 /* tent_config.flags */
 enum {
     TENT_FLAG_SKIP_OVERLAP_CHECK = 1u << 0,   /* tent_declare does not test extents for overlap  */
-    TENT_FLAG_PROFILE            = 1u << 1,   /* record HIP events around every kernel (see tent_get_timings) */
+    TENT_FLAG_PROFILE            = 1u << 1,   /* time every stage with HIP events (see tent_get_timings) */
     TENT_FLAG_SERIAL_BINDING     = 1u << 2    /* bind slice by slice on one wavefront instead of run-parallel  */
 };
 
@@ -199,11 +199,12 @@ int tent_slice_count(tent_ctx *ctx, tent_batch_t batch, uint64_t *n_slices);
  * host_out; TENT_ERR_RANGE if too small.  Waits for the device. */
 int tent_get_plan(tent_ctx *ctx, tent_batch_t batch, tent_slice *host_out, uint64_t cap);
 
-/* With TENT_FLAG_PROFILE: milliseconds spent in each stage (TENT_T_*) during the
- * most recent tent_plan / tent_execute on the batch's context; stages that did
- * not run report 0.  Waits for the recorded events.  `ms_out` is host memory
- * with TENT_T_COUNT entries. */
-int tent_get_timings(tent_ctx *ctx, float *ms_out);
+/* With TENT_FLAG_PROFILE every stage (TENT_T_*) of tent_plan / tent_execute is bracketed by a
+ * pair of HIP events on the caller's stream.  This call waits for the recorded events and
+ * returns, per stage, the summed milliseconds and the number of bracketed intervals since
+ * the previous call (0 for stages that did not run), then starts a new accounting period.
+ * `ms_out` and `launches_out` are host memory with TENT_T_COUNT entries each. */
+int tent_get_timings(tent_ctx *ctx, float *ms_out, uint32_t *launches_out);
 
 /* Free the batch's device tables.  Waits for the device. */
 int tent_release(tent_ctx *ctx, tent_batch_t batch);

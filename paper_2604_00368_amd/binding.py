@@ -80,7 +80,7 @@ def lib():
         L.tent_reset.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
         L.tent_slice_count.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64)]
         L.tent_get_plan.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
-        L.tent_get_timings.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
+        L.tent_get_timings.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_uint32)]
         L.tent_release.argtypes = [C.c_void_p, C.c_uint64]
         _lib = L
     return _lib
@@ -179,9 +179,11 @@ def tent_get_plan(ctx, batch: int) -> np.ndarray:
 
 
 def tent_get_timings(ctx) -> dict:
+    """{stage: (total_ms, intervals)} since the previous call."""
     ms = (C.c_float * len(TENT_T_NAMES))()
-    _check(lib().tent_get_timings(ctx, ms), "tent_get_timings")
-    return {k: float(ms[i]) for i, k in enumerate(TENT_T_NAMES)}
+    cnt = (C.c_uint32 * len(TENT_T_NAMES))()
+    _check(lib().tent_get_timings(ctx, ms, cnt), "tent_get_timings")
+    return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(TENT_T_NAMES)}
 
 
 def tent_release(ctx, batch: int):

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "tent_internal.h"
@@ -24,7 +25,11 @@ struct Batch {
     std::vector<void*> allocs;
 };
 
-struct Timing { hipEvent_t start = nullptr, stop = nullptr; bool used = false; };
+// Event pairs recorded around the launches of one stage since the last tent_get_timings.
+struct Timing {
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;   // every pair ever created for the stage
+    size_t used = 0;                                        // pairs recorded since the last read-out
+};
 
 }  // namespace
 
@@ -149,23 +154,31 @@ int check_overlap(const tent_ctx* ctx, uint64_t ns, const tent_extent* se, uint6
     return TENT_OK;
 }
 
+// Brackets the launches of one stage with a pair of HIP events on the caller's stream.
 struct StageTimer {
-    tent_ctx* ctx; int stage; hipStream_t s; bool on;
-    StageTimer(tent_ctx* c, int st, hipStream_t stream) : ctx(c), stage(st), s(stream)
+    hipEvent_t stop = nullptr;
+    hipStream_t s;
+    StageTimer(tent_ctx* c, int stage, hipStream_t stream) : s(stream)
     {
-        on = (c->cfg.flags & TENT_FLAG_PROFILE) != 0;
-        if (on) { (void)hipEventRecord(c->timing[st].start, s); }
+        if (!(c->cfg.flags & TENT_FLAG_PROFILE)) return;
+        Timing& t = c->timing[stage];
+        if (t.used == t.pool.size()) {
+            hipEvent_t a = nullptr, b = nullptr;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+                if (a) (void)hipEventDestroy(a);
+                return;
+            }
+            try { t.pool.emplace_back(a, b); } catch (const std::bad_alloc&) {
+                (void)hipEventDestroy(a); (void)hipEventDestroy(b);
+                return;
+            }
+        }
+        (void)hipEventRecord(t.pool[t.used].first, s);
+        stop = t.pool[t.used].second;
+        ++t.used;
     }
-    ~StageTimer()
-    {
-        if (on) { (void)hipEventRecord(ctx->timing[stage].stop, s); ctx->timing[stage].used = true; }
-    }
+    ~StageTimer() { if (stop) (void)hipEventRecord(stop, s); }
 };
-
-void clear_timings(tent_ctx* ctx, int lo, int hi)
-{
-    for (int t = lo; t <= hi; ++t) ctx->timing[t].used = false;
-}
 
 // Telemetry -> integer coefficients (Eq. 1 with the topology penalty folded in).
 int convert_rails(const tent_rail_state* rails, uint32_t n_rails, uint64_t pending_bytes, RailParams* rp)
@@ -230,14 +243,6 @@ int tent_create(tent_ctx** out, const tent_config* cfg)
         delete ctx;
         return TENT_ERR_NOMEM;
     }
-    if (cfg->flags & TENT_FLAG_PROFILE) {
-        for (Timing& t : ctx->timing) {
-            if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) {
-                tent_destroy(ctx);
-                return TENT_ERR_HIP;
-            }
-        }
-    }
     *out = ctx;
     return TENT_OK;
 }
@@ -248,10 +253,8 @@ int tent_destroy(tent_ctx* ctx)
     DeviceGuard g(ctx->device);
     (void)hipDeviceSynchronize();
     for (Batch& b : ctx->batches) if (b.alive) free_batch(b);
-    for (Timing& t : ctx->timing) {
-        if (t.start) (void)hipEventDestroy(t.start);
-        if (t.stop) (void)hipEventDestroy(t.stop);
-    }
+    for (Timing& t : ctx->timing)
+        for (auto& pr : t.pool) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
     if (ctx->seg_base_dev) (void)hipFree(ctx->seg_base_dev);
     if (ctx->host_plan) (void)hipHostFree(ctx->host_plan);
     delete ctx;
@@ -364,7 +367,6 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BatchDev& d = b->dev;
-    clear_timings(ctx, TENT_T_EXTENT_SCAN, TENT_T_BIND);
 
     const bool replan = b->has_done;
     if (!replan) {
@@ -442,7 +444,6 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* arena = static_cast<uint8_t*>(ctx->cfg.staging_arena);
-    clear_timings(ctx, TENT_T_GATHER, TENT_T_SCATTER);
     {
         StageTimer t(ctx, TENT_T_GATHER, s);
         HIP_TRY(launch_copy(b->dev, arena, true, ctx->cfg.copy_chunk_bytes, ctx->cfg.copy_grid_cap, s));
@@ -523,19 +524,30 @@ int tent_get_plan(tent_ctx* ctx, tent_batch_t batch, tent_slice* host_out, uint6
     return TENT_OK;
 }
 
-int tent_get_timings(tent_ctx* ctx, float* ms_out)
+int tent_get_timings(tent_ctx* ctx, float* ms_out, uint32_t* launches_out)
 {
-    if (!ctx || !ms_out) return TENT_ERR_INVALID;
+    if (!ctx || !ms_out || !launches_out) return TENT_ERR_INVALID;
     if (!(ctx->cfg.flags & TENT_FLAG_PROFILE)) return TENT_ERR_STATE;
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
-    for (int t = 0; t < TENT_T_COUNT; ++t) {
-        ms_out[t] = 0.0f;
-        if (!ctx->timing[t].used) continue;
-        HIP_TRY(hipEventSynchronize(ctx->timing[t].stop));
-        HIP_TRY(hipEventElapsedTime(&ms_out[t], ctx->timing[t].start, ctx->timing[t].stop));
+    int rc = TENT_OK;
+    for (int st = 0; st < TENT_T_COUNT; ++st) {
+        Timing& t = ctx->timing[st];
+        double total = 0.0;
+        for (size_t k = 0; k < t.used; ++k) {
+            float ms = 0.0f;
+            if (hipEventSynchronize(t.pool[k].second) != hipSuccess ||
+                hipEventElapsedTime(&ms, t.pool[k].first, t.pool[k].second) != hipSuccess) {
+                (void)hipGetLastError();
+                rc = TENT_ERR_HIP;
+            }
+            total += ms;
+        }
+        ms_out[st] = (float)total;
+        launches_out[st] = (uint32_t)t.used;
+        t.used = 0;
     }
-    return TENT_OK;
+    return rc;
 }
 
 int tent_release(tent_ctx* ctx, tent_batch_t batch)
