@@ -33,8 +33,6 @@ def parse():
                     choices=["tiny", "kv_migration", "rl_params", "many_small", "many_small_x6"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial-binding", action="store_true")
-    ap.add_argument("--chunk", type=int, default=0, help="copy_chunk_bytes tuning knob (0 = library default)")
-    ap.add_argument("--grid-cap", type=int, default=0, help="copy_grid_cap tuning knob (0 = library default)")
     return ap.parse_args()
 
 
@@ -114,8 +112,7 @@ def main():
     arena = torch.empty(w.staging_bytes, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream(dev)
     flags = T.TENT_FLAG_PROFILE | (T.TENT_FLAG_SERIAL_BINDING if args.serial_binding else 0)
-    ctx = T.tent_create(w.slice_bytes, arena.data_ptr(), arena.numel(), flags,
-                        copy_chunk_bytes=args.chunk, copy_grid_cap=args.grid_cap)
+    ctx = T.tent_create(w.slice_bytes, arena.data_ptr(), arena.numel(), flags)
     T.tent_register_segment(ctx, src.data_ptr(), src.numel())
     T.tent_register_segment(ctx, dst.data_ptr(), dst.numel())
 

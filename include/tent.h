@@ -52,13 +52,11 @@ enum {
 };
 
 typedef struct {
-    uint64_t slice_bytes;      /* S > 0: fixed slice size (Section 4.2, "Slice Decomposition")    */
+    uint64_t slice_bytes;      /* S in [1, 2^31]: fixed slice size (Section 4.2, "Slice Decomposition") */
     void    *staging_arena;    /* device: per-rail staging regions are carved from this           */
     uint64_t staging_bytes;    /* capacity of the arena                                           */
     uint32_t flags;
-    uint32_t copy_chunk_bytes; /* tuning, 0 = default: bytes of one slice that one workgroup moves  */
-    uint32_t copy_grid_cap;    /* tuning, 0 = default: upper bound on workgroups per copy launch    */
-    uint32_t reserved;
+    uint32_t reserved;         /* must be 0                                                       */
 } tent_config;
 
 /* One contiguous byte range of a registered segment (Section 3.1: a segment is a

@@ -1,60 +1,48 @@
 // Gather / scatter of slice bytes between paged extents and per-rail staging regions.
 //
 // Gather: slice bytes are read from the transfer's source extents (the paged side) and written
-// contiguously at arena + base[rail] + stage_off (the staging hop of Section 4.1 of the paper).
+// contiguously at the slice's staging address (the staging hop of Section 4.1 of the paper).
 // Scatter: the same bytes are read back from staging and written to the destination extents at
 // the slice's absolute offset inside the transfer (direct-to-offset writes, Section 4.4), so the
 // result does not depend on the order in which slices are moved.
 //
-// Work decomposition: a work item is (slice, chunk) with chunk_bytes of the slice; one 256-lane
-// workgroup walks the extents that intersect its chunk and copies each intersection ("piece")
-// cooperatively.  When the two addresses and the length of a piece are multiples of 16 the piece
-// moves as 16-byte-per-lane vectors, kUnroll loads in flight per lane before the first store;
-// otherwise head/tail bytes are peeled when both sides share their alignment, and fully
-// misaligned pieces move byte by byte.  All per-item bookkeeping is uniform across the workgroup.
+// Work decomposition: one 256-lane workgroup per 4 KiB block of a slice, one 16-byte vector per
+// lane, and the workgroup ends after its store.  Consecutive workgroups touch consecutive staging
+// addresses, so the set of DRAM pages open at any time stays small; on MI355X this one-shot shape
+// sustains more bandwidth than persistent workgroups that loop over larger chunks.  The paged-side
+// address comes from the tile table built by the splitter (one 8-byte entry per tile of 1-4 KiB),
+// looked up per lane, so extent boundaries inside a block cost nothing as long as they fall on
+// tile boundaries.  A block that holds a flagged tile (extent boundary inside the tile, or an
+// address that is not 16-byte aligned), a misaligned staging address or a ragged tail takes the
+// generic path, which walks the extent list and peels unaligned bytes.
+#include <cstdlib>
+
 #include "tent_internal.h"
 
 namespace tent {
 
 typedef uint32_t vec4u __attribute__((ext_vector_type(4)));
 
-constexpr int kCopyBlock = 256;
-constexpr int kUnroll = 8;
-
-__device__ __forceinline__ void copy_vectors(vec4u* __restrict__ dst, const vec4u* __restrict__ src, uint64_t nvec)
-{
-    for (uint64_t base = 0; base < nvec; base += (uint64_t)kCopyBlock * kUnroll) {
-        vec4u r[kUnroll];
-#pragma unroll
-        for (int k = 0; k < kUnroll; ++k) {
-            const uint64_t idx = base + (uint64_t)k * kCopyBlock + threadIdx.x;
-            if (idx < nvec) r[k] = __builtin_nontemporal_load(src + idx);
-        }
-#pragma unroll
-        for (int k = 0; k < kUnroll; ++k) {
-            const uint64_t idx = base + (uint64_t)k * kCopyBlock + threadIdx.x;
-            if (idx < nvec) __builtin_nontemporal_store(r[k], dst + idx);
-        }
-    }
-}
-
+// Wavefront-cooperative byte copy (64 lanes).
 __device__ __forceinline__ void copy_bytes(uint8_t* __restrict__ dst, const uint8_t* __restrict__ src, uint64_t n)
 {
-    for (uint64_t x = threadIdx.x; x < n; x += kCopyBlock) dst[x] = src[x];
+    for (uint64_t x = threadIdx.x & 63; x < n; x += 64) dst[x] = src[x];
 }
 
+// Wavefront-cooperative copy of n bytes, any alignment.
 __device__ __forceinline__ void copy_piece(uint8_t* dst, const uint8_t* src, uint64_t n)
 {
     const uint64_t d = (uint64_t)dst, s = (uint64_t)src;
-    if (((d | s | n) & 15) == 0) {
-        copy_vectors((vec4u*)dst, (const vec4u*)src, n >> 4);
-    } else if (((d ^ s) & 15) == 0) {
+    if (((d ^ s) & 15) == 0) {
         uint64_t head = (16 - (d & 15)) & 15;
         if (head > n) head = n;
         copy_bytes(dst, src, head);
-        const uint64_t body = (n - head) & ~15ull;
-        copy_vectors((vec4u*)(dst + head), (const vec4u*)(src + head), body >> 4);
-        copy_bytes(dst + head + body, src + head + body, n - head - body);
+        const uint64_t nvec = (n - head) >> 4;
+        vec4u* dv = (vec4u*)(dst + head);
+        const vec4u* sv = (const vec4u*)(src + head);
+        for (uint64_t v = threadIdx.x & 63; v < nvec; v += 64) dv[v] = sv[v];
+        const uint64_t done = head + (nvec << 4);
+        copy_bytes(dst + done, src + done, n - done);
     } else {
         copy_bytes(dst, src, n);
     }
@@ -69,69 +57,101 @@ __device__ __forceinline__ uint32_t last_not_above32(const uint64_t* a, uint32_t
     return lo;
 }
 
+// Generic path for one wavefront: bytes [lo, hi) of slice i, walking the extents that intersect the range.
 template <bool kGather>
-__global__ void __launch_bounds__(kCopyBlock) copy_kernel(BatchDev b, uint8_t* arena, uint32_t chunk_bytes,
-                                                          uint32_t chunks_per_slice)
+__device__ __forceinline__ void copy_range_generic(const BatchDev& b, uint64_t i, uint64_t lo, uint64_t hi, uint8_t* linear)
 {
-    const uint64_t items = b.n_slices * chunks_per_slice;
     const uint32_t*    ptr = kGather ? b.src_ptr : b.dst_ptr;
     const tent_extent* ext = kGather ? b.src_ext : b.dst_ext;
     const uint64_t*    pre = kGather ? b.src_pre : b.dst_pre;
-    const uint32_t*    e0s = kGather ? b.s_src_e0 : b.s_dst_e0;
-
-    for (uint64_t item = blockIdx.x; item < items; item += gridDim.x) {
-        const uint64_t i = item / chunks_per_slice;
-        const uint32_t c = (uint32_t)(item - i * chunks_per_slice);
-        if (b.s_state[i] != TENT_SLICE_BOUND) continue;
-        const uint32_t len = b.s_len[i];
-        const uint64_t lo = (uint64_t)c * chunk_bytes;
-        if (lo >= len) continue;
-        const uint64_t hi = lo + chunk_bytes < len ? lo + chunk_bytes : len;
-
-        const uint32_t j = b.s_desc[i];
-        const uint32_t e_lo = ptr[j], e_hi = ptr[j + 1];
-        uint64_t pos = pre[e_lo] + b.s_off[i] + lo;          // position in the batch-wide extent prefix
-        const uint64_t end = pos + (hi - lo);
-        uint8_t* linear = arena + b.plan->base[b.s_rail[i]] + b.s_stage_off[i] + lo;
-        uint32_t e = last_not_above32(pre, e0s[i], e_hi, pos);
-        while (pos < end) {
-            const uint64_t e_end = pre[e + 1];
-            const uint64_t n = (e_end < end ? e_end : end) - pos;
-            const tent_extent x = ext[e];
-            uint8_t* paged = (uint8_t*)(b.seg_base[x.seg] + x.off + (pos - pre[e]));
-            if (kGather) copy_piece(linear, paged, n); else copy_piece(paged, linear, n);
-            linear += n;
-            pos += n;
-            ++e;
-        }
+    const uint32_t     e0  = kGather ? b.s_src_e0[i] : b.s_dst_e0[i];
+    const uint32_t j = b.s_desc[i];
+    const uint32_t e_lo = ptr[j], e_hi = ptr[j + 1];
+    uint64_t pos = pre[e_lo] + b.s_off[i] + lo;              // position in the batch-wide extent prefix
+    const uint64_t end = pos + (hi - lo);
+    uint32_t e = last_not_above32(pre, e0, e_hi, pos);
+    while (pos < end) {
+        const uint64_t e_end = pre[e + 1];
+        const uint64_t n = (e_end < end ? e_end : end) - pos;
+        const tent_extent x = ext[e];
+        uint8_t* paged = (uint8_t*)(b.seg_base[x.seg] + x.off + (pos - pre[e]));
+        if (kGather) copy_piece(linear, paged, n); else copy_piece(paged, linear, n);
+        linear += n;
+        pos += n;
+        ++e;
     }
 }
 
-static void copy_geometry(const BatchDev& b, uint32_t chunk_bytes, uint32_t grid_cap,
-                          uint32_t* chunk, uint32_t* cps, uint32_t* grid)
+// One workgroup moves kLanes*16 bytes of one slice; every wavefront is independent of the others
+// (no barrier): it moves 1 KiB with one 16-byte vector per lane.  The slice record (scalar load)
+// and the tile entry (one load per lane) are fetched together before the first branch, so a
+// wavefront sees two memory round trips before its data load: kernel arguments, then metadata.
+template <bool kGather, int kLanes>
+__global__ void __launch_bounds__(kLanes) copy_kernel(const SliceRec* __restrict__ rec, const uint64_t* __restrict__ tab,
+                                                      uint64_t n_slices, uint32_t bps, uint32_t bps_shift,
+                                                      uint32_t tiles_per_slice, uint32_t tile_shift,
+                                                      const BatchDev* __restrict__ batch)
 {
-    uint64_t cb = chunk_bytes ? chunk_bytes : 64u * 1024u;
-    if (cb > b.slice_bytes) cb = b.slice_bytes;
-    if (cb > 0xFFFFFFFFull) cb = 0x80000000ull;
-    uint64_t per = (b.slice_bytes + cb - 1) / cb;
-    uint64_t items = b.n_slices * per;
-    uint64_t cap = grid_cap ? grid_cap : 0x7FFFFFFFull;
-    *chunk = (uint32_t)cb;
-    *cps = (uint32_t)per;
-    *grid = (uint32_t)(items < cap ? items : cap);
+    constexpr uint32_t kBlockBytes = kLanes * 16;
+    const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    const uint64_t i = bps_shift != 0xFFFFFFFFu ? (w >> bps_shift)
+                       : (w >> 32) == 0 ? (uint64_t)((uint32_t)w / bps) : w / bps;
+    if (i >= n_slices) return;
+    const uint32_t c = (uint32_t)(w - i * bps);
+    const uint32_t x = c * kBlockBytes + threadIdx.x * 16;   // this lane's byte offset inside the slice
+    uint32_t t = x >> tile_shift;
+    if (t >= tiles_per_slice) t = tiles_per_slice - 1;
+    const uint64_t entry = tab[i * tiles_per_slice + t];
+    const SliceRec r = rec[i];
+    const bool in_range = x + 16 <= r.len;
+    const bool ragged = x < r.len && !in_range;              // slice ends inside this lane's vector
+    const bool bad = ragged || (x < r.len && ((entry & kTileSlow) || (r.lin & 15)));
+    if (__any(bad)) {
+        const uint32_t wave_lo = c * kBlockBytes + (threadIdx.x & ~63u) * 16;
+        const uint32_t wave_hi = wave_lo + 1024 < r.len ? wave_lo + 1024 : r.len;
+        copy_range_generic<kGather>(*batch, i, wave_lo, wave_hi, (uint8_t*)(r.lin + wave_lo));
+        return;
+    }
+    if (!in_range) return;
+    const uint64_t paged = entry + (x & ((1u << tile_shift) - 1));
+    const uint64_t mine = r.lin + x;
+    if (kGather) {
+        vec4u v = __builtin_nontemporal_load((const vec4u*)paged);
+        __builtin_nontemporal_store(v, (vec4u*)mine);
+    } else {
+        vec4u v = __builtin_nontemporal_load((const vec4u*)mine);
+        __builtin_nontemporal_store(v, (vec4u*)paged);
+    }
 }
 
-hipError_t launch_copy(const BatchDev& b, uint8_t* arena, bool gather, uint32_t chunk_bytes, uint32_t grid_cap,
-                       hipStream_t s)
+template <bool kGather, int kLanes>
+static hipError_t launch_copy_lanes(const BatchDev& b, hipStream_t s)
 {
-    uint32_t chunk, cps, grid;
-    copy_geometry(b, chunk_bytes, grid_cap, &chunk, &cps, &grid);
-    if (grid == 0) return hipSuccess;
-    if (gather)
-        hipLaunchKernelGGL(copy_kernel<true>, dim3(grid), dim3(kCopyBlock), 0, s, b, arena, chunk, cps);
-    else
-        hipLaunchKernelGGL(copy_kernel<false>, dim3(grid), dim3(kCopyBlock), 0, s, b, arena, chunk, cps);
+    const uint32_t block_bytes = kLanes * 16;
+    const uint32_t bps = (uint32_t)((b.slice_bytes + block_bytes - 1) / block_bytes);
+    uint32_t bps_shift = 0xFFFFFFFFu;
+    if ((bps & (bps - 1)) == 0) { bps_shift = 0; while ((1u << bps_shift) < bps) ++bps_shift; }
+    uint32_t tile_shift = 0;
+    while ((1u << tile_shift) < b.tile_bytes) ++tile_shift;
+    const uint64_t blocks = b.n_slices * (uint64_t)bps;
+    if (blocks == 0) return hipSuccess;
+    // 2-D grid so that the block count is not capped by the 1-D limit
+    const uint32_t gx = blocks < 65536 ? (uint32_t)blocks : 65536u;
+    const uint64_t gy = (blocks + gx - 1) / gx;
+    if (gy > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((copy_kernel<kGather, kLanes>), dim3(gx, (uint32_t)gy), dim3(kLanes), 0, s,
+                       b.s_rec, kGather ? b.src_tile : b.dst_tile, b.n_slices, bps, bps_shift,
+                       b.tiles_per_slice, tile_shift, b.self);
     return hipGetLastError();
+}
+
+hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s)
+{
+    static int lanes = getenv("TENT_DEV_LANES") ? atoi(getenv("TENT_DEV_LANES")) : 256;
+    if (lanes == 64) return gather ? launch_copy_lanes<true, 64>(b, s) : launch_copy_lanes<false, 64>(b, s);
+    if (lanes == 128) return gather ? launch_copy_lanes<true, 128>(b, s) : launch_copy_lanes<false, 128>(b, s);
+    if (lanes == 512) return gather ? launch_copy_lanes<true, 512>(b, s) : launch_copy_lanes<false, 512>(b, s);
+    return gather ? launch_copy_lanes<true, 256>(b, s) : launch_copy_lanes<false, 256>(b, s);
 }
 
 }  // namespace tent

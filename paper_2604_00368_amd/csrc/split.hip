@@ -80,6 +80,72 @@ hipError_t launch_expand(const BatchDev& b, hipStream_t s)
     return hipGetLastError();
 }
 
+// ---- S3b: tile tables ------------------------------------------------------------------------
+// One thread per (slice, tile): locate the extent that holds the tile's first byte and store the
+// tile's device address, so that the copy kernels reach their bytes with one table load.
+__global__ void __launch_bounds__(256) tile_table_kernel(BatchDev b)
+{
+    const uint64_t n = b.n_slices * (uint64_t)b.tiles_per_slice;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < n; q += stride) {
+        const uint64_t i = q / b.tiles_per_slice;
+        const uint64_t x = (q - i * b.tiles_per_slice) * b.tile_bytes;      // byte offset inside the slice
+        const uint32_t len = b.s_len[i];
+        if (x >= len) { b.src_tile[q] = kTileSlow; b.dst_tile[q] = kTileSlow; continue; }
+        const uint64_t n_tile = len - x < b.tile_bytes ? len - x : b.tile_bytes;
+        const uint32_t j = b.s_desc[i];
+        {
+            const uint32_t hi = b.src_ptr[j + 1];
+            const uint64_t pos = b.src_pre[b.src_ptr[j]] + b.s_off[i] + x;
+            const uint32_t e = (uint32_t)last_not_above(b.src_pre, b.s_src_e0[i], hi, pos);
+            const tent_extent ex = b.src_ext[e];
+            const uint64_t addr = b.seg_base[ex.seg] + ex.off + (pos - b.src_pre[e]);
+            const bool slow = (pos + n_tile > b.src_pre[e + 1]) || (addr & 15);
+            b.src_tile[q] = addr | (slow ? kTileSlow : 0);
+        }
+        {
+            const uint32_t hi = b.dst_ptr[j + 1];
+            const uint64_t pos = b.dst_pre[b.dst_ptr[j]] + b.s_off[i] + x;
+            const uint32_t e = (uint32_t)last_not_above(b.dst_pre, b.s_dst_e0[i], hi, pos);
+            const tent_extent ex = b.dst_ext[e];
+            const uint64_t addr = b.seg_base[ex.seg] + ex.off + (pos - b.dst_pre[e]);
+            const bool slow = (pos + n_tile > b.dst_pre[e + 1]) || (addr & 15);
+            b.dst_tile[q] = addr | (slow ? kTileSlow : 0);
+        }
+    }
+}
+
+hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s)
+{
+    uint64_t blocks = (b.n_slices * (uint64_t)b.tiles_per_slice + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(tile_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    return hipGetLastError();
+}
+
+// Copy records: staging address (arena + region base of the rail + offset inside the region) and
+// length of every BOUND slice; slices in any other state get length 0 and are skipped by the copy.
+__global__ void __launch_bounds__(256) finalize_kernel(BatchDev b, uint8_t* arena)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slices; i += stride) {
+        SliceRec r{0, 0, 0};
+        if (b.s_state[i] == TENT_SLICE_BOUND) {
+            r.lin = (uint64_t)arena + b.plan->base[b.s_rail[i]] + b.s_stage_off[i];
+            r.len = b.s_len[i];
+        }
+        b.s_rec[i] = r;
+    }
+}
+
+hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s)
+{
+    uint64_t blocks = (b.n_slices + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(finalize_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, arena);
+    return hipGetLastError();
+}
+
 // ---- E1: ascending list of slices that are not DONE -----------------------------------------
 struct NotDone {
     const uint8_t* state;

@@ -97,11 +97,11 @@ struct Interval { uint64_t lo, hi; uint32_t seg; uint32_t is_dst; };
 // Walk both extent lists of every transfer: structure, bounds, equal lengths.  Also returns
 // the payload and the number of slices the device splitter will produce.
 int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const tent_extent* se,
-             const uint32_t* dp, const tent_extent* de, uint64_t* payload, uint64_t* n_slices)
+             const uint32_t* dp, const tent_extent* de, uint64_t* payload, uint64_t* n_slices, uint64_t* len_bits)
 {
     if (sp[0] != 0 || dp[0] != 0) return TENT_ERR_INVALID;
     const uint64_t S = ctx->cfg.slice_bytes;
-    uint64_t total = 0, slices = 0;
+    uint64_t total = 0, slices = 0, bits = 0;
     for (uint32_t j = 0; j < n_desc; ++j) {
         if (sp[j + 1] <= sp[j] || dp[j + 1] <= dp[j]) return TENT_ERR_INVALID;   // empty or non-monotone
         uint64_t ls = 0, ld = 0;
@@ -111,6 +111,7 @@ int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const ten
             const uint64_t seg_len = ctx->segments[x.seg].len;
             if (x.off > seg_len || x.len > seg_len - x.off) return TENT_ERR_INVALID;
             ls += x.len;
+            bits |= x.len;
         }
         for (uint32_t e = dp[j]; e < dp[j + 1]; ++e) {
             const tent_extent& x = de[e];
@@ -118,6 +119,7 @@ int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const ten
             const uint64_t seg_len = ctx->segments[x.seg].len;
             if (x.off > seg_len || x.len > seg_len - x.off) return TENT_ERR_INVALID;
             ld += x.len;
+            bits |= x.len;
         }
         if (ls != ld) return TENT_ERR_INVALID;
         total += ls;
@@ -125,6 +127,7 @@ int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const ten
     }
     *payload = total;
     *n_slices = slices;
+    *len_bits = bits;
     return TENT_OK;
 }
 
@@ -229,7 +232,7 @@ int tent_create(tent_ctx** out, const tent_config* cfg)
 {
     if (!out || !cfg) return TENT_ERR_INVALID;
     *out = nullptr;
-    if (cfg->slice_bytes == 0 || cfg->slice_bytes > 0xFFFFFFFFull) return TENT_ERR_INVALID;
+    if (cfg->slice_bytes == 0 || cfg->slice_bytes > 0x80000000ull) return TENT_ERR_INVALID;
     if (!cfg->staging_arena || cfg->staging_bytes == 0) return TENT_ERR_INVALID;
     tent_ctx* ctx = new (std::nothrow) tent_ctx;
     if (!ctx) return TENT_ERR_NOMEM;
@@ -280,8 +283,8 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
 {
     if (!ctx || !src_ptr || !src_ext || !dst_ptr || !dst_ext || !out || n_desc == 0) return TENT_ERR_INVALID;
     *out = 0;
-    uint64_t payload = 0, n_slices = 0;
-    int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, &payload, &n_slices);
+    uint64_t payload = 0, n_slices = 0, len_bits = 0;
+    int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, &payload, &n_slices, &len_bits);
     if (rc != TENT_OK) return rc;
     if (n_slices >= 0xFFFFFFFEull) return TENT_ERR_RANGE;
     const uint64_t ns = src_ptr[n_desc], nd = dst_ptr[n_desc];
@@ -310,6 +313,16 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     d.n_slices = n_slices;
     d.slice_bytes = ctx->cfg.slice_bytes;
     d.seg_base = ctx->seg_base_dev;
+    // Tile size: the largest power of two in [1 KiB, 4 KiB] that divides the slice size and every
+    // extent length, so that no tile crosses an extent boundary; geometry that allows no such size
+    // gets 1 KiB tiles, and the tiles that do cross a boundary take the generic copy path.
+    {
+        const uint64_t bits = len_bits | d.slice_bytes | kCopyBlockBytes;
+        uint32_t tile = (uint32_t)(bits & (~bits + 1));
+        d.tile_bytes = tile < 1024 ? 1024 : tile;
+        d.tiles_per_slice = (uint32_t)((d.slice_bytes + d.tile_bytes - 1) / d.tile_bytes);
+    }
+    const uint64_t n_tiles = n_slices * d.tiles_per_slice;
 
     uint32_t *sp = nullptr, *dp = nullptr;
     tent_extent *se = nullptr, *de = nullptr;
@@ -329,17 +342,24 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_rail, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_stage_off, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_state, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_rec, n_slices);
+    BatchDev* self_dev = nullptr;
+    if (rc == TENT_OK) rc = dev_alloc(b, &self_dev, 1);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.src_tile, n_tiles);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.dst_tile, n_tiles);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.pending, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_tmp, scan_n + 1);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_partials, scan_partials_capacity(scan_n));
     if (rc == TENT_OK) rc = dev_alloc(b, &d.plan, 1);
     if (rc != TENT_OK) { free_batch(b); return rc; }
     d.src_ptr = sp; d.dst_ptr = dp; d.src_ext = se; d.dst_ext = de;
+    d.self = self_dev;
 
     if (hipMemcpy(sp, src_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(dp, dst_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(se, src_ext, sizeof(tent_extent) * ns, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(de, dst_ext, sizeof(tent_extent) * nd, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(self_dev, &d, sizeof(BatchDev), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemset(d.plan, 0, sizeof(PlanState)) != hipSuccess) {
         (void)hipGetLastError();
         free_batch(b);
@@ -382,6 +402,7 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
         {
             StageTimer t(ctx, TENT_T_EXPAND, s);
             HIP_TRY(launch_expand(d, s));
+            HIP_TRY(launch_tile_tables(d, s));
         }
     } else {
         StageTimer t(ctx, TENT_T_COMPACT, s);
@@ -443,14 +464,14 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    uint8_t* arena = static_cast<uint8_t*>(ctx->cfg.staging_arena);
+    HIP_TRY(launch_finalize(b->dev, static_cast<uint8_t*>(ctx->cfg.staging_arena), s));
     {
         StageTimer t(ctx, TENT_T_GATHER, s);
-        HIP_TRY(launch_copy(b->dev, arena, true, ctx->cfg.copy_chunk_bytes, ctx->cfg.copy_grid_cap, s));
+        HIP_TRY(launch_copy(b->dev, true, s));
     }
     {
         StageTimer t(ctx, TENT_T_SCATTER, s);
-        HIP_TRY(launch_copy(b->dev, arena, false, ctx->cfg.copy_chunk_bytes, ctx->cfg.copy_grid_cap, s));
+        HIP_TRY(launch_copy(b->dev, false, s));
     }
     HIP_TRY(launch_mark_done(b->dev, s));
     b->has_done = true;

@@ -38,6 +38,13 @@ struct PlanState {
     uint64_t n_remaining;                 // tent_poll: slices not DONE
 };
 
+// What a copy workgroup needs to know about its slice, in one 16-byte scalar load.
+struct SliceRec {
+    uint64_t lin;                  // staging address of the slice's first byte
+    uint32_t len;                  // bytes to move; 0 when the slice is not BOUND
+    uint32_t pad;
+};
+
 // Device view of one batch: descriptor tables, prefix sums and the slice table (SoA).
 struct BatchDev {
     uint32_t n_desc;
@@ -62,6 +69,17 @@ struct BatchDev {
     uint64_t* s_stage_off;
     uint8_t*  s_state;
 
+    struct SliceRec* s_rec;        // packed copy record per slice, rebuilt by every tent_execute
+    const BatchDev* self;          // device copy of this structure (generic copy path)
+
+    // Tile tables: for every slice, tiles_per_slice entries per side; entry t holds the device
+    // address of byte t*tile_bytes of the slice on the paged side.  Bit 63 marks a tile that
+    // needs the generic path (it crosses an extent boundary or is not 16-byte aligned).
+    uint64_t* src_tile;            // [n_slices * tiles_per_slice]
+    uint64_t* dst_tile;
+    uint32_t  tile_bytes;          // 1 KiB, 2 KiB or 4 KiB
+    uint32_t  tiles_per_slice;
+
     uint32_t* pending;             // [n_slices] ascending ids of slices not DONE (re-planning)
     uint64_t* scan_tmp;            // [max(n_ext, n_slices, n_desc)+1] scan workspace
     uint64_t* scan_partials;       // per-block partial sums of the scans
@@ -70,6 +88,8 @@ struct BatchDev {
 };
 
 enum : uint32_t { kScanBlock = 256, kScanItems = 8, kScanTile = kScanBlock * kScanItems };
+enum : uint32_t { kCopyBlockBytes = 4096 };          // bytes one copy workgroup moves (256 lanes x 16 B)
+constexpr uint64_t kTileSlow = 1ull << 63;
 
 // ---- launch wrappers (each enqueues on `s` and returns the launch status) -------------------
 hipError_t launch_extent_scan(const tent_extent* ext, uint64_t n_ext, uint64_t* pre, uint64_t* partials,
@@ -78,8 +98,9 @@ hipError_t launch_slice_scan(const BatchDev& b, hipStream_t s);
 hipError_t launch_expand(const BatchDev& b, hipStream_t s);
 hipError_t launch_compact(const BatchDev& b, hipStream_t s);
 hipError_t launch_bind_serial(const BatchDev& b, const RailParams& rp, bool use_pending, hipStream_t s);
-hipError_t launch_copy(const BatchDev& b, uint8_t* arena, bool gather, uint32_t chunk_bytes, uint32_t grid_cap,
-                       hipStream_t s);
+hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
+hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s);
+hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s);
 hipError_t launch_mark_done(const BatchDev& b, hipStream_t s);
 hipError_t launch_retire(const BatchDev& b, const BudgetParams& bp, hipStream_t s);
 hipError_t launch_count_remaining(const BatchDev& b, hipStream_t s);

@@ -11,7 +11,7 @@ from paper_2604_00368_amd import workloads as W
 class Engine:
     """Device pools + one engine context for one workload (torch only provides memory and the stream)."""
 
-    def __init__(self, w, src_host=None, dst_host=None, flags=0, device="cuda:0", **tuning):
+    def __init__(self, w, src_host=None, dst_host=None, flags=0, device="cuda:0"):
         self.w = w
         self.dev = torch.device(device)
         torch.cuda.set_device(self.dev)
@@ -25,7 +25,7 @@ class Engine:
             self.dst = torch.zeros(w.seg_bytes[1], dtype=torch.uint8, device=self.dev)
         self.arena = torch.zeros(w.staging_bytes, dtype=torch.uint8, device=self.dev)
         self.stream = torch.cuda.current_stream(self.dev)
-        self.ctx = T.tent_create(w.slice_bytes, self.arena.data_ptr(), self.arena.numel(), flags, **tuning)
+        self.ctx = T.tent_create(w.slice_bytes, self.arena.data_ptr(), self.arena.numel(), flags)
         s0 = T.tent_register_segment(self.ctx, self.src.data_ptr(), self.src.numel())
         s1 = T.tent_register_segment(self.ctx, self.dst.data_ptr(), self.dst.numel())
         assert (s0, s1) == (W.SRC_SEG, W.DST_SEG)

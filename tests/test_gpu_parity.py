@@ -17,7 +17,7 @@ def H():
     return gpu_harness
 
 
-def run_and_compare(H, oracle, w, flags=0, **tuning):
+def run_and_compare(H, oracle, w, flags=0):
     src = W.fill_numpy(w, 0)
     dst0 = W.fill_numpy(w, 1)
     s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
@@ -25,7 +25,7 @@ def run_and_compare(H, oracle, w, flags=0, **tuning):
     dst_want = dst0.copy()
     staging_want = np.zeros(w.staging_bytes, dtype=np.uint8)
     oracle.execute(w, s, b, [src, dst_want], staging_want)
-    with H.Engine(w, src, dst0, flags=flags, **tuning) as eng:
+    with H.Engine(w, src, dst0, flags=flags) as eng:
         eng.declare()
         st, info = eng.plan()
         assert st == 0
@@ -52,9 +52,11 @@ def test_ragged_bit_exact(H, oracle, seed):
     run_and_compare(H, oracle, W.ragged(seed, slice_bytes=S, n_desc=12, max_len=40_000, max_ext=900, align=align))
 
 
-@pytest.mark.parametrize("chunk,cap", [(4096, 0), (65536, 7), (1 << 20, 300)])
-def test_launch_geometry_does_not_change_results(H, oracle, chunk, cap):
-    print("geometry", chunk, cap, flush=True)
-    run_and_compare(H, oracle, W.small_variant("kv_migration"), copy_chunk_bytes=chunk, copy_grid_cap=cap)
-    run_and_compare(H, oracle, W.ragged(42, slice_bytes=70_001, n_desc=6, max_len=300_000, max_ext=5000),
-                    copy_chunk_bytes=chunk, copy_grid_cap=cap)
+@pytest.mark.parametrize("S", [1024, 3072, 4096, 6144, 8192 + 2048, 65536 + 1024])
+def test_tile_sizes_and_partial_blocks(H, oracle, S):
+    # slice sizes that give 1 KiB / 2 KiB / 4 KiB tiles, partial last blocks and extent boundaries inside blocks
+    print("tile case S", S, flush=True)
+    w = W.ragged(7, slice_bytes=S, n_desc=10, max_len=300_000, max_ext=20_000, align=1024)
+    run_and_compare(H, oracle, w)
+    w = W.many_small(n_req=24, layers=2, slice_bytes=S)
+    run_and_compare(H, oracle, w)
