@@ -56,7 +56,7 @@ typedef struct {
     void    *staging_arena;    /* device: per-rail staging regions are carved from this           */
     uint64_t staging_bytes;    /* capacity of the arena                                           */
     uint32_t flags;
-    uint32_t reserved;         /* must be 0                                                       */
+    uint32_t max_rails;        /* most rails a plan may name, 0 = TENT_MAX_RAILS (sizes per-batch tables) */
 } tent_config;
 
 /* One contiguous byte range of a registered segment (Section 3.1: a segment is a
@@ -155,7 +155,7 @@ int tent_declare(tent_ctx *ctx, uint32_t n_desc,
  * NULL; when it is non-NULL the call waits for the stream and fills it, when it
  * is NULL the call only enqueues work on `stream`.
  * Returns TENT_DEFER (and binds nothing) when every rail is excluded;
- * TENT_ERR_RANGE when bw_MBps = 0, c1_d >= 2^32, (max A_d + pending bytes) *
+ * TENT_ERR_RANGE when n_rails exceeds the context's max_rails, bw_MBps = 0, c1_d >= 2^32, (max A_d + pending bytes) *
  * max c1_d >= 2^63, or the arena is smaller than pending bytes + 256*n_rails.
  */
 int tent_plan(tent_ctx *ctx, tent_batch_t batch, const tent_rail_state *rails, uint32_t n_rails,

@@ -30,7 +30,7 @@ EXPORTS = ["tent_create", "tent_destroy", "tent_register_segment", "tent_declare
 
 class tent_config(C.Structure):
     _fields_ = [("slice_bytes", C.c_uint64), ("staging_arena", C.c_void_p), ("staging_bytes", C.c_uint64),
-                ("flags", C.c_uint32), ("reserved", C.c_uint32)]
+                ("flags", C.c_uint32), ("max_rails", C.c_uint32)]
 
 
 class tent_plan_info(C.Structure):
@@ -106,8 +106,8 @@ def tent_strerror(status: int) -> str:
     return lib().tent_strerror(int(status)).decode()
 
 
-def tent_create(slice_bytes: int, staging_arena_ptr: int, staging_bytes: int, flags: int = 0):
-    cfg = tent_config(slice_bytes, staging_arena_ptr, staging_bytes, flags, 0)
+def tent_create(slice_bytes: int, staging_arena_ptr: int, staging_bytes: int, flags: int = 0, max_rails: int = 0):
+    cfg = tent_config(slice_bytes, staging_arena_ptr, staging_bytes, flags, max_rails)
     ctx = C.c_void_p()
     _check(lib().tent_create(C.byref(ctx), C.byref(cfg)), "tent_create")
     return ctx

@@ -36,6 +36,7 @@ struct Timing {
 struct tent_ctx {
     int device = 0;
     tent_config cfg{};
+    uint32_t max_rails = TENT_MAX_RAILS;
     std::vector<Segment> segments;
     uint64_t* seg_base_dev = nullptr;       // device table of segment base addresses
     uint32_t seg_capacity = 0;
@@ -234,9 +235,11 @@ int tent_create(tent_ctx** out, const tent_config* cfg)
     *out = nullptr;
     if (cfg->slice_bytes == 0 || cfg->slice_bytes > 0x80000000ull) return TENT_ERR_INVALID;
     if (!cfg->staging_arena || cfg->staging_bytes == 0) return TENT_ERR_INVALID;
+    if (cfg->max_rails > TENT_MAX_RAILS) return TENT_ERR_RANGE;
     tent_ctx* ctx = new (std::nothrow) tent_ctx;
     if (!ctx) return TENT_ERR_NOMEM;
     ctx->cfg = *cfg;
+    ctx->max_rails = cfg->max_rails ? cfg->max_rails : TENT_MAX_RAILS;
     if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return TENT_ERR_HIP; }
     ctx->seg_capacity = kMaxSegments;
     if (hipMalloc((void**)&ctx->seg_base_dev, sizeof(uint64_t) * ctx->seg_capacity) != hipSuccess ||
@@ -286,7 +289,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     uint64_t payload = 0, n_slices = 0, len_bits = 0;
     int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, &payload, &n_slices, &len_bits);
     if (rc != TENT_OK) return rc;
-    if (n_slices >= 0xFFFFFFFEull) return TENT_ERR_RANGE;
+    if (n_slices >= 0xFFFFFFFEull || n_desc >= 0x7FFFFFFFu) return TENT_ERR_RANGE;
     const uint64_t ns = src_ptr[n_desc], nd = dst_ptr[n_desc];
     if (!(ctx->cfg.flags & TENT_FLAG_SKIP_OVERLAP_CHECK)) {
         rc = check_overlap(ctx, ns, src_ext, nd, dst_ext);
@@ -347,6 +350,11 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc == TENT_OK) rc = dev_alloc(b, &self_dev, 1);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.src_tile, n_tiles);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.dst_tile, n_tiles);
+    d.run_capacity = 2u * n_desc;
+    d.run_stride = ctx->max_rails;
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.run_start, (uint64_t)d.run_capacity + 1);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.run_T, (uint64_t)d.run_capacity * d.run_stride);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.run_K, (uint64_t)d.run_capacity * d.run_stride);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.pending, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_tmp, scan_n + 1);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_partials, scan_partials_capacity(scan_n));
@@ -376,7 +384,7 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     if (!ctx || !rails) return TENT_ERR_INVALID;
     Batch* b = find_batch(ctx, batch);
     if (!b) return TENT_ERR_INVALID;
-    if (n_rails == 0 || n_rails > TENT_MAX_RAILS) return TENT_ERR_RANGE;
+    if (n_rails == 0 || n_rails > ctx->max_rails) return TENT_ERR_RANGE;
     RailParams rp;
     int rc = convert_rails(rails, n_rails, b->payload, &rp);
     if (rc != TENT_OK) return rc;
@@ -410,7 +418,13 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     }
     {
         StageTimer t(ctx, TENT_T_BIND, s);
-        HIP_TRY(launch_bind_serial(d, rp, replan, s));
+        // the run-parallel chain divides by c1, so a rail whose cost does not grow with bytes
+        // (c1 = 0) sends the plan down the slice-by-slice kernel
+        bool serial = (ctx->cfg.flags & TENT_FLAG_SERIAL_BINDING) != 0;
+        for (uint32_t r = 0; r < n_rails; ++r)
+            if (((rp.admitted >> r) & 1) && rp.c1[r] == 0) serial = true;
+        if (serial) HIP_TRY(launch_bind_serial(d, rp, replan, s));
+        else        HIP_TRY(launch_bind_runs(d, rp, replan, s));
     }
     b->planned = true;
     b->last_rails = rp;

@@ -34,6 +34,7 @@ struct PlanState {
     uint64_t cnt[TENT_MAX_RAILS];         // slices bound per rail
     uint64_t A_after[TENT_MAX_RAILS];     // queued bytes after the plan
     uint64_t base[TENT_MAX_RAILS];        // staging region base of each rail (bytes into the arena)
+    uint64_t n_runs;                      // runs of equal-length slices seen by the plan
     uint64_t n_done;                      // tent_sim_advance: slices that stayed bound
     uint64_t n_remaining;                 // tent_poll: slices not DONE
 };
@@ -80,6 +81,13 @@ struct BatchDev {
     uint32_t  tile_bytes;          // 1 KiB, 2 KiB or 4 KiB
     uint32_t  tiles_per_slice;
 
+    // Run-parallel binding: maximal runs of equal-length pending slices (at most two per transfer)
+    uint32_t* run_start;           // [run_capacity + 1] first pending position of every run
+    uint64_t* run_T;               // [run_capacity * run_stride] bytes bound per rail before the run
+    uint32_t* run_K;               // [run_capacity * run_stride] slots each rail takes in the run
+    uint32_t  run_capacity;        // 2 * n_desc
+    uint32_t  run_stride;          // rails per row
+
     uint32_t* pending;             // [n_slices] ascending ids of slices not DONE (re-planning)
     uint64_t* scan_tmp;            // [max(n_ext, n_slices, n_desc)+1] scan workspace
     uint64_t* scan_partials;       // per-block partial sums of the scans
@@ -98,6 +106,7 @@ hipError_t launch_slice_scan(const BatchDev& b, hipStream_t s);
 hipError_t launch_expand(const BatchDev& b, hipStream_t s);
 hipError_t launch_compact(const BatchDev& b, hipStream_t s);
 hipError_t launch_bind_serial(const BatchDev& b, const RailParams& rp, bool use_pending, hipStream_t s);
+hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, bool use_pending, hipStream_t s);
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
 hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s);
 hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s);
