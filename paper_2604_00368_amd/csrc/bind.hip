@@ -16,8 +16,9 @@ namespace tent {
 template <int kCtrl>
 __device__ __forceinline__ uint64_t dpp_move64(uint64_t v)
 {
-    int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, kCtrl, 0xF, 0xF, false);
-    int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), kCtrl, 0xF, 0xF, false);
+    // every control used below gives each lane a valid source lane, so no fill value is needed
+    int lo = __builtin_amdgcn_mov_dpp((int)(uint32_t)v, kCtrl, 0xF, 0xF, true);
+    int hi = __builtin_amdgcn_mov_dpp((int)(uint32_t)(v >> 32), kCtrl, 0xF, 0xF, true);
     return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo;
 }
 

@@ -31,7 +31,8 @@ constexpr uint64_t kCostCap = 1ull << 47;  // every feasible (X * c1) >> 16 is b
 template <int kCtrl>
 __device__ __forceinline__ uint32_t dpp32(uint32_t v)
 {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kCtrl, 0xF, 0xF, false);
+    // every control used below gives each lane a valid source lane, so no fill value is needed
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, kCtrl, 0xF, 0xF, true);
 }
 template <int kCtrl>
 __device__ __forceinline__ uint64_t dpp64(uint64_t v)
@@ -89,7 +90,9 @@ __device__ __forceinline__ uint64_t div_exact(uint64_t a, uint32_t b, double inv
     if (a >> 50) return a / b;
     uint64_t q = (uint64_t)((double)a * inv);
     int64_t r = (int64_t)(a - q * b);
+#pragma clang loop unroll(disable)
     while (r < 0) { --q; r += b; }
+#pragma clang loop unroll(disable)
     while (r >= (int64_t)b) { ++q; r -= b; }
     return q;
 }
@@ -101,9 +104,12 @@ struct Rail {
     double inv_c1;
 };
 
-__device__ __forceinline__ uint64_t slot_cost(const Rail& r, uint64_t A, uint32_t l, uint64_t k)
+// Cost of the rail's slot k (0-based) of a run of l-byte slices when A bytes are already queued.
+// k + 1 <= 2^32 - 1 because a batch holds fewer than 2^32 - 1 slices.
+__device__ __forceinline__ uint64_t slot_cost(const Rail& r, uint64_t A, uint32_t l, uint32_t k)
 {
-    return r.c0 + (((A + (k + 1) * l) * (uint64_t)r.c1) >> 16);
+    const uint64_t x = A + (uint64_t)(k + 1u) * l;
+    return r.c0 + ((x * (uint64_t)r.c1) >> 16);
 }
 
 // #{k >= 0 : slot_cost(k) <= v}, clamped to m.  v may be negative.
@@ -158,20 +164,56 @@ __global__ void __launch_bounds__(256) run_table_kernel(BatchDev b, int use_pend
 __global__ void set_pending_all_kernel(BatchDev b) { b.plan->n_pending = b.n_slices; }
 
 // ---- step 2: chain over runs ------------------------------------------------------------------
+// Same value as slots_upto, reached from a floating-point estimate that is then checked against
+// the integer cost of the neighbouring slots; falls back to the closed form when the estimate
+// cannot be trusted to be within a few slots.
+__device__ __forceinline__ uint32_t slots_upto_fast(const Rail& r, uint64_t A, uint32_t l, double inv_l, int64_t v, uint32_t m)
+{
+    if (v < 0 || (uint64_t)v < r.c0) return 0;
+    const uint64_t w1 = (uint64_t)v - r.c0 + 1;
+    if ((w1 >> 36) || (A >> 52)) return slots_upto(r, A, l, inv_l, v, m);
+    const double x = (double)(w1 << 16) * r.inv_c1;            // bytes the rail may hold at cost v
+    double kf = (x - (double)A) * inv_l;
+    kf = kf < 0.0 ? 0.0 : (kf > (double)m ? (double)m : kf);
+    uint32_t k = (uint32_t)kf;
+    // the estimate is almost always exact: two cost evaluations confirm it
+    const bool low = k < m && slot_cost(r, A, l, k) <= (uint64_t)v;
+    const bool high = k > 0 && slot_cost(r, A, l, k - 1) > (uint64_t)v;
+    if (low) {
+        ++k;
+#pragma clang loop unroll(disable)
+        while (k < m && slot_cost(r, A, l, k) <= (uint64_t)v) ++k;
+    } else if (high) {
+        --k;
+#pragma clang loop unroll(disable)
+        while (k > 0 && slot_cost(r, A, l, k - 1) > (uint64_t)v) --k;
+    }
+    return k;
+}
+
 __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams rp, int use_pending)
 {
     const int lane = threadIdx.x;
     const uint32_t R = rp.n_rails;
     const bool live = lane < (int)R && ((rp.admitted >> lane) & 1);
+    const uint64_t live_mask = __ballot(live);
+    const double n_live = (double)__popcll(live_mask);
     Rail rail;
     rail.c0 = rp.c0[lane];
     rail.c1 = live ? (uint32_t)rp.c1[lane] : 1u;
     rail.inv_c1 = 1.0 / (double)rail.c1;
     const double G = live ? 65536.0 * rail.inv_c1 : 0.0;      // bytes the rail absorbs per picosecond
     const double g = (double)rail.c0 * G;                     // its fixed latency expressed in bytes
+    const double inv_S = 1.0 / (double)b.slice_bytes;
     uint64_t A = rp.A[lane], T = 0, cnt = 0;
     const uint64_t n_runs = b.plan->n_runs;
     const uint32_t stride = b.run_stride;
+
+    // Water-filling model: once every admitted rail has received a slot, all of them sit at the
+    // common cost level, and level(bytes) = (bytes + sum_d(g_d + A_d)) / sum_d G_d needs no
+    // cross-lane work: the second sum grows by exactly the bytes bound.
+    bool all_proven = false;
+    double pool_G = 0.0, pool_B = 0.0, inv_pool_G = 0.0;
 
     // run descriptors are fetched 64 at a time, one per lane, the next block prefetched
     uint32_t nx_start = 0, nx_m = 0, nx_len = 0, nx_id = 0;
@@ -208,39 +250,58 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
                 k = lane == win;
             } else {
                 if (lane < (int)R) b.run_T[row + lane] = T;
-                const double inv_l = 1.0 / (double)l;
+                const double inv_l = l == b.slice_bytes ? inv_S : 1.0 / (double)l;
                 uint32_t taken = 0;
                 if (m > (uint32_t)kTol) {
-                    // bracket: slots_upto(lo) sums below m, slots_upto(hi) sums to at least m
-                    const uint64_t head = live ? slot_cost(rail, A, l, 0) : ~0ull;
-                    int64_t lo = (int64_t)uniform64(wave_reduce64(head, R, OpMin{})) - 1;
-                    const uint64_t alone = live ? slot_cost(rail, A, l, m - 1) : ~0ull;
-                    int64_t hi = (int64_t)uniform64(wave_reduce64(alone, R, OpMin{}));
-                    // water-filling guess over the rails that are below the level
-                    bool wet = live;
-                    double v = 0.0;
-                    for (int pass = 0; pass < 64; ++pass) {
-                        const uint64_t wet_mask = __ballot(wet);
-                        const double sumG = wave_sum_f64(wet ? G : 0.0, R);
-                        const double sumB = wave_sum_f64(wet ? g + (double)A : 0.0, R);
-                        const double need = ((double)m + 0.5 * (double)__popcll(wet_mask)) * (double)l;
-                        v = __longlong_as_double((long long)uniform64((uint64_t)__double_as_longlong((need + sumB) / sumG)));
-                        const bool still = wet && (double)head <= v;
-                        const uint64_t still_mask = __ballot(still);
-                        if (still_mask == wet_mask || still_mask == 0) break;
-                        wet = still;
+                    double v;
+                    if (all_proven) {
+                        v = (((double)m + 0.5 * n_live) * (double)l + pool_B) * inv_pool_G;
+                    } else {
+                        // rails whose next slot already costs more than the level stay out of the pool
+                        const uint64_t head = live ? slot_cost(rail, A, l, 0) : ~0ull;
+                        bool wet = live;
+                        v = 0.0;
+                        for (int pass = 0; pass < 64; ++pass) {
+                            const uint64_t wet_mask = __ballot(wet);
+                            const double sumG = wave_sum_f64(wet ? G : 0.0, R);
+                            const double sumB = wave_sum_f64(wet ? g + (double)A : 0.0, R);
+                            const double need = ((double)m + 0.5 * (double)__popcll(wet_mask)) * (double)l;
+                            v = __longlong_as_double((long long)uniform64((uint64_t)__double_as_longlong((need + sumB) / sumG)));
+                            const bool still = wet && (cnt > 0 || (double)head <= v);
+                            const uint64_t still_mask = __ballot(still);
+                            if (still_mask == wet_mask || still_mask == 0) break;
+                            wet = still;
+                        }
                     }
+                    // bracket (computed only if the first guess misses):
+                    // slots summed over rails stay below m at `lo` and reach at least m at `hi`
+                    bool bracketed = false;
+                    int64_t lo = 0, hi = 0;
                     for (int iter = 0;; ++iter) {
                         int64_t vi = (v >= 0.0 && v < 9.0e18) ? (int64_t)v : -1;
-                        if (iter >= 8 || vi <= lo || vi >= hi) {       // guess unusable: bisect
+                        if (!bracketed && vi < 0) {
+                            const uint64_t head = live ? slot_cost(rail, A, l, 0) : ~0ull;
+                            const uint64_t alone = live ? slot_cost(rail, A, l, m - 1) : ~0ull;
+                            lo = (int64_t)uniform64(wave_reduce64(head, R, OpMin{})) - 1;
+                            hi = (int64_t)uniform64(wave_reduce64(alone, R, OpMin{}));
+                            bracketed = true;
+                        }
+                        if (bracketed && (iter >= 8 || vi <= lo || vi >= hi)) {   // guess unusable: bisect
                             vi = lo + (hi - lo) / 2;
                             if (vi <= lo) vi = hi;
                         }
-                        const uint32_t kk = live ? slots_upto(rail, A, l, inv_l, vi, m) : 0;
+                        const uint32_t kk = live ? slots_upto_fast(rail, A, l, inv_l, vi, m) : 0;
                         const uint64_t tt = uniform64(wave_reduce64(kk, R, OpAdd{}));
                         const int64_t miss = (int64_t)m - (int64_t)tt;
                         if (miss <= kTol && miss >= -kTol) { k = kk; taken = (uint32_t)tt; break; }
-                        if (miss > 0) lo = vi; else hi = vi;
+                        if (!bracketed) {
+                            const uint64_t head = live ? slot_cost(rail, A, l, 0) : ~0ull;
+                            const uint64_t alone = live ? slot_cost(rail, A, l, m - 1) : ~0ull;
+                            lo = (int64_t)uniform64(wave_reduce64(head, R, OpMin{})) - 1;
+                            hi = (int64_t)uniform64(wave_reduce64(alone, R, OpMin{}));
+                            bracketed = true;
+                        }
+                        if (miss > 0) { if (vi > lo) lo = vi; } else { if (vi < hi) hi = vi; }
                         if (hi - lo == 1) {
                             // the whole deficit sits at cost `hi`: hand it out in rail order
                             const uint32_t k_lo = live ? slots_upto(rail, A, l, inv_l, lo, m) : 0;
@@ -259,7 +320,7 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
                             taken = m;
                             break;
                         }
-                        const bool near = live && (kk > 0 || (int64_t)head <= vi + 1);
+                        const bool near = live && (kk > 0 || slot_cost(rail, A, l, 0) <= (uint64_t)(vi < 0 ? 0 : vi) + 1);
                         double rate = wave_sum_f64(near ? G : 0.0, R);
                         if (!(rate > 0.0)) rate = wave_sum_f64(G, R);
                         v = __longlong_as_double((long long)uniform64(
@@ -285,6 +346,16 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
             A += bytes;
             T += bytes;
             cnt += k;
+            if (all_proven) {
+                pool_B += (double)m * (double)l;
+            } else if (__ballot(live && cnt > 0) == live_mask) {
+                all_proven = true;
+                pool_G = wave_sum_f64(G, R);
+                pool_B = wave_sum_f64(live ? g + (double)A : 0.0, R);
+                pool_G = __longlong_as_double((long long)uniform64((uint64_t)__double_as_longlong(pool_G)));
+                pool_B = __longlong_as_double((long long)uniform64((uint64_t)__double_as_longlong(pool_B)));
+                inv_pool_G = 1.0 / pool_G;
+            }
         }
     }
 
