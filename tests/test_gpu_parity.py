@@ -119,3 +119,149 @@ def test_run_parallel_binding_matches_oracle(H, oracle, kind):
             st, info = eng.plan()
             assert st == 0
             H.assert_plan_equal(eng.table(), s, b, info)
+
+
+def run_epochs_and_compare(H, oracle, w, flags=0):
+    from paper_2604_00368_amd import binding as T
+    src = W.fill_numpy(w, 0)
+    dst0 = W.fill_numpy(w, 1)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    dst_want = dst0.copy()
+    staging_want = np.zeros(w.staging_bytes, dtype=np.uint8)
+    records, left = oracle.run_epochs(w, s, [src, dst_want], staging_want)
+    assert left.shape[0] == 0
+    with H.Engine(w, src, dst0, flags=flags) as eng:
+        eng.declare()
+        done_so_far = np.zeros(s.n, dtype=bool)
+        for e, (rec, ep) in enumerate(zip(records, list(w.epochs) + [w.drain])):
+            print("epoch", e, "pending", rec["pending"].shape[0], flush=True)
+            st, info = eng.plan(rails=ep.rails)
+            assert st == rec["status"] == 0
+            assert info.n_slices == rec["pending"].shape[0] == info.n_pending_before
+            tab = eng.table()
+            pend = rec["pending"]
+            assert np.array_equal(np.nonzero(tab["state"] != 2)[0], pend)           # pending set
+            if rec["rail"] is not None:
+                assert np.array_equal(tab["rail"][pend], rec["rail"])
+                assert np.array_equal(tab["stage_off"][pend], rec["stage_off"])
+            if rec["T"] is not None:
+                R = ep.rails.shape[0]
+                assert list(info.rail_bytes)[:R] == rec["T"].tolist()
+                assert list(info.stage_base)[:R] == rec["base"].tolist()
+            n_done = T.tent_sim_advance(eng.ctx, eng.batch, ep.budget, eng.stream)
+            assert n_done == rec["done_ids"].shape[0]
+            tab = eng.table()
+            assert np.array_equal(np.nonzero(tab["state"] == 1)[0], rec["done_ids"])  # done set of the epoch
+            eng.execute()
+            done_so_far[rec["done_ids"]] = True
+            assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == int((~done_so_far).sum())
+        assert done_so_far.all()
+        assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+        assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+
+
+def test_replanning_epochs_bit_exact(H, oracle):
+    from paper_2604_00368_amd import binding as T
+    run_epochs_and_compare(H, oracle, W.small_variant("replanning"))
+    run_epochs_and_compare(H, oracle, W.small_variant("replanning"), flags=T.TENT_FLAG_SERIAL_BINDING)
+
+
+def test_replanning_many_small_shape(H, oracle):
+    # re-planning over a workload whose slices straddle pages and whose pending runs are short
+    w = W.many_small(n_req=48, layers=2)
+    kv = W.replanning(n_req=4, layers=2, ctx_lo=200, ctx_hi=900, queued_hi=64 * 1024)
+    R = w.rails.shape[0]
+    rng = np.random.Generator(np.random.PCG64(77))
+    t_us = -(-w.payload // int(6 * int(w.rails["bw_MBps"].astype(np.uint64).sum())))
+    epochs = []
+    for e in range(8):
+        bw = np.maximum(1, np.rint(w.rails["bw_MBps"] * np.exp(0.5 * rng.standard_normal(R)))).astype(np.uint64)
+        health = np.zeros(R, dtype=np.uint8)
+        if e >= 2:
+            health[5] = 2
+        if e >= 4:
+            health[0] = 2
+        rails = W.make_rails(bw, queued=rng.integers(0, 64 * 1024, size=R), health=health)
+        epochs.append(W.Epoch(rails, bw * np.uint64(t_us)))
+    w.epochs = epochs
+    w.drain = W.Epoch(epochs[-1].rails.copy(), np.full(R, np.iinfo(np.uint64).max, dtype=np.uint64))
+    run_epochs_and_compare(H, oracle, w)
+
+
+def test_defer_errors_and_reuse(H, oracle):
+    from paper_2604_00368_amd import binding as T
+    w = W.tiny()
+    src = W.fill_numpy(w, 0)
+    dst0 = np.zeros(w.seg_bytes[1], dtype=np.uint8)
+    with H.Engine(w, src, dst0) as eng:
+        h = eng.declare()
+        # execute before plan
+        with pytest.raises(T.TentError) as ei:
+            T.tent_execute(eng.ctx, h, eng.stream)
+        assert ei.value.status == T.TENT_ERR_STATE
+        # every rail excluded: deferred, nothing bound, batch still usable
+        rails = w.rails.copy()
+        rails["health"] = 2
+        st, info = eng.plan(rails=rails)
+        assert st == T.TENT_DEFER
+        assert T.tent_poll(eng.ctx, h, eng.stream) == T.tent_slice_count(eng.ctx, h)
+        # range errors
+        bad = w.rails.copy(); bad["bw_MBps"][0] = 0
+        with pytest.raises(T.TentError) as ei:
+            eng.plan(rails=bad)
+        assert ei.value.status == T.TENT_ERR_RANGE
+        bad = w.rails.copy(); bad["queued_bytes"][0] = 1 << 62
+        with pytest.raises(T.TentError) as ei:
+            eng.plan(rails=bad)
+        assert ei.value.status == T.TENT_ERR_RANGE
+        with pytest.raises(T.TentError) as ei:
+            T.tent_plan(eng.ctx, h, np.zeros(65, dtype=W.RAIL_DTYPE), True, eng.stream)
+        assert ei.value.status == T.TENT_ERR_RANGE
+        # malformed declarations
+        def declare(sp, se, dp, de):
+            return T.tent_declare(eng.ctx, sp, se, dp, de)
+        se = w.src_ext.copy(); se["len"][3] = 0
+        with pytest.raises(T.TentError) as ei:
+            declare(w.src_ptr, se, w.dst_ptr, w.dst_ext)
+        assert ei.value.status == T.TENT_ERR_INVALID
+        se = w.src_ext.copy(); se["off"][3] = w.seg_bytes[0] - 10
+        with pytest.raises(T.TentError):
+            declare(w.src_ptr, se, w.dst_ptr, w.dst_ext)
+        se = w.src_ext.copy(); se["len"][0] += 16                                   # source longer than destination
+        with pytest.raises(T.TentError):
+            declare(w.src_ptr, se, w.dst_ptr, w.dst_ext)
+        de = w.dst_ext.copy(); de["off"][1] = de["off"][0] + 100                    # overlapping destinations
+        with pytest.raises(T.TentError):
+            declare(w.src_ptr, w.src_ext, w.dst_ptr, de)
+        de = w.dst_ext.copy(); de["seg"][:] = 0                                     # destination on top of sources
+        with pytest.raises(T.TentError):
+            declare(w.src_ptr, w.src_ext, w.dst_ptr, de)
+        sp = w.src_ptr.copy(); sp[5] = sp[4]                                        # empty transfer
+        with pytest.raises(T.TentError):
+            declare(sp, w.src_ext, w.dst_ptr, w.dst_ext)
+        with pytest.raises(T.TentError):
+            T.tent_execute(eng.ctx, 12345, eng.stream)                             # unknown handle
+        # the batch still plans and executes correctly after all of that; reset + second pass is idempotent
+        s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+        b = oracle.bind(s.len, w.rails)
+        want = dst0.copy()
+        staging = np.zeros(w.staging_bytes, dtype=np.uint8)
+        oracle.execute(w, s, b, [src, want], staging)
+        for _ in range(2):
+            st, info = eng.plan()
+            assert st == 0
+            H.assert_plan_equal(eng.table(), s, b, info)
+            eng.execute()
+            assert T.tent_poll(eng.ctx, h, eng.stream) == 0
+            assert np.array_equal(eng.dst.cpu().numpy(), want)
+            T.tent_reset(eng.ctx, h, eng.stream)
+        # plan after completion without reset binds nothing
+        st, info = eng.plan(); eng.execute()
+        st, info = eng.plan()
+        assert info.n_slices == 0 and info.n_pending_before == 0
+        # release, then the handle is dead and its slot is reused with a new generation
+        T.tent_release(eng.ctx, h)
+        with pytest.raises(T.TentError):
+            T.tent_slice_count(eng.ctx, h)
+        h2 = eng.declare()
+        assert h2 != h and T.tent_slice_count(eng.ctx, h2) == s.n
