@@ -202,13 +202,17 @@ def rl_params(seed: int = 3, layers: int = 32, hidden: int = 4096, ffn: int = 14
 # Config 4: congestion / failure re-planning over telemetry epochs
 # --------------------------------------------------------------------------
 def replanning(seed: int = 4, n_epochs: int = 16, fail_at=((5, 3), (11, 6)),
-               queued_hi: int = 64 * MiB, **kv_kwargs) -> Workload:
+               queued_hi: int = 64 * MiB, epoch_share: int = 16, **kv_kwargs) -> Workload:
+    """KV migration replayed over telemetry epochs.  Every epoch lasts t_us, the time the nominal
+    rails need for 1/epoch_share of the payload; rail d drains bw_d * t_us bytes per epoch, so the
+    transfer spans all epochs (both rail failures happen while slices are still pending) and a final
+    drain pass with unlimited budget finishes what is left."""
     kv_kwargs.setdefault("seed", 2)
     w = kv_migration(**kv_kwargs)
     rng = np.random.Generator(np.random.PCG64(seed))
     nominal = w.rails["bw_MBps"].astype(np.float64)
     R = nominal.shape[0]
-    t_us = -(-w.payload // int(12 * int(w.rails["bw_MBps"].astype(np.uint64).sum())))
+    t_us = -(-w.payload // int(epoch_share * int(w.rails["bw_MBps"].astype(np.uint64).sum())))
     epochs = []
     health = np.zeros(R, dtype=np.uint8)
     for e in range(n_epochs):

@@ -1,0 +1,145 @@
+"""Full-size GPU parity on the benchmark's launch configuration.
+
+The plan (slice table, rails, staging offsets, per-rail totals) is compared with the CPU oracle in
+full.  Bytes are compared two ways: (1) for a sample of transfers the oracle moves the bytes on the
+host (source extents fetched from the device pool) and every destination and staging byte of those
+transfers must match; (2) for every transfer, DST_j[x] == SRC_j[x] is checked on the device with
+plain torch indexing (the definition of the result, independent of slices and rails).
+"""
+import gc
+
+import numpy as np
+import pytest
+
+from paper_2604_00368_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_harness
+    return gpu_harness
+
+
+def device_definition_check(w, src, dst, chunk_extents=1 << 15):
+    """DST_j[x] == SRC_j[x] for all j, x, when source and destination extents pair up one to one."""
+    assert np.array_equal(w.src_ptr, w.dst_ptr) and np.array_equal(w.src_ext["len"], w.dst_ext["len"])
+    lens = np.unique(w.src_ext["len"])
+    if lens.shape[0] == 1:                       # uniform pages: gather both sides as rows
+        page = int(lens[0])
+        assert (w.src_ext["off"] % page == 0).all() and (w.dst_ext["off"] % page == 0).all()
+        sv, dv = src.view(-1, page), dst.view(-1, page)
+        for lo in range(0, w.src_ext.shape[0], chunk_extents):
+            si = torch.from_numpy((w.src_ext["off"][lo:lo + chunk_extents] // page).astype(np.int64)).to(src.device)
+            di = torch.from_numpy((w.dst_ext["off"][lo:lo + chunk_extents] // page).astype(np.int64)).to(src.device)
+            assert torch.equal(sv[si], dv[di]), f"extent chunk at {lo}"
+    else:                                        # few large extents: compare slice by slice
+        for se, de in zip(w.src_ext, w.dst_ext):
+            a = src[int(se["off"]):int(se["off"]) + int(se["len"])]
+            b = dst[int(de["off"]):int(de["off"]) + int(de["len"])]
+            assert torch.equal(a, b)
+
+
+def sampled_bytes_check(oracle, w, s, b, eng, sample, ids_filter=None):
+    """Oracle moves the sampled transfers on the host; device bytes of those transfers must match."""
+    src_h = np.zeros(w.seg_bytes[0], dtype=np.uint8)          # untouched pages are never committed
+    dst_h = np.zeros(w.seg_bytes[1], dtype=np.uint8)
+    stg_h = np.zeros(w.staging_bytes, dtype=np.uint8)
+    for j in sample:
+        for e in w.src_ext[w.src_ptr[j]:w.src_ptr[j + 1]]:
+            o, n = int(e["off"]), int(e["len"])
+            src_h[o:o + n] = eng.src[o:o + n].cpu().numpy()
+    ids = np.concatenate([np.arange(s.first[j], s.first[j + 1], dtype=np.uint32) for j in sample])
+    oracle.execute(w, s, b, [src_h, dst_h], stg_h, ids=np.ascontiguousarray(ids))
+    for j in sample:
+        for e in w.dst_ext[w.dst_ptr[j]:w.dst_ptr[j + 1]]:
+            o, n = int(e["off"]), int(e["len"])
+            assert np.array_equal(eng.dst[o:o + n].cpu().numpy(), dst_h[o:o + n]), (j, o)
+    for i in ids:
+        o, n = int(b.base[b.rail[i]] + b.stage_off[i]), int(s.len[i])
+        assert np.array_equal(eng.arena[o:o + n].cpu().numpy(), stg_h[o:o + n]), ("staging", int(i))
+
+
+def pick_sample(w, k, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    D = w.n_desc
+    ext_count = np.diff(w.src_ptr.astype(np.int64))
+    small = np.nonzero(ext_count <= 600)[0]
+    picks = set(rng.choice(small, size=min(k, small.shape[0]), replace=False).tolist())
+    picks.update([0, D - 1])
+    return sorted(picks)
+
+
+def full_config(name):
+    if name == "many_small_x6":
+        return W.many_small(layers=6)
+    return W.CONFIGS[name]()
+
+
+@pytest.mark.parametrize("name", ["kv_migration", "rl_params", "many_small", "many_small_x6"])
+def test_full_size_config(H, oracle, name):
+    from paper_2604_00368_amd import binding as T
+    print("full-size", name, flush=True)
+    w = full_config(name)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    b = oracle.bind(s.len, w.rails)
+    eng = H.Engine(w, flags=T.TENT_FLAG_PROFILE)             # pools filled on the device, as in bench.py
+    try:
+        eng.declare()
+        st, _ = eng.plan(want_info=False)
+        assert st == 0
+        eng.execute()
+        print("  executed", s.n, "slices", flush=True)
+        H.assert_plan_equal(eng.table(), s, b)
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        device_definition_check(w, eng.src, eng.dst)
+        print("  definition check done", flush=True)
+        if name == "rl_params":
+            sample = [1, 6, 2, 3, w.n_desc - 1]               # norms (8 KiB) and 8-32 MiB projections
+        else:
+            sample = pick_sample(w, 12, seed=len(name))
+        sampled_bytes_check(oracle, w, s, b, eng, sample)
+    finally:
+        eng.close()
+        del eng
+        gc.collect()
+        torch.cuda.empty_cache()
+
+
+def test_full_size_replanning(H, oracle):
+    from paper_2604_00368_amd import binding as T
+    print("full-size replanning", flush=True)
+    w = W.replanning()
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    records, left = oracle.run_epochs(w, s)                   # plan and retire only: no host byte pools
+    assert left.shape[0] == 0
+    eng = H.Engine(w, flags=T.TENT_FLAG_PROFILE)
+    try:
+        eng.declare()
+        for e, (rec, ep) in enumerate(zip(records, list(w.epochs) + [w.drain])):
+            st, info = eng.plan(rails=ep.rails)
+            assert st == 0 and info.n_slices == rec["pending"].shape[0]
+            tab = eng.table()
+            pend = rec["pending"]
+            assert np.array_equal(np.nonzero(tab["state"] != 2)[0], pend)
+            if rec["rail"] is not None:
+                assert np.array_equal(tab["rail"][pend], rec["rail"])
+                assert np.array_equal(tab["stage_off"][pend], rec["stage_off"])
+                R = ep.rails.shape[0]
+                assert list(info.rail_bytes)[:R] == rec["T"].tolist()
+            n_done = T.tent_sim_advance(eng.ctx, eng.batch, ep.budget, eng.stream)
+            assert n_done == rec["done_ids"].shape[0]
+            eng.execute()
+            print("  epoch", e, "pending", pend.shape[0], "done", n_done, flush=True)
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        device_definition_check(w, eng.src, eng.dst)
+    finally:
+        eng.close()
+        del eng
+        gc.collect()
+        torch.cuda.empty_cache()
