@@ -7,8 +7,9 @@ batch of the KVCache-migration workload; descriptor tables and byte pools are re
 before the timed region starts.  Prints ONE JSON line.
 
   value        read+write GB/s of the whole step: 4 * payload * steps / elapsed
-  roofline     the gather kernel (source pages -> staging): 2 * payload bytes per launch against
-               HBM peak, duration from HIP events recorded on the launch stream inside the timed region
+  roofline     the slower of the two copy kernels (gather: source pages -> staging, scatter: staging ->
+               destination): 2 * payload bytes per launch against HBM peak, duration from HIP events
+               recorded on the launch stream around every launch inside the timed region
   cpu_baseline the sequential CPU oracle on a reduced instance of the same workload
 """
 from __future__ import annotations
@@ -22,6 +23,26 @@ import time
 import numpy as np
 
 HBM_PEAK_GBPS = 8000.0
+
+# HBM bytes per copy launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
+# plain-copy calibration dispatch of the same run; summaries under profiles/).  The figures belong
+# to one version of the copy kernel source: when copy.hip changes they are reported as null.
+PMC_TRAFFIC = {
+    "copy_hip_sha256": "4deac334c2cefdcbee737ac859497ddf24c90842868dd5fb4108bd504b665158",
+    "kv_migration": {"gather": 42713231773, "scatter": 42713434909},
+}
+
+
+def measured_traffic(workload, kernel):
+    import hashlib
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_00368_amd", "csrc", "copy.hip")
+    try:
+        digest = hashlib.sha256(open(path, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    if digest != PMC_TRAFFIC["copy_hip_sha256"]:
+        return None
+    return PMC_TRAFFIC.get(workload, {}).get(kernel)
 
 
 def parse():
@@ -142,6 +163,19 @@ def main():
     remaining = T.tent_poll(ctx, batches[-1], stream)
     assert remaining == 0, remaining
 
+    # Plain copy of known size (1 GiB read + 1 GiB written by one elementwise kernel), outside the
+    # timed region: the practical copy ceiling of the box and the reference dispatch that scales
+    # hardware byte counters when this script runs under a counter-collecting profiler.
+    cal_n = min(1 << 30, src.numel(), dst.numel())
+    cal_in, cal_out = src[:cal_n], arena[:cal_n]
+    torch.bitwise_not(cal_in, out=cal_out)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    torch.bitwise_not(cal_in, out=cal_out)
+    ev1.record()
+    torch.cuda.synchronize(dev)
+    plain_copy_GBps = 2 * cal_n / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+
     def avg_ms(*names):
         return sum(tm[n][0] for n in names) / max(1, args.steps)
 
@@ -152,7 +186,9 @@ def main():
     scatter_avg = scatter_ms / max(1, scatter_n)
     ms_per_step = elapsed * 1e3 / args.steps
     value = 4 * w.payload / (ms_per_step * 1e-3) / 1e9
-    achieved = 2 * w.payload / (gather_avg * 1e-3) / 1e9
+    # the roofline entry describes the slower of the two copy launches
+    dom, dom_avg = ("scatter", scatter_avg) if scatter_avg >= gather_avg else ("gather", gather_avg)
+    achieved = 2 * w.payload / (dom_avg * 1e-3) / 1e9
 
     out = {
         "metric": "slice gather/scatter GB/s (read+write bytes, whole plan+execute step)",
@@ -167,10 +203,14 @@ def main():
         "stage_ms": {k: round(v[0] / max(1, args.steps), 4) for k, v in tm.items()},
         "execute_GBps": round(4 * w.payload / ((gather_avg + scatter_avg) * 1e-3) / 1e9, 2),
         "declare_ms": round(declare_ms, 3),
-        "roofline": {"bound": "hbm", "kernel": "copy_kernel<gather>", "achieved": round(achieved, 2),
+        "plain_copy_GBps": round(plain_copy_GBps, 2),
+        "roofline": {"bound": "hbm", "kernel": f"copy_kernel<{dom}>", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": None,
-                     "scatter_achieved": round(2 * w.payload / (scatter_avg * 1e-3) / 1e9, 2)},
+                     "traffic": measured_traffic(w.name, dom),
+                     "algorithmic_bytes_per_launch": 2 * w.payload,
+                     "avg_launch_ms": round(dom_avg, 4),
+                     "gather_GBps": round(2 * w.payload / (gather_avg * 1e-3) / 1e9, 2),
+                     "scatter_GBps": round(2 * w.payload / (scatter_avg * 1e-3) / 1e9, 2)},
     }
     T.tent_destroy(ctx)
     del src, dst, arena
