@@ -47,7 +47,7 @@ __device__ __forceinline__ uint64_t xor64(uint64_t v, int mask)
 // All-reduce over the wavefront with a symmetric butterfly (quad swaps, half-row mirror, row mirror,
 // then rows), so every lane ends with the same value.  `wide` > 16 / > 32 enables the row steps.
 template <class Op>
-__device__ __forceinline__ uint64_t wave_reduce64(uint64_t v, uint32_t wide, Op op)
+__device__ __forceinline__ uint64_t wave_reduce64(uint64_t v, int wide, Op op)
 {
     v = op(v, dpp64<0xB1>(v));
     v = op(v, dpp64<0x4E>(v));
@@ -66,7 +66,7 @@ struct OpAddF {
         return (uint64_t)__double_as_longlong(__longlong_as_double((long long)a) + __longlong_as_double((long long)b));
     }
 };
-__device__ __forceinline__ double wave_sum_f64(double x, uint32_t wide)
+__device__ __forceinline__ double wave_sum_f64(double x, int wide)
 {
     return __longlong_as_double((long long)wave_reduce64((uint64_t)__double_as_longlong(x), wide, OpAddF{}));
 }
@@ -81,6 +81,44 @@ __device__ __forceinline__ uint64_t read_lane64(uint64_t v, int lane)
     uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, lane);
     uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), lane);
     return ((uint64_t)hi << 32) | lo;
+}
+
+
+// 32-bit all-reduce over the wavefront; the DPP moves fold into the min/max/add instructions.
+template <class Op>
+__device__ __forceinline__ uint32_t wave_reduce32(uint32_t v, int wide, Op op)
+{
+    v = op(v, dpp32<0xB1>(v));
+    v = op(v, dpp32<0x4E>(v));
+    v = op(v, dpp32<0x141>(v));
+    v = op(v, dpp32<0x140>(v));
+    if (wide > 16) v = op(v, (uint32_t)__shfl_xor((int)v, 16, 64));
+    if (wide > 32) v = op(v, (uint32_t)__shfl_xor((int)v, 32, 64));
+    return v;
+}
+struct Min32 { __device__ uint32_t operator()(uint32_t a, uint32_t b) const { return a < b ? a : b; } };
+struct Max32 { __device__ uint32_t operator()(uint32_t a, uint32_t b) const { return a > b ? a : b; } };
+struct Add32 { __device__ uint32_t operator()(uint32_t a, uint32_t b) const { return a + b; } };
+
+// Lane holding the smallest (cost, lane) pair among the lanes with valid = true (ties to the lowest
+// lane), as a uniform value.  The 64-bit key (cost << 6) | lane is reduced as two 32-bit halves:
+// first the high half, then the low half among the lanes that match the winning high half.
+__device__ __forceinline__ int argmin_cost(uint64_t cost, bool valid, int lane, int wide)
+{
+    const uint32_t hi = valid ? (uint32_t)(cost >> 26) : 0xFFFFFFFFu;
+    const uint32_t lo = ((uint32_t)cost << 6) | (uint32_t)lane;
+    const uint32_t hi_min = wave_reduce32(hi, wide, Min32{});
+    const uint32_t lo_min = wave_reduce32(hi == hi_min && valid ? lo : 0xFFFFFFFFu, wide, Min32{});
+    return (int)(__builtin_amdgcn_readfirstlane((int)lo_min) & 63);
+}
+// Same for the largest (cost, lane) pair (ties to the highest lane).
+__device__ __forceinline__ int argmax_cost(uint64_t cost, bool valid, int lane, int wide)
+{
+    const uint32_t hi = valid ? (uint32_t)(cost >> 26) : 0u;
+    const uint32_t lo = ((uint32_t)cost << 6) | (uint32_t)lane;
+    const uint32_t hi_max = wave_reduce32(hi, wide, Max32{});
+    const uint32_t lo_max = wave_reduce32(hi == hi_max && valid ? lo : 0u, wide, Max32{});
+    return (int)(__builtin_amdgcn_readfirstlane((int)lo_max) & 63);
 }
 
 // floor(a / b) for 1 <= b < 2^32 with inv = 1.0 / b.  The floating-point quotient is only an
@@ -191,11 +229,14 @@ __device__ __forceinline__ uint32_t slots_upto_fast(const Rail& r, uint64_t A, u
     return k;
 }
 
+// kWide = 16, 32 or 64: lanes that can hold a rail; with 16 every reduction stays inside one DPP row.
+template <int kWide>
 __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams rp, int use_pending)
 {
     const int lane = threadIdx.x;
-    const uint32_t R = rp.n_rails;
-    const bool live = lane < (int)R && ((rp.admitted >> lane) & 1);
+    constexpr int R = kWide;                                  // reduction width
+    const int n_rails = (int)rp.n_rails;
+    const bool live = lane < n_rails && ((rp.admitted >> lane) & 1);
     const uint64_t live_mask = __ballot(live);
     const double n_live = (double)__popcll(live_mask);
     Rail rail;
@@ -205,7 +246,9 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
     const double G = live ? 65536.0 * rail.inv_c1 : 0.0;      // bytes the rail absorbs per picosecond
     const double g = (double)rail.c0 * G;                     // its fixed latency expressed in bytes
     const double inv_S = 1.0 / (double)b.slice_bytes;
+    const double c0d1 = 1.0 - (double)rail.c0;               // 1 - c0 as a double (c0 < 2^53)
     uint64_t A = rp.A[lane], T = 0, cnt = 0;
+    double Ad = (double)A;                                    // floating-point shadow of A, estimates only
     const uint64_t n_runs = b.plan->n_runs;
     const uint32_t stride = b.run_stride;
 
@@ -236,10 +279,10 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
             const uint64_t row = (blk + t) * stride;
             uint32_t k = 0;
 
+            const double ld = (double)l;
             if (m == 1) {
                 // a single slice: plain argmin, result written directly
-                const uint64_t key = live ? ((slot_cost(rail, A, l, 0) << 6) | (uint32_t)lane) : ~0ull;
-                const int win = (int)(uniform64(wave_reduce64(key, R, OpMin{})) & 63);
+                const int win = argmin_cost(slot_cost(rail, A, l, 0), live, lane, R);
                 const uint64_t T_win = read_lane64(T, win);
                 if (lane == 0) {
                     const uint32_t id = __builtin_amdgcn_readlane((int)my_id, t);
@@ -249,10 +292,58 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
                 }
                 k = lane == win;
             } else {
-                if (lane < (int)R) b.run_T[row + lane] = T;
-                const double inv_l = l == b.slice_bytes ? inv_S : 1.0 / (double)l;
+                if (lane < n_rails) b.run_T[row + lane] = T;
+                const double inv_l = l == b.slice_bytes ? inv_S : 1.0 / ld;
                 uint32_t taken = 0;
-                if (m > (uint32_t)kTol) {
+                bool solved = false;
+                if (__builtin_expect(all_proven && m > (uint32_t)kTol, 1)) {
+                    // Steady state, lean path: level from the incremental water-filling sums, slot
+                    // counts from a floating-point estimate confirmed by the integer cost of the
+                    // slot below and the slot above, repair with incrementally updated costs.
+                    const double v = (((double)m + 0.5 * n_live) * ld + pool_B) * inv_pool_G;
+                    if (__builtin_expect(v >= 0.0 && v < 1.0e15, 1)) {
+                        const double vfl = floor(v);
+                        const uint64_t vi = (uint64_t)vfl;
+                        double kf = ((vfl + c0d1) * G - Ad) * inv_l;
+                        kf = kf > 0.0 ? kf : 0.0;
+                        kf = kf < (double)m ? kf : (double)m;
+                        uint32_t kk = (uint32_t)kf;
+                        const uint64_t lc1 = (uint64_t)l * rail.c1;
+                        uint64_t p_prev = (A + (uint64_t)kk * l) * (uint64_t)rail.c1;   // slot kk-1 ends here
+                        uint64_t p_next = p_prev + lc1;                                  // slot kk ends here
+                        uint64_t c_prev = rail.c0 + (p_prev >> 16);
+                        uint64_t c_next = rail.c0 + (p_next >> 16);
+                        const bool off = live && ((kk < m && c_next <= vi) || (kk > 0 && c_prev > vi));
+                        if (__builtin_expect(__ballot(off) == 0, 1)) {
+                            const uint32_t tt = __builtin_amdgcn_readfirstlane((int)wave_reduce32(kk, R, Add32{}));
+                            int miss = (int)m - (int)tt;
+                            if (__builtin_expect(miss <= kTol && miss >= -kTol, 1)) {
+                                while (miss > 0) {            // add the cheapest free slot
+                                    const int win = argmin_cost(c_next, live && kk < m, lane, R);
+                                    if (lane == win) {
+                                        ++kk;
+                                        p_prev = p_next; c_prev = c_next;
+                                        p_next += lc1;   c_next = rail.c0 + (p_next >> 16);
+                                    }
+                                    --miss;
+                                }
+                                while (miss < 0) {            // drop the dearest taken slot
+                                    const int win = argmax_cost(c_prev, live && kk > 0, lane, R);
+                                    if (lane == win) {
+                                        --kk;
+                                        p_next = p_prev; c_next = c_prev;
+                                        p_prev -= lc1;   c_prev = rail.c0 + (p_prev >> 16);
+                                    }
+                                    ++miss;
+                                }
+                                k = kk;
+                                taken = m;
+                                solved = true;
+                            }
+                        }
+                    }
+                }
+                if (__builtin_expect(!solved && m > (uint32_t)kTol, 0)) {
                     double v;
                     if (all_proven) {
                         v = (((double)m + 0.5 * n_live) * (double)l + pool_B) * inv_pool_G;
@@ -329,25 +420,24 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
                 }
                 // repair: add the cheapest free slot / drop the dearest taken slot
                 while (taken < m) {
-                    const uint64_t key = live ? ((slot_cost(rail, A, l, k) << 6) | (uint32_t)lane) : ~0ull;
-                    const int win = (int)(uniform64(wave_reduce64(key, R, OpMin{})) & 63);
+                    const int win = argmin_cost(slot_cost(rail, A, l, k), live && k < m, lane, R);
                     k += lane == win;
                     ++taken;
                 }
                 while (taken > m) {
-                    const uint64_t key = (live && k > 0) ? ((slot_cost(rail, A, l, k - 1) << 6) | (uint32_t)lane) : 0ull;
-                    const int win = (int)(uniform64(wave_reduce64(key, R, OpMax{})) & 63);
+                    const int win = argmax_cost(slot_cost(rail, A, l, k > 0 ? k - 1 : 0), live && k > 0, lane, R);
                     k -= lane == win;
                     --taken;
                 }
-                if (lane < (int)R) b.run_K[row + lane] = k;
+                if (lane < n_rails) b.run_K[row + lane] = k;
             }
             const uint64_t bytes = (uint64_t)k * l;
             A += bytes;
             T += bytes;
             cnt += k;
+            Ad = fma((double)k, ld, Ad);
             if (all_proven) {
-                pool_B += (double)m * (double)l;
+                pool_B += (double)m * ld;
             } else if (__ballot(live && cnt > 0) == live_mask) {
                 all_proven = true;
                 pool_G = wave_sum_f64(G, R);
@@ -451,7 +541,9 @@ hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, bool use_pe
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(run_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, up);
-    hipLaunchKernelGGL(bind_chain_kernel, dim3(1), dim3(64), 0, s, b, rp, up);
+    if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, up);
+    else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, up);
+    else                       hipLaunchKernelGGL(bind_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, up);
     hipLaunchKernelGGL(bind_emit_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, rp, up);
     return hipGetLastError();
 }
