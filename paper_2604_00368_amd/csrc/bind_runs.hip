@@ -245,7 +245,6 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
     rail.inv_c1 = 1.0 / (double)rail.c1;
     const double G = live ? 65536.0 * rail.inv_c1 : 0.0;      // bytes the rail absorbs per picosecond
     const double g = (double)rail.c0 * G;                     // its fixed latency expressed in bytes
-    const double inv_S = 1.0 / (double)b.slice_bytes;
     const double c0d1 = 1.0 - (double)rail.c0;               // 1 - c0 as a double (c0 < 2^53)
     uint64_t A = rp.A[lane], T = 0, cnt = 0;
     double Ad = (double)A;                                    // floating-point shadow of A, estimates only
@@ -259,7 +258,7 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
     double pool_G = 0.0, pool_B = 0.0, inv_pool_G = 0.0;
 
     // run descriptors are fetched 64 at a time, one per lane, the next block prefetched
-    uint32_t nx_start = 0, nx_m = 0, nx_len = 0, nx_id = 0;
+    uint32_t nx_start = 0, nx_m = 0, nx_len = 1, nx_id = 0;
     auto fetch = [&](uint64_t r) {
         if (r < n_runs) {
             nx_start = b.run_start[r];
@@ -271,6 +270,7 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
     fetch(lane);
     for (uint64_t blk = 0; blk < n_runs; blk += 64) {
         const uint32_t my_m = nx_m, my_len = nx_len, my_id = nx_id;
+        const double my_inv_len = 1.0 / (double)my_len;       // one division per lane serves 64 runs
         fetch(blk + 64 + lane);
         const int in_blk = (int)(n_runs - blk < 64 ? n_runs - blk : 64);
         for (int t = 0; t < in_blk; ++t) {
@@ -293,7 +293,8 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
                 k = lane == win;
             } else {
                 if (lane < n_rails) b.run_T[row + lane] = T;
-                const double inv_l = l == b.slice_bytes ? inv_S : 1.0 / ld;
+                const double inv_l = __longlong_as_double((long long)read_lane64(
+                    (uint64_t)__double_as_longlong(my_inv_len), t));
                 uint32_t taken = 0;
                 bool solved = false;
                 if (__builtin_expect(all_proven && m > (uint32_t)kTol, 1)) {
