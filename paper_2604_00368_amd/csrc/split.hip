@@ -115,11 +115,50 @@ __global__ void __launch_bounds__(256) tile_table_kernel(BatchDev b)
     }
 }
 
+// Destination-ordered tiles: tile q covers bytes [q*tile, (q+1)*tile) of the destination extents
+// laid end to end in ascending device address.  For each tile: its destination address, the slice
+// that owns it and its offset inside that slice (independent of the binding).
+struct OrderedLen {
+    const tent_extent* ext;
+    const uint32_t* order;
+    __device__ uint64_t operator()(uint64_t r) const { return ext[order[r]].len; }
+};
+
+__global__ void __launch_bounds__(256) scatter_table_kernel(BatchDev b)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < b.n_sc_tiles; q += stride) {
+        const uint64_t at = q * b.tile_bytes;
+        const uint64_t r = last_not_above(b.ord_pre, 0, b.n_dst_ext, at);
+        const uint32_t e = b.dst_order[r];
+        const uint64_t within = at - b.ord_pre[r];
+        const tent_extent ex = b.dst_ext[e];
+        // owning transfer: last j with dst_ptr[j] <= e
+        uint32_t lo = 0, hi = b.n_desc;
+        while (hi - lo > 1) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            if (b.dst_ptr[mid] <= e) lo = mid; else hi = mid;
+        }
+        const uint64_t off = b.dst_pre[e] + within - b.dst_pre[b.dst_ptr[lo]];   // offset inside the transfer
+        const uint64_t k = off / b.slice_bytes;
+        b.sc_dst[q] = b.seg_base[ex.seg] + ex.off + within;
+        b.sc_slice[q] = (uint32_t)(b.first[lo] + k);
+        b.sc_x[q] = (uint32_t)(off - k * b.slice_bytes);
+    }
+}
+
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s)
 {
     uint64_t blocks = (b.n_slices * (uint64_t)b.tiles_per_slice + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(tile_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    if (b.n_sc_tiles) {
+        hipError_t e = exclusive_scan(OrderedLen{b.dst_ext, b.dst_order}, b.n_dst_ext, b.ord_pre, b.scan_partials, s);
+        if (e != hipSuccess) return e;
+        blocks = (b.n_sc_tiles + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(scatter_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    }
     return hipGetLastError();
 }
 
@@ -138,11 +177,26 @@ __global__ void __launch_bounds__(256) finalize_kernel(BatchDev b, uint8_t* aren
     }
 }
 
+// Staging address of every destination-ordered tile whose slice is about to move (0 otherwise).
+__global__ void __launch_bounds__(256) finalize_scatter_kernel(BatchDev b)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < b.n_sc_tiles; q += stride) {
+        const SliceRec r = b.s_rec[b.sc_slice[q]];
+        b.sc_lin[q] = r.len ? r.lin + b.sc_x[q] : 0;
+    }
+}
+
 hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s)
 {
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(finalize_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, arena);
+    if (b.n_sc_tiles) {
+        blocks = (b.n_sc_tiles + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(finalize_scatter_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    }
     return hipGetLastError();
 }
 

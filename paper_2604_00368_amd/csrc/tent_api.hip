@@ -93,7 +93,7 @@ void free_batch(Batch& b)
     b.dev = BatchDev{};
 }
 
-struct Interval { uint64_t lo, hi; uint32_t seg; uint32_t is_dst; };
+struct Interval { uint64_t lo, hi; uint32_t idx; uint32_t is_dst; };
 
 // Walk both extent lists of every transfer: structure, bounds, equal lengths.  Also returns
 // the payload and the number of slices the device splitter will produce.
@@ -132,29 +132,44 @@ int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const ten
     return TENT_OK;
 }
 
-// A destination extent may overlap neither another destination extent nor a source extent
-// (addresses compared, so aliasing segments are caught as well).
-int check_overlap(const tent_ctx* ctx, uint64_t ns, const tent_extent* se, uint64_t nd, const tent_extent* de)
+// Destination extents sorted by device address (the scatter kernel walks them in this order so
+// that its writes are sequential).  With `check` set, also verify that a destination extent
+// overlaps neither another destination extent nor any source extent of the batch (addresses are
+// compared, so aliasing segments are caught as well).
+int order_destinations(const tent_ctx* ctx, uint64_t ns, const tent_extent* se, uint64_t nd, const tent_extent* de,
+                       bool check, std::vector<uint32_t>* order, uint64_t* addr_bits)
 {
     std::vector<Interval> iv;
-    try { iv.reserve(ns + nd); } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
-    for (uint64_t e = 0; e < ns; ++e) {
-        uint64_t a = (uint64_t)ctx->segments[se[e].seg].base + se[e].off;
-        iv.push_back({a, a + se[e].len, se[e].seg, 0});
-    }
+    try {
+        iv.reserve(nd + (check ? ns : 0));
+        order->resize(nd);
+    } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
+    uint64_t bits = 0;
     for (uint64_t e = 0; e < nd; ++e) {
-        uint64_t a = (uint64_t)ctx->segments[de[e].seg].base + de[e].off;
-        iv.push_back({a, a + de[e].len, de[e].seg, 1});
+        const uint64_t a = (uint64_t)ctx->segments[de[e].seg].base + de[e].off;
+        bits |= a;
+        iv.push_back({a, a + de[e].len, (uint32_t)e, 1});
     }
-    std::sort(iv.begin(), iv.end(), [](const Interval& x, const Interval& y) { return x.lo < y.lo; });
+    if (check)
+        for (uint64_t e = 0; e < ns; ++e) {
+            const uint64_t a = (uint64_t)ctx->segments[se[e].seg].base + se[e].off;
+            iv.push_back({a, a + se[e].len, (uint32_t)e, 0});
+        }
+    std::sort(iv.begin(), iv.end(), [](const Interval& x, const Interval& y) {
+        return x.lo != y.lo ? x.lo < y.lo : x.idx < y.idx;
+    });
     // sweep: remember the furthest end seen so far among destinations and among all intervals
-    uint64_t far_any = 0, far_dst = 0;
+    uint64_t far_any = 0, far_dst = 0, k = 0;
     for (const Interval& x : iv) {
-        if (x.is_dst) { if (x.lo < far_any) return TENT_ERR_INVALID; }
-        else          { if (x.lo < far_dst) return TENT_ERR_INVALID; }
-        far_any = std::max(far_any, x.hi);
-        if (x.is_dst) far_dst = std::max(far_dst, x.hi);
+        if (check) {
+            if (x.is_dst) { if (x.lo < far_any) return TENT_ERR_INVALID; }
+            else          { if (x.lo < far_dst) return TENT_ERR_INVALID; }
+            far_any = std::max(far_any, x.hi);
+            if (x.is_dst) far_dst = std::max(far_dst, x.hi);
+        }
+        if (x.is_dst) (*order)[k++] = x.idx;
     }
+    *addr_bits = bits;
     return TENT_OK;
 }
 
@@ -291,10 +306,11 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc != TENT_OK) return rc;
     if (n_slices >= 0xFFFFFFFEull || n_desc >= 0x7FFFFFFFu) return TENT_ERR_RANGE;
     const uint64_t ns = src_ptr[n_desc], nd = dst_ptr[n_desc];
-    if (!(ctx->cfg.flags & TENT_FLAG_SKIP_OVERLAP_CHECK)) {
-        rc = check_overlap(ctx, ns, src_ext, nd, dst_ext);
-        if (rc != TENT_OK) return rc;
-    }
+    std::vector<uint32_t> dst_order;
+    uint64_t dst_addr_bits = 0;
+    rc = order_destinations(ctx, ns, src_ext, nd, dst_ext, !(ctx->cfg.flags & TENT_FLAG_SKIP_OVERLAP_CHECK),
+                            &dst_order, &dst_addr_bits);
+    if (rc != TENT_OK) return rc;
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
 
@@ -326,6 +342,14 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
         d.tiles_per_slice = (uint32_t)((d.slice_bytes + d.tile_bytes - 1) / d.tile_bytes);
     }
     const uint64_t n_tiles = n_slices * d.tiles_per_slice;
+    // Destination-ordered scatter needs every boundary on a tile boundary and 16-byte aligned
+    // addresses on both sides; other geometry keeps the slice-ordered scatter.
+    {
+        const uint64_t bits = len_bits | d.slice_bytes;
+        const bool tiled = (bits & (d.tile_bytes - 1)) == 0;
+        const bool aligned = ((dst_addr_bits | (uint64_t)ctx->cfg.staging_arena) & 15) == 0;
+        d.n_sc_tiles = (tiled && aligned) ? payload / d.tile_bytes : 0;
+    }
 
     uint32_t *sp = nullptr, *dp = nullptr;
     tent_extent *se = nullptr, *de = nullptr;
@@ -355,13 +379,29 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc == TENT_OK) rc = dev_alloc(b, &d.run_start, (uint64_t)d.run_capacity + 1);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.run_T, (uint64_t)d.run_capacity * d.run_stride);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.run_K, (uint64_t)d.run_capacity * d.run_stride);
+    uint32_t* order_dev = nullptr;
+    if (d.n_sc_tiles) {
+        if (rc == TENT_OK) rc = dev_alloc(b, &order_dev, nd);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.ord_pre, nd + 1);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_dst, d.n_sc_tiles);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_lin, d.n_sc_tiles);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_slice, d.n_sc_tiles);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_x, d.n_sc_tiles);
+    }
     if (rc == TENT_OK) rc = dev_alloc(b, &d.pending, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_tmp, scan_n + 1);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_partials, scan_partials_capacity(scan_n));
     if (rc == TENT_OK) rc = dev_alloc(b, &d.plan, 1);
     if (rc != TENT_OK) { free_batch(b); return rc; }
     d.src_ptr = sp; d.dst_ptr = dp; d.src_ext = se; d.dst_ext = de;
+    d.dst_order = order_dev;
     d.self = self_dev;
+    if (order_dev &&
+        hipMemcpy(order_dev, dst_order.data(), sizeof(uint32_t) * nd, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        free_batch(b);
+        return TENT_ERR_HIP;
+    }
 
     if (hipMemcpy(sp, src_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(dp, dst_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
@@ -485,7 +525,8 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     }
     {
         StageTimer t(ctx, TENT_T_SCATTER, s);
-        HIP_TRY(launch_copy(b->dev, false, s));
+        if (b->dev.n_sc_tiles) HIP_TRY(launch_scatter_ordered(b->dev, s));
+        else                   HIP_TRY(launch_copy(b->dev, false, s));
     }
     HIP_TRY(launch_mark_done(b->dev, s));
     b->has_done = true;

@@ -81,6 +81,17 @@ struct BatchDev {
     uint32_t  tile_bytes;          // 1 KiB, 2 KiB or 4 KiB
     uint32_t  tiles_per_slice;
 
+    // Destination-ordered scatter (only when every boundary falls on a tile boundary and all
+    // addresses are 16-byte aligned; n_sc_tiles = 0 otherwise): tiles of the destination bytes in
+    // ascending device address, so that the scatter kernel writes sequentially.
+    const uint32_t* dst_order;     // [n_dst_ext] destination extents sorted by device address
+    uint64_t* ord_pre;             // [n_dst_ext+1] exclusive prefix of their lengths in that order
+    uint64_t  n_sc_tiles;          // payload / tile_bytes
+    uint64_t* sc_dst;              // [n_sc_tiles] destination address of the tile
+    uint64_t* sc_lin;              // [n_sc_tiles] staging address of the tile, 0 = not to be moved
+    uint32_t* sc_slice;            // [n_sc_tiles] slice that holds the tile
+    uint32_t* sc_x;                // [n_sc_tiles] byte offset of the tile inside that slice
+
     // Run-parallel binding: maximal runs of equal-length pending slices (at most two per transfer)
     uint32_t* run_start;           // [run_capacity + 1] first pending position of every run
     uint64_t* run_T;               // [run_capacity * run_stride] bytes bound per rail before the run
@@ -110,6 +121,7 @@ hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, bool use_pe
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
 hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s);
 hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s);
+hipError_t launch_scatter_ordered(const BatchDev& b, hipStream_t s);
 hipError_t launch_mark_done(const BatchDev& b, hipStream_t s);
 hipError_t launch_retire(const BatchDev& b, const BudgetParams& bp, hipStream_t s);
 hipError_t launch_count_remaining(const BatchDev& b, hipStream_t s);
