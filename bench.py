@@ -28,8 +28,8 @@ HBM_PEAK_GBPS = 8000.0
 # plain-copy calibration dispatch of the same run; summaries under profiles/).  The figures belong
 # to one version of the copy kernel source: when copy.hip changes they are reported as null.
 PMC_TRAFFIC = {
-    "copy_hip_sha256": "4deac334c2cefdcbee737ac859497ddf24c90842868dd5fb4108bd504b665158",
-    "kv_migration": {"gather": 42713231773, "scatter": 42713434909},
+    "copy_hip_sha256": "e0d8de25db98adf0b620fd6a59409e6ea88291c8e46d68551c96c5f180f74c5d",
+    "kv_migration": {"gather": 42713234077, "scatter": 43019354183},
 }
 
 
@@ -204,7 +204,7 @@ def main():
         "execute_GBps": round(4 * w.payload / ((gather_avg + scatter_avg) * 1e-3) / 1e9, 2),
         "declare_ms": round(declare_ms, 3),
         "plain_copy_GBps": round(plain_copy_GBps, 2),
-        "roofline": {"bound": "hbm", "kernel": f"copy_kernel<{dom}>", "achieved": round(achieved, 2),
+        "roofline": {"bound": "hbm", "kernel": "copy_kernel<gather>" if dom == "gather" else "scatter_ordered_kernel", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(w.name, dom),
                      "algorithmic_bytes_per_launch": 2 * w.payload,
