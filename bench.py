@@ -4,7 +4,10 @@
 One step = tent_plan (extent scans, slice scan, slice-table expansion, rail binding) followed by
 tent_execute (gather into per-rail staging, scatter to destination) over one freshly declared
 batch of the KVCache-migration workload; descriptor tables and byte pools are resident in HBM
-before the timed region starts.  Prints ONE JSON line.
+before the timed region starts.  The K timed steps run twice: on a single stream, and with the
+plans on a second stream so that step k+1's binding (a one-wavefront dependency chain) runs under
+step k's copies; the second figure is the headline unless --single-stream is given, both are
+printed.  Prints ONE JSON line.
 
   value        read+write GB/s of the whole step: 4 * payload * steps / elapsed
   roofline     the slower of the two copy kernels (gather: source pages -> staging, scatter: staging ->
@@ -54,6 +57,9 @@ def parse():
                     choices=["tiny", "kv_migration", "rl_params", "many_small", "many_small_x6"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial-binding", action="store_true")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="report the single-stream step time as the headline (default: plan of step k+1 "
+                         "overlaps execute of step k on a second stream)")
     return ap.parse_args()
 
 
@@ -143,25 +149,45 @@ def main():
     declare_ms = (time.perf_counter() - t0) * 1e3 / total
     n_slices = T.tent_slice_count(ctx, batches[0])
 
-    def step(h):
+    plan_stream = torch.cuda.Stream(dev)               # default priority
+
+    def step_single(h):
         T.tent_plan(ctx, h, w.rails, want_info=False, stream=stream)
         T.tent_execute(ctx, h, stream)
 
-    for h in batches[:args.warmup]:
-        step(h)
-    torch.cuda.synchronize(dev)
-    T.tent_get_timings(ctx)                            # drop warm-up intervals
+    def step_pipelined(h):
+        # every step still plans and executes its own batch; the plan is enqueued on a second stream
+        # so that the next step's (mostly one-wavefront) binding runs under this step's copies
+        T.tent_plan(ctx, h, w.rails, want_info=False, stream=plan_stream)
+        ev = torch.cuda.Event()
+        ev.record(plan_stream)
+        stream.wait_event(ev)
+        T.tent_execute(ctx, h, stream)
 
-    torch.cuda.synchronize(dev)
-    t0 = time.perf_counter()
-    for h in batches[args.warmup:]:
-        step(h)
-    torch.cuda.synchronize(dev)
-    elapsed = time.perf_counter() - t0
+    def timed_pass(step):
+        for h in batches[:args.warmup]:
+            step(h)
+        torch.cuda.synchronize(dev)
+        T.tent_get_timings(ctx)                        # drop warm-up intervals
+        torch.cuda.synchronize(dev)
+        t0 = time.perf_counter()
+        for h in batches[args.warmup:]:
+            step(h)
+        torch.cuda.synchronize(dev)
+        dt = time.perf_counter() - t0
+        tm_ = T.tent_get_timings(ctx)
+        assert T.tent_poll(ctx, batches[-1], stream) == 0
+        return dt, tm_
 
-    tm = T.tent_get_timings(ctx)
-    remaining = T.tent_poll(ctx, batches[-1], stream)
-    assert remaining == 0, remaining
+    elapsed_single, tm_single = timed_pass(step_single)
+    for h in batches:
+        T.tent_reset(ctx, h, stream)                   # back to PENDING: the next pass re-plans from scratch
+    torch.cuda.synchronize(dev)
+    elapsed_piped, tm_piped = timed_pass(step_pipelined)
+    if args.single_stream:
+        elapsed, tm = elapsed_single, tm_single
+    else:
+        elapsed, tm = elapsed_piped, tm_piped
 
     # Plain copy of known size (1 GiB read + 1 GiB written by one elementwise kernel), outside the
     # timed region: the practical copy ceiling of the box and the reference dispatch that scales
@@ -197,7 +223,11 @@ def main():
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": w.name, "payload_bytes": w.payload, "n_desc": w.n_desc,
                    "n_extents": int(w.src_ext.shape[0]), "n_slices": n_slices, "slice_bytes": w.slice_bytes,
-                   "n_rails": int(w.rails.shape[0]), "binding": "serial" if args.serial_binding else "default"},
+                   "n_rails": int(w.rails.shape[0]), "binding": "serial" if args.serial_binding else "default",
+                   "streams": "single" if args.single_stream else
+                              "two: plan of step k+1 overlaps execute of step k; every step plans and executes its own batch"},
+        "ms_per_step_single_stream": round(elapsed_single * 1e3 / args.steps, 4),
+        "ms_per_step_two_streams": round(elapsed_piped * 1e3 / args.steps, 4),
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "slices_planned_per_s": round(n_slices / (plan_ms * 1e-3), 1) if plan_ms > 0 else None,
         "stage_ms": {k: round(v[0] / max(1, args.steps), 4) for k, v in tm.items()},
