@@ -202,10 +202,8 @@ def main():
     torch.cuda.synchronize(dev)
     plain_copy_GBps = 2 * cal_n / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
 
-    def avg_ms(*names):
-        return sum(tm[n][0] for n in names) / max(1, args.steps)
-
-    plan_ms = avg_ms("extent_scan", "slice_scan", "expand", "compact", "bind")
+    # plan stages are timed on the single-stream pass, where nothing runs beside them
+    plan_ms = sum(tm_single[n][0] for n in ("extent_scan", "slice_scan", "expand", "compact", "bind")) / max(1, args.steps)
     gather_ms, gather_n = tm["gather"]
     scatter_ms, scatter_n = tm["scatter"]
     gather_avg = gather_ms / max(1, gather_n)
@@ -231,6 +229,7 @@ def main():
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "slices_planned_per_s": round(n_slices / (plan_ms * 1e-3), 1) if plan_ms > 0 else None,
         "stage_ms": {k: round(v[0] / max(1, args.steps), 4) for k, v in tm.items()},
+        "stage_ms_single_stream": {k: round(v[0] / max(1, args.steps), 4) for k, v in tm_single.items()},
         "execute_GBps": round(4 * w.payload / ((gather_avg + scatter_avg) * 1e-3) / 1e9, 2),
         "declare_ms": round(declare_ms, 3),
         "plain_copy_GBps": round(plain_copy_GBps, 2),
