@@ -265,3 +265,55 @@ def test_defer_errors_and_reuse(H, oracle):
             T.tent_slice_count(eng.ctx, h)
         h2 = eng.declare()
         assert h2 != h and T.tent_slice_count(eng.ctx, h2) == s.n
+
+
+@pytest.mark.parametrize("R", [1, 16, 17, 33, 64])
+def test_rail_counts_up_to_the_maximum(H, oracle, R):
+    # 1, 16 | 17 | 33, 64 rails exercise the three reduction widths of the binder
+    print("rails", R, flush=True)
+    rng = np.random.Generator(np.random.PCG64(500 + R))
+    w = W.many_small(n_req=40, layers=1)
+    w.rails = W.make_rails(rng.integers(5000, 200000, size=R), lat_ns=rng.integers(1000, 9000, size=R),
+                           queued=rng.integers(0, 1 << 20, size=R),
+                           health=np.where(rng.random(R) < 0.15, 2, 0).astype(np.uint8) if R > 1 else 0)
+    if (w.rails["health"] == 2).all():
+        w.rails["health"][0] = 0
+    run_and_compare(H, oracle, w)
+    from paper_2604_00368_amd import binding as T
+    run_and_compare(H, oracle, w, flags=T.TENT_FLAG_SERIAL_BINDING)
+
+
+def test_degenerate_batches(H, oracle):
+    from paper_2604_00368_amd import binding as T
+    print("degenerate", flush=True)
+    # one transfer of one byte
+    ptr = np.array([0, 1], dtype=np.uint32)
+    w = W.Workload("one_byte", 9, 65536, [64, 64], ptr, W._extents(0, [5], 1), ptr.copy(), W._extents(1, [17], 1),
+                   W.make_rails([25000, 50000]), "u8")
+    run_and_compare(H, oracle, w)
+    # a transfer exactly one slice long, one exactly two slices long, slice size 1 byte over a ragged batch
+    ptr = np.array([0, 1, 2], dtype=np.uint32)
+    w = W.Workload("exact", 10, 4096, [16384, 16384], ptr, W._extents(0, [0, 4096], [4096, 8192]), ptr.copy(),
+                   W._extents(1, [8192, 0], [4096, 8192]), W.make_rails([25000, 50000, 100000]), "u8")
+    run_and_compare(H, oracle, w)
+    # no transfers at all is rejected
+    with H.Engine(w, np.zeros(16384, np.uint8), np.zeros(16384, np.uint8)) as eng:
+        with pytest.raises(T.TentError) as ei:
+            T.tent_declare(eng.ctx, np.zeros(1, np.uint32), np.zeros(0, W.EXTENT_DTYPE),
+                           np.zeros(1, np.uint32), np.zeros(0, W.EXTENT_DTYPE))
+        assert ei.value.status == T.TENT_ERR_INVALID
+        # the arena must hold the payload plus one alignment gap per rail
+    small_arena = W.Workload("exact", 10, 4096, [16384, 16384], ptr, W._extents(0, [0, 4096], [4096, 8192]),
+                             ptr.copy(), W._extents(1, [8192, 0], [4096, 8192]), W.make_rails([25000] * 3), "u8")
+    eng = H.Engine(small_arena, np.zeros(16384, np.uint8), np.zeros(16384, np.uint8))
+    try:
+        ctx2 = T.tent_create(4096, eng.arena.data_ptr(), 12288 + 256, 0)        # 3 rails need 12288 + 768
+        T.tent_register_segment(ctx2, eng.src.data_ptr(), eng.src.numel())
+        T.tent_register_segment(ctx2, eng.dst.data_ptr(), eng.dst.numel())
+        h = T.tent_declare(ctx2, small_arena.src_ptr, small_arena.src_ext, small_arena.dst_ptr, small_arena.dst_ext)
+        with pytest.raises(T.TentError) as ei:
+            T.tent_plan(ctx2, h, small_arena.rails, True, eng.stream)
+        assert ei.value.status == T.TENT_ERR_RANGE
+        T.tent_destroy(ctx2)
+    finally:
+        eng.close()
