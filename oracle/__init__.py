@@ -49,6 +49,8 @@ def lib():
         L.ora_coeffs.restype = None
         L.ora_stage_bases.restype = None
         L.ora_execute.restype = None
+        L.ora_sim_latency.restype = None
+        L.ora_probe.restype = None
         _lib = L
     return _lib
 
@@ -147,6 +149,59 @@ def retire(s: Slices, b: Binding, queued, budget, ids=None) -> np.ndarray:
                  _p(np.ascontiguousarray(queued, dtype=np.uint64)),
                  _p(np.ascontiguousarray(budget, dtype=np.uint64)), _p(done))
     return done
+
+
+def sim_latency(s: Slices, b: Binding, rails, true_bw_MBps, ids=None, tau=None) -> np.ndarray:
+    """Simulated end-to-end latency (ns) of the listed slices; entries of other slices are left alone."""
+    L = lib()
+    n = s.n if ids is None else ids.shape[0]
+    if tau is None:
+        tau = np.zeros(s.n, dtype=np.uint64)
+    L.ora_sim_latency(C.c_uint64(n), _p(ids), _p(s.len), _p(b.rail), _p(b.stage_off),
+                      _p(np.ascontiguousarray(rails["queued_bytes"], dtype=np.uint64)),
+                      _p(np.ascontiguousarray(rails["lat_ns"], dtype=np.uint32)),
+                      _p(np.ascontiguousarray(true_bw_MBps, dtype=np.uint32)), _p(tau))
+    return tau
+
+
+def probe(s: Slices, b: Binding, tau, params, bw_MBps, ids=None):
+    """Eq. 2 peak picking over the listed slices and the smoothed update; returns (new estimates, probes)."""
+    L = lib()
+    n = s.n if ids is None else ids.shape[0]
+    bw = np.ascontiguousarray(bw_MBps, dtype=np.uint32).copy()
+    out = np.zeros(bw.shape[0], dtype=np.uint32)
+    L.ora_probe(C.c_uint64(n), _p(ids), _p(s.len), _p(b.rail), _p(tau), C.c_uint32(bw.shape[0]),
+                _p(np.ascontiguousarray(params)), _p(bw), _p(out))
+    return bw, out
+
+
+def run_epochs_closed_loop(w, s: Slices, params, pools=None, staging=None):
+    """Re-planning with the telemetry loop closed: the planner's bandwidth estimates start at the
+    nominal values and follow the probes of the slices that completed in each epoch; the epochs'
+    own bandwidths act as the rails' true bandwidths (budgets and simulated latencies)."""
+    pending = np.arange(s.n, dtype=np.uint32)
+    est = w.rails["bw_MBps"].astype(np.uint32).copy()
+    records = []
+    for ep in list(w.epochs) + [w.drain]:
+        rails = ep.rails.copy()
+        rails["bw_MBps"] = est
+        rec = dict(pending=pending, est=est.copy(), rails=rails, status=OK, rail=None, stage_off=None,
+                   done_ids=pending[:0], probe=None, est_after=est.copy(), tau=None)
+        if pending.shape[0]:
+            b = bind(s.len, rails, ids=pending)
+            rec["status"] = b.status
+            if b.status == OK:
+                done = retire(s, b, rails["queued_bytes"], ep.budget, ids=pending).astype(bool)
+                done_ids = np.ascontiguousarray(pending[done])
+                tau = sim_latency(s, b, rails, ep.rails["bw_MBps"], ids=done_ids)
+                est, pr = probe(s, b, tau, params, est, ids=done_ids)
+                if pools is not None and done_ids.shape[0]:
+                    execute(w, s, b, pools, staging, ids=done_ids)
+                rec.update(rail=b.rail[pending].copy(), stage_off=b.stage_off[pending].copy(), done_ids=done_ids,
+                           probe=pr, est_after=est.copy(), tau=tau[done_ids].copy(), T=b.T, base=b.base)
+                pending = np.ascontiguousarray(pending[~done])
+        records.append(rec)
+    return records, pending
 
 
 def run_epochs(w, s: Slices, pools=None, staging=None):

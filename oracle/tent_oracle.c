@@ -221,3 +221,63 @@ uint64_t ora_retire(uint64_t n, const uint32_t *ids, const uint32_t *s_len,
     }
     return n_done;
 }
+
+/* ---- telemetry feedback (Section 4.2: Eq. 2 "peak picking" and the smoothing filter) --------
+ * Eq. 2: within a measurement window the bandwidth probe of rail d is
+ *     B_probe_d = min{ B_hw_d, max_i alpha * L_i / (tau_i - delta) }
+ * over the slices i that completed on d in the window (L_i bytes, tau_i end-to-end latency), and
+ * the estimate B_d follows the probes through an exponentially weighted moving average.
+ * Integer reading: tau and delta in ns, bandwidths in 1e6 B/s, so a sample is
+ *     floor(alpha_q8 * L * 1000 / (256 * (tau - delta)))        (alpha in Q8.8)
+ * a slice with tau <= delta counts as a sample at the hardware bandwidth; the update is
+ *     B_d <- max(1, (ewma_q8 * B_probe_d + (256 - ewma_q8) * B_d) >> 8)
+ * and a rail without a completed slice in the window keeps its estimate. */
+typedef struct { uint32_t hw_MBps; uint32_t alpha_q8; uint32_t delta_ns; uint32_t ewma_q8; } ora_probe_params;
+
+/* Rail simulator: latency of a slice = the rail's fixed latency plus the time the rail needs, at
+ * its true bandwidth, to drain the bytes queued before the plan, the slices staged ahead of this
+ * one and the slice itself.  ceil(x * 1000 / bw) is taken as (x / bw) * 1000 + ceil((x % bw) * 1000 / bw). */
+void ora_sim_latency(uint64_t n, const uint32_t *ids, const uint32_t *s_len, const uint32_t *s_rail,
+                     const uint64_t *s_stage_off, const uint64_t *queued, const uint32_t *lat_ns,
+                     const uint32_t *true_bw_MBps, uint64_t *tau_ns)
+{
+    for (uint64_t q = 0; q < n; ++q) {
+        uint64_t i = ids ? ids[q] : q;
+        uint32_t d = s_rail[i];
+        uint64_t x = queued[d] + s_stage_off[i] + s_len[i];
+        uint64_t bw = true_bw_MBps[d];
+        uint64_t whole = x / bw, rest = x % bw;
+        tau_ns[i] = lat_ns[d] + whole * 1000 + (rest * 1000 + bw - 1) / bw;
+    }
+}
+
+void ora_probe(uint64_t n, const uint32_t *ids, const uint32_t *s_len, const uint32_t *s_rail,
+               const uint64_t *tau_ns, uint32_t R, const ora_probe_params *pp,
+               uint32_t *bw_MBps /* in: estimate, out: updated estimate */,
+               uint32_t *probe_MBps /* out: B_probe, 0 where no slice completed */)
+{
+    uint64_t peak[64];
+    uint8_t seen[64];
+    for (uint32_t d = 0; d < R; ++d) { peak[d] = 0; seen[d] = 0; }
+    for (uint64_t q = 0; q < n; ++q) {
+        uint64_t i = ids ? ids[q] : q;
+        uint32_t d = s_rail[i];
+        uint64_t sample;
+        if (tau_ns[i] <= pp[d].delta_ns) {
+            sample = pp[d].hw_MBps;
+        } else {
+            uint64_t t = tau_ns[i] - pp[d].delta_ns;
+            sample = ((uint64_t)pp[d].alpha_q8 * s_len[i] * 1000) / (256 * t);
+        }
+        if (sample > peak[d]) peak[d] = sample;
+        seen[d] = 1;
+    }
+    for (uint32_t d = 0; d < R; ++d) {
+        probe_MBps[d] = 0;
+        if (!seen[d]) continue;
+        uint64_t probe = peak[d] < pp[d].hw_MBps ? peak[d] : pp[d].hw_MBps;
+        uint64_t next = ((uint64_t)pp[d].ewma_q8 * probe + (uint64_t)(256 - pp[d].ewma_q8) * bw_MBps[d]) >> 8;
+        probe_MBps[d] = (uint32_t)probe;
+        bw_MBps[d] = (uint32_t)(next ? next : 1);
+    }
+}

@@ -33,6 +33,11 @@ RAIL_DTYPE = np.dtype(
      "formats": ["<u4", "<u4", "<u8", "<u2", "<u2", "u1"],
      "offsets": [0, 4, 8, 16, 18, 20], "itemsize": 24})
 
+# struct { uint32 hw_MBps; uint32 alpha_q8; uint32 delta_ns; uint32 ewma_q8; }  -- 16 bytes
+PROBE_DTYPE = np.dtype(
+    {"names": ["hw_MBps", "alpha_q8", "delta_ns", "ewma_q8"], "formats": ["<u4"] * 4,
+     "offsets": [0, 4, 8, 12], "itemsize": 16})
+
 HEALTHY = 0
 DEGRADED = 1
 EXCLUDED = 2
@@ -52,6 +57,17 @@ def make_rails(bw_MBps, lat_ns=5000, queued=0, health=0, beta1_q8=256, penalty_q
     r["penalty_q8"] = penalty_q8
     r["health"] = health
     return r
+
+
+def make_probe_params(hw_MBps, alpha_q8=256, delta_ns=5000, ewma_q8=64):
+    """Per-rail calibration of the bandwidth probe: hardware bandwidth, alpha, delta, smoothing weight."""
+    hw = np.asarray(hw_MBps, dtype=np.uint64)
+    p = np.zeros(hw.shape[0], dtype=PROBE_DTYPE)
+    p["hw_MBps"] = hw
+    p["alpha_q8"] = alpha_q8
+    p["delta_ns"] = delta_ns
+    p["ewma_q8"] = ewma_q8
+    return p
 
 
 @dataclass
