@@ -189,6 +189,19 @@ def main():
     else:
         elapsed, tm = elapsed_piped, tm_piped
 
+    # Telemetry feedback (Eq. 2 probe + smoothed update) over one full window, outside the timed region:
+    # every slice of one batch BOUND, latencies from the rail simulator at the nominal bandwidths.
+    h_fb = batches[-1]
+    T.tent_reset(ctx, h_fb, stream)
+    T.tent_plan(ctx, h_fb, w.rails, want_info=False, stream=stream)
+    T.tent_sim_latency(ctx, h_fb, w.rails["bw_MBps"], stream)
+    torch.cuda.synchronize(dev)
+    T.tent_get_timings(ctx)
+    fb_params = W.make_probe_params(2 * w.rails["bw_MBps"].astype(np.uint64))
+    for _ in range(5):
+        T.tent_update_bandwidth(ctx, h_fb, fb_params, w.rails, stream)
+    fb_ms, fb_n = T.tent_get_timings(ctx)["feedback"]
+
     # Plain copy of known size (1 GiB read + 1 GiB written by one elementwise kernel), outside the
     # timed region: the practical copy ceiling of the box and the reference dispatch that scales
     # hardware byte counters when this script runs under a counter-collecting profiler.
@@ -232,6 +245,8 @@ def main():
         "stage_ms_single_stream": {k: round(v[0] / max(1, args.steps), 4) for k, v in tm_single.items()},
         "execute_GBps": round(4 * w.payload / ((gather_avg + scatter_avg) * 1e-3) / 1e9, 2),
         "declare_ms": round(declare_ms, 3),
+        "feedback": {"window_slices": n_slices, "ms_per_window": round(fb_ms / max(1, fb_n), 4),
+                     "bytes_per_slice": 17},
         "plain_copy_GBps": round(plain_copy_GBps, 2),
         "roofline": {"bound": "hbm", "kernel": "copy_kernel<gather>" if dom == "gather" else "scatter_ordered_kernel", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),

@@ -88,6 +88,14 @@ typedef struct {
 
 enum { TENT_SLICE_PENDING = 0, TENT_SLICE_BOUND = 1, TENT_SLICE_DONE = 2 };
 
+/* Calibration of one rail's bandwidth probe (Section 4.2, Eq. 2 and the smoothing filter). */
+typedef struct {
+    uint32_t hw_MBps;          /* B_hw: bandwidth reported by the hardware, 10^6 bytes/s            */
+    uint32_t alpha_q8;         /* alpha in Q8.8 (256 = 1.0), at most 65535                          */
+    uint32_t delta_ns;         /* delta: latency that carries no rate information                   */
+    uint32_t ewma_q8;          /* weight of the new probe in Q8.8, 0..256 (256 replaces the estimate) */
+} tent_probe_params;
+
 /* One row of the slice table: the task triple <path, offset, length> of
  * Algorithm 1 plus the bookkeeping of the staging hop. */
 typedef struct {
@@ -108,7 +116,8 @@ enum {
     TENT_T_BIND        = 4,    /* rail assignment                                                 */
     TENT_T_GATHER      = 5,    /* paged source -> staging                                         */
     TENT_T_SCATTER     = 6,    /* staging -> destination                                          */
-    TENT_T_COUNT       = 7
+    TENT_T_FEEDBACK    = 7,    /* bandwidth probe over the completed slices (tent_update_bandwidth) */
+    TENT_T_COUNT       = 8
 };
 
 /* Create an engine on the current HIP device.  `cfg` is host memory. */
@@ -172,6 +181,35 @@ int tent_plan(tent_ctx *ctx, tent_batch_t batch, const tent_rail_state *rails, u
  */
 int tent_sim_advance(tent_ctx *ctx, tent_batch_t batch, const uint64_t *budget_bytes,
                      uint64_t *n_done, void *stream);
+
+/*
+ * Rail simulator, second half (not an operation of the paper): the end-to-end latency of
+ * every BOUND slice, tau = lat_ns_d + ceil((queued_bytes_d + stage_off + len) * 1000 / true_bw_MBps[d])
+ * nanoseconds, i.e. the rail drains what was queued before the last tent_plan, then the slices
+ * staged ahead of this one, then the slice, at its true bandwidth.  lat_ns and queued_bytes are
+ * those of the last tent_plan.  `true_bw_MBps` is host memory with n_rails entries, all > 0.
+ * Call it after tent_sim_advance and before tent_execute.  Only enqueues on `stream`.
+ * TENT_ERR_RANGE when queued bytes plus payload reach 2^53.
+ */
+int tent_sim_latency(tent_ctx *ctx, tent_batch_t batch, const uint32_t *true_bw_MBps, void *stream);
+
+/*
+ * Telemetry feedback (Section 4.2, Eq. 2): over the measurement window formed by the BOUND
+ * slices of the batch and their recorded latencies,
+ *     B_probe_d = min{ hw_MBps_d, max_i floor(alpha_q8 * len_i * 1000 / (256 * (tau_i - delta_ns))) }
+ * (a slice with tau_i <= delta_ns counts as a sample at hw_MBps_d), and the estimate follows
+ *     bw_MBps_d <- max(1, (ewma_q8 * B_probe_d + (256 - ewma_q8) * bw_MBps_d) >> 8).
+ * A rail without a BOUND slice keeps its estimate.  `params` (host, n_rails entries) is read,
+ * `rails` (host, n_rails entries) has its bw_MBps fields updated in place, `probe_MBps_out` (host,
+ * n_rails entries or NULL) receives B_probe_d, 0 where the rail had no sample.  n_rails must equal
+ * the rail count of the last tent_plan.  Waits for `stream`.
+ */
+int tent_update_bandwidth(tent_ctx *ctx, tent_batch_t batch, const tent_probe_params *params,
+                          tent_rail_state *rails, uint32_t n_rails, uint32_t *probe_MBps_out, void *stream);
+
+/* Copy the recorded slice latencies (ns, one per slice; meaningful for slices that were BOUND at
+ * the last tent_sim_latency) to host memory for verification.  Waits for the device. */
+int tent_get_latencies(tent_ctx *ctx, tent_batch_t batch, uint64_t *host_out, uint64_t cap);
 
 /*
  * Move every BOUND slice: gather its bytes from the paged source extents into

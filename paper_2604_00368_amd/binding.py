@@ -11,7 +11,7 @@ import os
 
 import numpy as np
 
-from .workloads import EXTENT_DTYPE, RAIL_DTYPE
+from .workloads import EXTENT_DTYPE, PROBE_DTYPE, RAIL_DTYPE
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libtent.so")
@@ -21,10 +21,10 @@ TENT_ERR_INVALID, TENT_ERR_RANGE, TENT_ERR_STATE, TENT_ERR_NOMEM, TENT_ERR_HIP =
 TENT_MAX_RAILS = 64
 TENT_FLAG_SKIP_OVERLAP_CHECK, TENT_FLAG_PROFILE, TENT_FLAG_SERIAL_BINDING = 1, 2, 4
 TENT_SLICE_PENDING, TENT_SLICE_BOUND, TENT_SLICE_DONE = 0, 1, 2
-TENT_T_NAMES = ["extent_scan", "slice_scan", "expand", "compact", "bind", "gather", "scatter"]
+TENT_T_NAMES = ["extent_scan", "slice_scan", "expand", "compact", "bind", "gather", "scatter", "feedback"]
 
 EXPORTS = ["tent_create", "tent_destroy", "tent_register_segment", "tent_declare", "tent_plan",
-           "tent_sim_advance", "tent_execute", "tent_poll", "tent_reset", "tent_slice_count",
+           "tent_sim_advance", "tent_sim_latency", "tent_update_bandwidth", "tent_get_latencies", "tent_execute", "tent_poll", "tent_reset", "tent_slice_count",
            "tent_get_plan", "tent_get_timings", "tent_release", "tent_strerror"]
 
 
@@ -74,6 +74,10 @@ def lib():
         L.tent_plan.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.POINTER(tent_plan_info),
                                 C.c_void_p]
         L.tent_sim_advance.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.POINTER(C.c_uint64), C.c_void_p]
+        L.tent_sim_latency.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
+        L.tent_update_bandwidth.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
+                                            C.c_void_p]
+        L.tent_get_latencies.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
         L.tent_execute.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
         L.tent_poll.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64), C.c_void_p]
         L.tent_reset.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
@@ -147,6 +151,28 @@ def tent_sim_advance(ctx, batch: int, budget_bytes, stream=None) -> int:
     n = C.c_uint64()
     _check(lib().tent_sim_advance(ctx, batch, bp, C.byref(n), _stream(stream)), "tent_sim_advance")
     return n.value
+
+
+def tent_sim_latency(ctx, batch: int, true_bw_MBps, stream=None):
+    b, bp = _host(true_bw_MBps, np.uint32)
+    _check(lib().tent_sim_latency(ctx, batch, bp, _stream(stream)), "tent_sim_latency")
+
+
+def tent_update_bandwidth(ctx, batch: int, params, rails, stream=None):
+    """Returns (rails with updated bw_MBps, probe_MBps); the input arrays are not modified."""
+    p, pp = _host(params, PROBE_DTYPE)
+    r = np.ascontiguousarray(rails, dtype=RAIL_DTYPE).copy()
+    probe = np.zeros(r.shape[0], dtype=np.uint32)
+    _check(lib().tent_update_bandwidth(ctx, batch, pp, r.ctypes.data_as(C.c_void_p), r.shape[0],
+                                       probe.ctypes.data_as(C.c_void_p), _stream(stream)), "tent_update_bandwidth")
+    return r, probe
+
+
+def tent_get_latencies(ctx, batch: int) -> np.ndarray:
+    n = tent_slice_count(ctx, batch)
+    out = np.zeros(n, dtype=np.uint64)
+    _check(lib().tent_get_latencies(ctx, batch, out.ctypes.data_as(C.c_void_p), n), "tent_get_latencies")
+    return out
 
 
 def tent_execute(ctx, batch: int, stream=None):

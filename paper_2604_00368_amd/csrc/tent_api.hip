@@ -21,6 +21,7 @@ struct Batch {
     uint32_t generation = 0;
     uint64_t payload = 0;
     RailParams last_rails{};     // telemetry of the last plan (for the rail simulator)
+    uint32_t last_lat_ns[TENT_MAX_RAILS] = {};
     BatchDev dev{};
     std::vector<void*> allocs;
 };
@@ -369,6 +370,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_rail, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_stage_off, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_state, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_tau, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_rec, n_slices);
     BatchDev* self_dev = nullptr;
     if (rc == TENT_OK) rc = dev_alloc(b, &self_dev, 1);
@@ -468,6 +470,7 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     }
     b->planned = true;
     b->last_rails = rp;
+    for (uint32_t r = 0; r < n_rails; ++r) b->last_lat_ns[r] = rails[r].lat_ns;
 
     if (info) {
         HIP_TRY(hipMemcpyAsync(ctx->host_plan, d.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
@@ -506,6 +509,76 @@ int tent_sim_advance(tent_ctx* ctx, tent_batch_t batch, const uint64_t* budget_b
     HIP_TRY(hipMemcpyAsync(ctx->host_plan, b->dev.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     if (n_done) *n_done = ctx->host_plan->n_done;
+    return TENT_OK;
+}
+
+int tent_sim_latency(tent_ctx* ctx, tent_batch_t batch, const uint32_t* true_bw_MBps, void* stream)
+{
+    if (!ctx || !true_bw_MBps) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (!b->planned) return TENT_ERR_STATE;
+    LatencyParams lp;
+    std::memset(&lp, 0, sizeof(lp));
+    uint64_t max_q = 0;
+    for (uint32_t d = 0; d < TENT_MAX_RAILS; ++d) lp.bw_MBps[d] = 1;
+    for (uint32_t d = 0; d < b->last_rails.n_rails; ++d) {
+        if (true_bw_MBps[d] == 0) return TENT_ERR_RANGE;
+        lp.queued[d] = b->last_rails.A[d];
+        lp.lat_ns[d] = b->last_lat_ns[d];
+        lp.bw_MBps[d] = true_bw_MBps[d];
+        max_q = std::max(max_q, lp.queued[d]);
+    }
+    if (max_q >= (1ull << 53) || b->payload >= (1ull << 53) || max_q + b->payload >= (1ull << 53)) return TENT_ERR_RANGE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    HIP_TRY(launch_sim_latency(b->dev, lp, static_cast<hipStream_t>(stream)));
+    return TENT_OK;
+}
+
+int tent_update_bandwidth(tent_ctx* ctx, tent_batch_t batch, const tent_probe_params* params, tent_rail_state* rails,
+                          uint32_t n_rails, uint32_t* probe_MBps_out, void* stream)
+{
+    if (!ctx || !params || !rails) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (!b->planned) return TENT_ERR_STATE;
+    if (n_rails != b->last_rails.n_rails) return TENT_ERR_RANGE;
+    ProbeParams pp;
+    std::memset(&pp, 0, sizeof(pp));
+    pp.n_rails = n_rails;
+    for (uint32_t d = 0; d < n_rails; ++d) {
+        if (params[d].alpha_q8 > 65535u || params[d].ewma_q8 > 256u) return TENT_ERR_RANGE;
+        pp.cal[d] = params[d];
+        pp.bw_MBps[d] = rails[d].bw_MBps;
+    }
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        StageTimer t(ctx, TENT_T_FEEDBACK, s);
+        HIP_TRY(launch_probe(b->dev, pp, s));
+    }
+    HIP_TRY(hipMemcpyAsync(ctx->host_plan, b->dev.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    for (uint32_t d = 0; d < n_rails; ++d) {
+        rails[d].bw_MBps = ctx->host_plan->bw_next[d];
+        if (probe_MBps_out) probe_MBps_out[d] = ctx->host_plan->probe[d];
+    }
+    return TENT_OK;
+}
+
+int tent_get_latencies(tent_ctx* ctx, tent_batch_t batch, uint64_t* host_out, uint64_t cap)
+{
+    if (!ctx || !host_out) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (!b->planned) return TENT_ERR_STATE;
+    if (cap < b->dev.n_slices) return TENT_ERR_RANGE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(host_out, b->dev.s_tau, b->dev.n_slices * sizeof(uint64_t), hipMemcpyDeviceToHost));
     return TENT_OK;
 }
 

@@ -21,6 +21,20 @@ struct RailParams {
     uint32_t pad;
 };
 
+// Rail simulator inputs for slice latencies.
+struct LatencyParams {
+    uint64_t queued[TENT_MAX_RAILS];
+    uint32_t lat_ns[TENT_MAX_RAILS];
+    uint32_t bw_MBps[TENT_MAX_RAILS];   // true bandwidth, > 0
+};
+
+// Bandwidth-probe calibration and current estimates.
+struct ProbeParams {
+    tent_probe_params cal[TENT_MAX_RAILS];
+    uint32_t bw_MBps[TENT_MAX_RAILS];   // estimates before the window
+    uint32_t n_rails;
+};
+
 struct BudgetParams {
     uint64_t queued[TENT_MAX_RAILS];
     uint64_t budget[TENT_MAX_RAILS];
@@ -37,6 +51,9 @@ struct PlanState {
     uint64_t n_runs;                      // runs of equal-length slices seen by the plan
     uint64_t n_done;                      // tent_sim_advance: slices that stayed bound
     uint64_t n_remaining;                 // tent_poll: slices not DONE
+    uint64_t peak[TENT_MAX_RAILS];        // bandwidth probe: 1 + best sample of the window, 0 = no sample
+    uint32_t probe[TENT_MAX_RAILS];       // B_probe per rail (0 = no sample)
+    uint32_t bw_next[TENT_MAX_RAILS];     // smoothed estimate after the window
 };
 
 // What a copy workgroup needs to know about its slice, in one 16-byte scalar load.
@@ -69,6 +86,7 @@ struct BatchDev {
     uint32_t* s_rail;
     uint64_t* s_stage_off;
     uint8_t*  s_state;
+    uint64_t* s_tau;               // recorded end-to-end latency in ns (rail simulator / telemetry)
 
     struct SliceRec* s_rec;        // packed copy record per slice, rebuilt by every tent_execute
     const BatchDev* self;          // device copy of this structure (generic copy path)
@@ -126,6 +144,8 @@ hipError_t launch_mark_done(const BatchDev& b, hipStream_t s);
 hipError_t launch_retire(const BatchDev& b, const BudgetParams& bp, hipStream_t s);
 hipError_t launch_count_remaining(const BatchDev& b, hipStream_t s);
 hipError_t launch_reset(const BatchDev& b, hipStream_t s);
+hipError_t launch_sim_latency(const BatchDev& b, const LatencyParams& lp, hipStream_t s);
+hipError_t launch_probe(const BatchDev& b, const ProbeParams& pp, hipStream_t s);
 
 uint64_t scan_partials_capacity(uint64_t n);
 

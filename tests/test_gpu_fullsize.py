@@ -143,3 +143,14 @@ def test_full_size_replanning(H, oracle):
         del eng
         gc.collect()
         torch.cuda.empty_cache()
+
+
+def test_full_size_closed_loop(H, oracle):
+    # config 4 with the telemetry loop closed (plan, rails, latencies, probes and estimates per epoch)
+    import test_gpu_parity as P
+    print("full-size closed loop", flush=True)
+    w = W.replanning()
+    params = W.make_probe_params(2 * w.rails["bw_MBps"].astype(np.uint64), ewma_q8=64)
+    P.run_closed_loop_and_compare(H, oracle, w, params, bytes_too=False)
+    gc.collect()
+    torch.cuda.empty_cache()

@@ -317,3 +317,79 @@ def test_degenerate_batches(H, oracle):
         T.tent_destroy(ctx2)
     finally:
         eng.close()
+
+
+def run_closed_loop_and_compare(H, oracle, w, params, bytes_too=True):
+    from paper_2604_00368_amd import binding as T
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    src = W.fill_numpy(w, 0) if bytes_too else None
+    dst0 = W.fill_numpy(w, 1) if bytes_too else None
+    dst_want = dst0.copy() if bytes_too else None
+    staging_want = np.zeros(w.staging_bytes, dtype=np.uint8) if bytes_too else None
+    records, left = oracle.run_epochs_closed_loop(w, s, params, [src, dst_want] if bytes_too else None, staging_want)
+    assert left.shape[0] == 0
+    eng = H.Engine(w, src, dst0) if bytes_too else H.Engine(w)
+    try:
+        eng.declare()
+        est = w.rails["bw_MBps"].astype(np.uint32).copy()
+        for e, (rec, ep) in enumerate(zip(records, list(w.epochs) + [w.drain])):
+            print("closed-loop epoch", e, "pending", rec["pending"].shape[0], flush=True)
+            assert np.array_equal(est, rec["est"])
+            rails = ep.rails.copy()
+            rails["bw_MBps"] = est
+            st, info = eng.plan(rails=rails)
+            assert st == 0 and info.n_slices == rec["pending"].shape[0]
+            n_done = T.tent_sim_advance(eng.ctx, eng.batch, ep.budget, eng.stream)
+            assert n_done == rec["done_ids"].shape[0]
+            T.tent_sim_latency(eng.ctx, eng.batch, ep.rails["bw_MBps"], eng.stream)
+            new_rails, probe = T.tent_update_bandwidth(eng.ctx, eng.batch, params, rails, eng.stream)
+            if rec["tau"] is not None:
+                tab = eng.table()
+                assert np.array_equal(tab["rail"][rec["pending"]], rec["rail"])
+                tau = T.tent_get_latencies(eng.ctx, eng.batch)
+                assert np.array_equal(tau[rec["done_ids"]], rec["tau"])
+                assert np.array_equal(probe, rec["probe"])
+            else:
+                assert not probe.any()
+            assert np.array_equal(new_rails["bw_MBps"], rec["est_after"])
+            assert np.array_equal(new_rails["queued_bytes"], rails["queued_bytes"])     # only bw_MBps changes
+            est = new_rails["bw_MBps"].astype(np.uint32)
+            eng.execute()
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        if bytes_too:
+            assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+            assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+        return eng
+    finally:
+        eng.close()
+
+
+def test_telemetry_feedback_closed_loop(H, oracle):
+    from paper_2604_00368_amd import binding as T
+    w = W.small_variant("replanning")
+    params = W.make_probe_params(2 * w.rails["bw_MBps"].astype(np.uint64), ewma_q8=128)
+    run_closed_loop_and_compare(H, oracle, w, params)
+    # other calibrations: alpha != 1, hardware cap below the true bandwidth, delta above some latencies
+    rng = np.random.Generator(np.random.PCG64(8))
+    R = w.rails.shape[0]
+    params = W.make_probe_params(rng.integers(20000, 90000, size=R), alpha_q8=rng.integers(128, 700, size=R),
+                                 delta_ns=rng.integers(0, 40000, size=R), ewma_q8=rng.integers(0, 257, size=R))
+    run_closed_loop_and_compare(H, oracle, w, params)
+    # argument errors
+    with H.Engine(w, W.fill_numpy(w, 0), W.fill_numpy(w, 1)) as eng:
+        h = eng.declare()
+        with pytest.raises(T.TentError) as ei:
+            T.tent_sim_latency(eng.ctx, h, w.rails["bw_MBps"], eng.stream)
+        assert ei.value.status == T.TENT_ERR_STATE
+        eng.plan()
+        bad = w.rails["bw_MBps"].copy(); bad[2] = 0
+        with pytest.raises(T.TentError) as ei:
+            T.tent_sim_latency(eng.ctx, h, bad, eng.stream)
+        assert ei.value.status == T.TENT_ERR_RANGE
+        with pytest.raises(T.TentError) as ei:
+            T.tent_update_bandwidth(eng.ctx, h, params[:3], w.rails[:3], eng.stream)
+        assert ei.value.status == T.TENT_ERR_RANGE
+        p2 = params.copy(); p2["ewma_q8"][0] = 300
+        with pytest.raises(T.TentError) as ei:
+            T.tent_update_bandwidth(eng.ctx, h, p2, w.rails, eng.stream)
+        assert ei.value.status == T.TENT_ERR_RANGE
