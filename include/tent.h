@@ -74,7 +74,7 @@ typedef struct {
     uint64_t queued_bytes;     /* A_d: bytes already in flight on the rail                        */
     uint16_t beta1_q8;         /* beta1_d in Q8.8 (256 = 1.0)                                     */
     uint16_t penalty_q8;       /* topology penalty P_d in Q8.8 (256 = 1.0)                        */
-    uint8_t  health;           /* 0 healthy, 1 degraded (treated as healthy), 2 excluded          */
+    uint8_t  health;           /* 0 healthy, 1 degraded (cost counts twice), 2 excluded (never chosen) */
 } tent_rail_state;
 
 typedef struct {
@@ -156,7 +156,8 @@ int tent_declare(tent_ctx *ctx, uint32_t n_desc,
  * rail (health != 2) with the smallest
  *     c0_d + (((A_d + len) * c1_d) >> 16),
  *     c1_d = floor(1e6 * beta1_q8 * penalty_q8 / bw_MBps),  c0_d = (lat_ns*1000*penalty_q8) >> 8
- * (picoseconds; ties to the lowest rail index), after which A_d += len.  The
+ * (picoseconds; ties to the lowest rail index; both coefficients are doubled for a rail with
+ * health = 1: Section 4.3, a degraded rail keeps half its weight), after which A_d += len.  The
  * slice's staging offset is the number of bytes bound to that rail earlier in
  * this call.  Rail d's staging region starts at the sum over d' < d of the
  * rail totals rounded up to 256 bytes.

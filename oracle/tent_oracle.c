@@ -30,6 +30,8 @@
  *   c1_d   = floor(1e6 * beta1_q8 * penalty_q8 / bw_MBps)   picoseconds per byte, Q16
  *   c0_d   = (lat_ns * 1000 * penalty_q8) >> 8              picoseconds
  *   cost_d = c0_d + (((A_d + L) * c1_d) >> 16)
+ *   a DEGRADED rail (Section 4.3: "0.5x weight penalty but remains eligible") has both
+ *   coefficients doubled, i.e. its predicted cost counts twice;
  *   ties go to the lowest rail index; slices are bound in ascending index order;
  *   a rail's staging region packs its slices in bind order; region bases are the
  *   exclusive sum of the rails' byte totals, each rounded up to 256 bytes.
@@ -45,7 +47,7 @@ typedef struct {
     uint64_t queued_bytes;
     uint16_t beta1_q8;
     uint16_t penalty_q8;
-    uint8_t  health;      /* 2 = excluded */
+    uint8_t  health;      /* 0 healthy, 1 degraded, 2 excluded */
 } ora_rail;
 
 enum { ORA_OK = 0, ORA_DEFER = 1, ORA_BAD = -1 };
@@ -98,6 +100,10 @@ void ora_coeffs(const ora_rail *rails, uint32_t R,
         uint64_t bp = (uint64_t)rails[d].beta1_q8 * rails[d].penalty_q8;
         c1[d] = rails[d].bw_MBps ? (1000000ull * bp) / rails[d].bw_MBps : ~0ull;
         c0[d] = ((uint64_t)rails[d].lat_ns * 1000ull * rails[d].penalty_q8) >> 8;
+        if (rails[d].health == 1) {      /* degraded: half weight = twice the cost, still eligible */
+            c1[d] *= 2;
+            c0[d] *= 2;
+        }
         excluded[d] = (rails[d].health == 2);
         A[d] = rails[d].queued_bytes;
     }

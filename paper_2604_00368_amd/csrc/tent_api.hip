@@ -210,10 +210,12 @@ int convert_rails(const tent_rail_state* rails, uint32_t n_rails, uint64_t pendi
         const tent_rail_state& r = rails[d];
         if (r.bw_MBps == 0) return TENT_ERR_RANGE;
         const uint64_t bp = (uint64_t)r.beta1_q8 * r.penalty_q8;
-        const uint64_t c1 = (1000000ull * bp) / r.bw_MBps;
+        // a degraded rail keeps half its weight: its predicted cost counts twice (Section 4.3)
+        const uint64_t weight = r.health == 1 ? 2 : 1;
+        const uint64_t c1 = weight * ((1000000ull * bp) / r.bw_MBps);
         if (c1 >= (1ull << 32)) return TENT_ERR_RANGE;
         rp->c1[d] = c1;
-        rp->c0[d] = ((uint64_t)r.lat_ns * 1000ull * r.penalty_q8) >> 8;
+        rp->c0[d] = weight * (((uint64_t)r.lat_ns * 1000ull * r.penalty_q8) >> 8);
         rp->A[d] = r.queued_bytes;
         if (r.health != 2) {
             rp->admitted |= 1ull << d;

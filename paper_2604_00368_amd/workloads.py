@@ -300,7 +300,8 @@ def ragged(seed: int, n_desc: int = 24, max_len: int = 200_000, max_ext: int = 4
     sp, se, spool = layout(SRC_SEG)
     dp, de, dpool = layout(DST_SEG)
     bw = rng.integers(1000, 400000, size=n_rails)
-    health = np.where(rng.random(n_rails) < 0.25, EXCLUDED, HEALTHY).astype(np.uint8)
+    u = rng.random(n_rails)
+    health = np.where(u < 0.25, EXCLUDED, np.where(u < 0.45, DEGRADED, HEALTHY)).astype(np.uint8)
     if (health == EXCLUDED).all():
         health[int(rng.integers(0, n_rails))] = HEALTHY
     rails = make_rails(bw, lat_ns=rng.integers(0, 20000, size=n_rails),

@@ -97,9 +97,12 @@ def _runs_workload(rng, kind):
         lat = rng.integers(0, 2**32 - 1, size=R)
     if kind == 4:                                              # long queues
         queued = rng.integers(0, 1 << 31, size=R)                # (max A + payload) * max c1 stays below 2^63
-    health = np.where(rng.random(R) < 0.2, 2, 0).astype(np.uint8)
+    u = rng.random(R)
+    health = np.where(u < 0.2, 2, np.where(u < 0.4, 1, 0)).astype(np.uint8)       # excluded / degraded / healthy
     if (health == 2).all():
         health[0] = 0
+    if kind == 3:
+        pen = np.minimum(pen, 500)               # doubled coefficients of degraded rails must stay in range
     rails = W.make_rails(bw, lat_ns=lat, queued=queued, health=health, beta1_q8=b1, penalty_q8=pen)
     return W.Workload("runs", 0, S, [total, total], ptr, W._extents(0, off, lens), ptr.copy(),
                       W._extents(1, off, lens), rails, "u8")

@@ -324,3 +324,25 @@ def test_replanning_epochs(oracle):
             rail_full = np.zeros(s.n, np.uint32); rail_full[r["pending"]] = r["rail"]
             so_full = np.zeros(s.n, np.uint64); so_full[r["pending"]] = r["stage_off"]
             check_greedy_choice(s.len, ep.rails, rail_full, so_full, c0, c1, exc, ids=r["pending"])
+
+
+def test_degraded_rail_costs_twice(oracle):
+    # Section 4.3: a DEGRADED rail "receives a 0.5x weight penalty but remains eligible"
+    healthy = W.make_rails([50000, 50000])
+    degraded = W.make_rails([50000, 50000], health=[1, 0])
+    c0h, c1h, exh, _ = oracle.coeffs(healthy)
+    c0d, c1d, exd, _ = oracle.coeffs(degraded)
+    assert int(c0d[0]) == 2 * int(c0h[0]) and int(c1d[0]) == 2 * int(c1h[0]) and not exd[0]
+    assert int(c0d[1]) == int(c0h[1]) and int(c1d[1]) == int(c1h[1])
+    # the degraded rail still takes traffic, about half as many bytes as its healthy twin would
+    w = one_transfer(600 * 64 * KiB, 64 * KiB, degraded)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    b = oracle.bind(s.len, degraded)
+    share = int(b.T[0]) / w.payload
+    assert 0.30 < share < 0.36                                   # 1/3 of the bytes: weights 1 : 2
+    c0, c1, ex, _ = oracle.coeffs(degraded)
+    check_greedy_choice(s.len, degraded, b.rail, b.stage_off, c0, c1, ex)
+    # with a healthy rail of half the bandwidth and half... the latency term doubles too: compare with P = 2
+    same = W.make_rails([50000, 50000], penalty_q8=[512, 256])
+    b2 = oracle.bind(s.len, same)
+    assert np.array_equal(b.rail, b2.rail)
