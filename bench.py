@@ -54,7 +54,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="kv_migration",
-                    choices=["tiny", "kv_migration", "rl_params", "many_small", "many_small_x6"])
+                    choices=["tiny", "kv_migration", "rl_params", "many_small", "many_small_x6", "kv_skewed"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial-binding", action="store_true")
     ap.add_argument("--single-stream", action="store_true",
@@ -67,6 +67,8 @@ def make_workload(name):
     from paper_2604_00368_amd import workloads as W
     if name == "many_small_x6":
         return W.many_small(layers=6)
+    if name == "kv_skewed":          # a quarter of config 2 with every page at an odd address (generic copy path)
+        return W.kv_migration(n_req=8, skew=(3, 5))
     return W.CONFIGS[name]()
 
 

@@ -12,16 +12,17 @@
 // sustains more bandwidth than persistent workgroups that loop over larger chunks.  The paged-side
 // address comes from the tile table built by the splitter (one 8-byte entry per tile of 1-4 KiB),
 // looked up per lane, so extent boundaries inside a block cost nothing as long as they fall on
-// tile boundaries.  A block that holds a flagged tile (extent boundary inside the tile, or an
-// address that is not 16-byte aligned), a misaligned staging address or a ragged tail takes the
-// generic path, which walks the extent list and peels unaligned bytes.
-#include <cstdlib>
-
+// tile boundaries, at any address alignment.  A wavefront that meets a flagged tile (extent
+// boundary inside the tile) or a slice that ends inside a lane's vector takes the
+// generic path, which walks the extent list, aligns its stores and loads at any alignment.
 #include "tent_internal.h"
 
 namespace tent {
 
 typedef uint32_t vec4u __attribute__((ext_vector_type(4)));
+// 16-byte vector at any address: gfx950 global loads and stores need no alignment, and the compiler
+// emits a single dwordx4 access for this type.
+typedef vec4u vec4u_any __attribute__((aligned(1)));
 
 // Wavefront-cooperative byte copy (64 lanes).
 __device__ __forceinline__ void copy_bytes(uint8_t* __restrict__ dst, const uint8_t* __restrict__ src, uint64_t n)
@@ -29,23 +30,24 @@ __device__ __forceinline__ void copy_bytes(uint8_t* __restrict__ dst, const uint
     for (uint64_t x = threadIdx.x & 63; x < n; x += 64) dst[x] = src[x];
 }
 
-// Wavefront-cooperative copy of n bytes, any alignment.
+// Wavefront-cooperative copy of n bytes, any alignment: bytes up to the first 16-byte boundary of
+// the destination, then aligned 16-byte stores fed by 16-byte loads at whatever alignment the
+// source has (gfx950 global loads need no alignment), then the remaining bytes.
 __device__ __forceinline__ void copy_piece(uint8_t* dst, const uint8_t* src, uint64_t n)
 {
-    const uint64_t d = (uint64_t)dst, s = (uint64_t)src;
-    if (((d ^ s) & 15) == 0) {
-        uint64_t head = (16 - (d & 15)) & 15;
-        if (head > n) head = n;
-        copy_bytes(dst, src, head);
-        const uint64_t nvec = (n - head) >> 4;
-        vec4u* dv = (vec4u*)(dst + head);
-        const vec4u* sv = (const vec4u*)(src + head);
-        for (uint64_t v = threadIdx.x & 63; v < nvec; v += 64) dv[v] = sv[v];
-        const uint64_t done = head + (nvec << 4);
-        copy_bytes(dst + done, src + done, n - done);
-    } else {
-        copy_bytes(dst, src, n);
+    uint64_t head = (16 - ((uint64_t)dst & 15)) & 15;
+    if (head > n) head = n;
+    copy_bytes(dst, src, head);
+    const uint64_t nvec = (n - head) >> 4;
+    vec4u* dv = (vec4u*)(dst + head);
+    const uint8_t* sb = src + head;
+    for (uint64_t v = threadIdx.x & 63; v < nvec; v += 64) {
+        vec4u x;
+        __builtin_memcpy(&x, sb + (v << 4), 16);
+        dv[v] = x;
     }
+    const uint64_t done = head + (nvec << 4);
+    copy_bytes(dst + done, src + done, n - done);
 }
 
 __device__ __forceinline__ uint32_t last_not_above32(const uint64_t* a, uint32_t lo, uint32_t hi, uint64_t key)
@@ -105,7 +107,7 @@ __global__ void __launch_bounds__(kLanes) copy_kernel(const SliceRec* __restrict
     const SliceRec r = rec[i];
     const bool in_range = x + 16 <= r.len;
     const bool ragged = x < r.len && !in_range;              // slice ends inside this lane's vector
-    const bool bad = ragged || (x < r.len && ((entry & kTileSlow) || (r.lin & 15)));
+    const bool bad = ragged || (x < r.len && (entry & kTileSlow));
     if (__any(bad)) {
         const uint32_t wave_lo = c * kBlockBytes + (threadIdx.x & ~63u) * 16;
         const uint32_t wave_hi = wave_lo + 1024 < r.len ? wave_lo + 1024 : r.len;
@@ -116,11 +118,11 @@ __global__ void __launch_bounds__(kLanes) copy_kernel(const SliceRec* __restrict
     const uint64_t paged = entry + (x & ((1u << tile_shift) - 1));
     const uint64_t mine = r.lin + x;
     if (kGather) {
-        vec4u v = __builtin_nontemporal_load((const vec4u*)paged);
-        __builtin_nontemporal_store(v, (vec4u*)mine);
+        vec4u v = __builtin_nontemporal_load((const vec4u_any*)paged);
+        __builtin_nontemporal_store(v, (vec4u_any*)mine);
     } else {
-        vec4u v = __builtin_nontemporal_load((const vec4u*)mine);
-        __builtin_nontemporal_store(v, (vec4u*)paged);
+        vec4u v = __builtin_nontemporal_load((const vec4u_any*)mine);
+        __builtin_nontemporal_store(v, (vec4u_any*)paged);
     }
 }
 
@@ -148,7 +150,7 @@ static hipError_t launch_copy_lanes(const BatchDev& b, hipStream_t s)
 // Scatter in ascending destination address: workgroup w moves 4 KiB of the destination bytes laid
 // end to end in address order, so consecutive workgroups write consecutive destination addresses
 // while the reads hop between staging regions (HBM tolerates scattered reads better than scattered
-// writes).  Only used when every tile is whole and 16-byte aligned on both sides.
+// writes).  Only used when every tile is whole (no extent boundary inside a tile).
 __global__ void __launch_bounds__(256) scatter_ordered_kernel(const uint64_t* __restrict__ sc_dst,
                                                               const uint64_t* __restrict__ sc_lin,
                                                               uint64_t n_tiles, uint32_t tile_shift)
@@ -161,8 +163,8 @@ __global__ void __launch_bounds__(256) scatter_ordered_kernel(const uint64_t* __
     const uint64_t dst = sc_dst[q];
     if (lin == 0) return;
     const uint64_t in_tile = at & ((1ull << tile_shift) - 1);
-    vec4u v = __builtin_nontemporal_load((const vec4u*)(lin + in_tile));
-    __builtin_nontemporal_store(v, (vec4u*)(dst + in_tile));
+    vec4u v = __builtin_nontemporal_load((const vec4u_any*)(lin + in_tile));
+    __builtin_nontemporal_store(v, (vec4u_any*)(dst + in_tile));
 }
 
 hipError_t launch_scatter_ordered(const BatchDev& b, hipStream_t s)
@@ -182,10 +184,7 @@ hipError_t launch_scatter_ordered(const BatchDev& b, hipStream_t s)
 
 hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s)
 {
-    static int lanes = getenv("TENT_DEV_LANES") ? atoi(getenv("TENT_DEV_LANES")) : 256;
-    if (lanes == 64) return gather ? launch_copy_lanes<true, 64>(b, s) : launch_copy_lanes<false, 64>(b, s);
-    if (lanes == 128) return gather ? launch_copy_lanes<true, 128>(b, s) : launch_copy_lanes<false, 128>(b, s);
-    if (lanes == 512) return gather ? launch_copy_lanes<true, 512>(b, s) : launch_copy_lanes<false, 512>(b, s);
+    // 256 lanes (4 KiB per workgroup) measured best among 64/128/256/512 on MI355X
     return gather ? launch_copy_lanes<true, 256>(b, s) : launch_copy_lanes<false, 256>(b, s);
 }
 

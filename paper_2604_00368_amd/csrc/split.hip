@@ -100,7 +100,7 @@ __global__ void __launch_bounds__(256) tile_table_kernel(BatchDev b)
             const uint32_t e = (uint32_t)last_not_above(b.src_pre, b.s_src_e0[i], hi, pos);
             const tent_extent ex = b.src_ext[e];
             const uint64_t addr = b.seg_base[ex.seg] + ex.off + (pos - b.src_pre[e]);
-            const bool slow = (pos + n_tile > b.src_pre[e + 1]) || (addr & 15);
+            const bool slow = pos + n_tile > b.src_pre[e + 1];
             b.src_tile[q] = addr | (slow ? kTileSlow : 0);
         }
         {
@@ -109,7 +109,7 @@ __global__ void __launch_bounds__(256) tile_table_kernel(BatchDev b)
             const uint32_t e = (uint32_t)last_not_above(b.dst_pre, b.s_dst_e0[i], hi, pos);
             const tent_extent ex = b.dst_ext[e];
             const uint64_t addr = b.seg_base[ex.seg] + ex.off + (pos - b.dst_pre[e]);
-            const bool slow = (pos + n_tile > b.dst_pre[e + 1]) || (addr & 15);
+            const bool slow = pos + n_tile > b.dst_pre[e + 1];
             b.dst_tile[q] = addr | (slow ? kTileSlow : 0);
         }
     }

@@ -345,13 +345,11 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
         d.tiles_per_slice = (uint32_t)((d.slice_bytes + d.tile_bytes - 1) / d.tile_bytes);
     }
     const uint64_t n_tiles = n_slices * d.tiles_per_slice;
-    // Destination-ordered scatter needs every boundary on a tile boundary and 16-byte aligned
-    // addresses on both sides; other geometry keeps the slice-ordered scatter.
+    // Destination-ordered scatter needs every boundary on a tile boundary (addresses may have any
+    // alignment); other geometry keeps the slice-ordered scatter.
     {
         const uint64_t bits = len_bits | d.slice_bytes;
-        const bool tiled = (bits & (d.tile_bytes - 1)) == 0;
-        const bool aligned = ((dst_addr_bits | (uint64_t)ctx->cfg.staging_arena) & 15) == 0;
-        d.n_sc_tiles = (tiled && aligned) ? payload / d.tile_bytes : 0;
+        d.n_sc_tiles = (bits & (d.tile_bytes - 1)) == 0 ? payload / d.tile_bytes : 0;
     }
 
     uint32_t *sp = nullptr, *dp = nullptr;

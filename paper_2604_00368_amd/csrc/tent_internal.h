@@ -93,14 +93,14 @@ struct BatchDev {
 
     // Tile tables: for every slice, tiles_per_slice entries per side; entry t holds the device
     // address of byte t*tile_bytes of the slice on the paged side.  Bit 63 marks a tile that
-    // needs the generic path (it crosses an extent boundary or is not 16-byte aligned).
+    // needs the generic path (it crosses an extent boundary).
     uint64_t* src_tile;            // [n_slices * tiles_per_slice]
     uint64_t* dst_tile;
     uint32_t  tile_bytes;          // 1 KiB, 2 KiB or 4 KiB
     uint32_t  tiles_per_slice;
 
-    // Destination-ordered scatter (only when every boundary falls on a tile boundary and all
-    // addresses are 16-byte aligned; n_sc_tiles = 0 otherwise): tiles of the destination bytes in
+    // Destination-ordered scatter (only when every boundary falls on a tile boundary;
+    // n_sc_tiles = 0 otherwise): tiles of the destination bytes in
     // ascending device address, so that the scatter kernel writes sequentially.
     const uint32_t* dst_order;     // [n_dst_ext] destination extents sorted by device address
     uint64_t* ord_pre;             // [n_dst_ext+1] exclusive prefix of their lengths in that order

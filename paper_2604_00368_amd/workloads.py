@@ -171,13 +171,18 @@ def _paged_kv(rng, n_req, pages_per_req, planes, page_bytes):
 def kv_migration(seed: int = 2, n_req: int = 32, layers: int = 32,
                  ctx_lo: int = 2048, ctx_hi: int = 8192, page_tokens: int = 16,
                  kv_heads: int = 8, head_dim: int = 128,
-                 slice_bytes: int = 256 * KiB) -> Workload:
+                 slice_bytes: int = 256 * KiB, skew=(0, 0)) -> Workload:
+    """skew = (source, destination) byte shift of every page, to exercise unaligned addresses."""
     rng = np.random.Generator(np.random.PCG64(seed))
     page_bytes = page_tokens * kv_heads * head_dim * 2          # bf16
     ctx = rng.integers(ctx_lo, ctx_hi + 1, size=n_req)
     pages = -(-ctx // page_tokens)
     ptr, src_ext, dst_ext, pool, P = _paged_kv(rng, n_req, pages, layers * 2, page_bytes)
     rails = make_rails([50000] * 8 + [400000])
+    if skew != (0, 0):
+        src_ext["off"] += np.uint64(skew[0])
+        dst_ext["off"] += np.uint64(skew[1])
+        pool += 16
     return Workload("kv_migration", seed, slice_bytes, [pool, pool], ptr, src_ext,
                     ptr.copy(), dst_ext, rails, "bf16",
                     notes={"pages": int(P), "page_bytes": page_bytes, "ctx": ctx.tolist()})
