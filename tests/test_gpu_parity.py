@@ -17,7 +17,7 @@ def H():
     return gpu_harness
 
 
-def run_and_compare(H, oracle, w, flags=0):
+def run_and_compare(H, oracle, w, flags=0, arena_skew=0):
     src = W.fill_numpy(w, 0)
     dst0 = W.fill_numpy(w, 1)
     s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
@@ -25,7 +25,7 @@ def run_and_compare(H, oracle, w, flags=0):
     dst_want = dst0.copy()
     staging_want = np.zeros(w.staging_bytes, dtype=np.uint8)
     oracle.execute(w, s, b, [src, dst_want], staging_want)
-    with H.Engine(w, src, dst0, flags=flags) as eng:
+    with H.Engine(w, src, dst0, flags=flags, arena_skew=arena_skew) as eng:
         eng.declare()
         st, info = eng.plan()
         assert st == 0
@@ -396,3 +396,13 @@ def test_telemetry_feedback_closed_loop(H, oracle):
         with pytest.raises(T.TentError) as ei:
             T.tent_update_bandwidth(eng.ctx, h, p2, w.rails, eng.stream)
         assert ei.value.status == T.TENT_ERR_RANGE
+
+
+@pytest.mark.parametrize("skew,arena_skew", [((3, 5), 0), ((0, 0), 7), ((1, 0), 9), ((8, 4), 0)])
+def test_unaligned_addresses_take_the_fast_paths(H, oracle, skew, arena_skew):
+    # pages and staging arena at odd addresses: same bytes, table-driven kernels with unaligned accesses
+    print("skew", skew, arena_skew, flush=True)
+    w = W.kv_migration(n_req=4, layers=2, ctx_lo=200, ctx_hi=900, skew=skew if skew != (0, 0) else (0, 0))
+    run_and_compare(H, oracle, w, arena_skew=arena_skew)
+    w = W.many_small(n_req=24, layers=2)
+    run_and_compare(H, oracle, w, arena_skew=arena_skew)
