@@ -244,7 +244,7 @@ def main():
     achieved = 2 * w.payload / (dom_avg * 1e-3) / 1e9
 
     out = {
-        "metric": "slice gather/scatter GB/s (read+write bytes, whole plan+execute step)",
+        "metric": "slice gather/scatter GB/s (% of HBM peak) + slices planned/sec, 1 MI355X",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",

@@ -273,6 +273,9 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
         const double my_inv_len = 1.0 / (double)my_len;       // one division per lane serves 64 runs
         fetch(blk + 64 + lane);
         const int in_blk = (int)(n_runs - blk < 64 ? n_runs - blk : 64);
+        // results of single-slice runs wait in the lane that fetched the run and leave after the block
+        uint32_t single_rail = 0xFFFFFFFFu;
+        uint64_t single_off = 0;
         for (int t = 0; t < in_blk; ++t) {
             const uint32_t l = __builtin_amdgcn_readlane((int)my_len, t);
             const uint32_t m = __builtin_amdgcn_readlane((int)my_m, t);
@@ -281,15 +284,10 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
 
             const double ld = (double)l;
             if (m == 1) {
-                // a single slice: plain argmin, result written directly
+                // a single slice: plain argmin
                 const int win = argmin_cost(slot_cost(rail, A, l, 0), live, lane, R);
                 const uint64_t T_win = read_lane64(T, win);
-                if (lane == 0) {
-                    const uint32_t id = __builtin_amdgcn_readlane((int)my_id, t);
-                    b.s_rail[id] = (uint32_t)win;
-                    b.s_stage_off[id] = T_win;
-                    b.s_state[id] = TENT_SLICE_BOUND;
-                }
+                if (lane == t) { single_rail = (uint32_t)win; single_off = T_win; }
                 k = lane == win;
             } else {
                 if (lane < n_rails) b.run_T[row + lane] = T;
@@ -447,6 +445,11 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
                 pool_B = __longlong_as_double((long long)uniform64((uint64_t)__double_as_longlong(pool_B)));
                 inv_pool_G = 1.0 / pool_G;
             }
+        }
+        if (single_rail != 0xFFFFFFFFu) {
+            b.s_rail[my_id] = single_rail;
+            b.s_stage_off[my_id] = single_off;
+            b.s_state[my_id] = TENT_SLICE_BOUND;
         }
     }
 
