@@ -346,3 +346,27 @@ def test_degraded_rail_costs_twice(oracle):
     same = W.make_rails([50000, 50000], penalty_q8=[512, 256])
     b2 = oracle.bind(s.len, same)
     assert np.array_equal(b.rail, b2.rail)
+
+
+def test_region_bases_round_each_total_up_to_256(oracle):
+    # odd byte totals: base_d = sum over d' < d of ceil(T_d' / 256) * 256
+    w = W.ragged(3, n_desc=10, max_len=60_000, slice_bytes=4099, n_rails=6)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    b = oracle.bind(s.len, w.rails)
+    assert (b.T % 256 != 0).any()
+    want, at = [], 0
+    for t in b.T.tolist():
+        want.append(at)
+        at += -(-t // 256) * 256
+    assert b.base.tolist() == want
+
+
+def test_retire_boundary_is_inclusive(oracle):
+    # FIFO drain: queued bytes first, then the plan's slices; a slice whose last byte lands exactly on the budget completes
+    rails = W.make_rails([50000], queued=100)
+    w = one_transfer(3000, 1000, rails)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    b = oracle.bind(s.len, rails)
+    for budget, n_done in [(99, 0), (1099, 0), (1100, 1), (2099, 1), (2100, 2), (3099, 2), (3100, 3), (10**9, 3)]:
+        done = oracle.retire(s, b, rails["queued_bytes"], [budget])
+        assert done.tolist() == [1] * n_done + [0] * (3 - n_done), budget
