@@ -94,8 +94,6 @@ void free_batch(Batch& b)
     b.dev = BatchDev{};
 }
 
-struct Interval { uint64_t lo, hi; uint32_t idx; uint32_t is_dst; };
-
 // Walk both extent lists of every transfer: structure, bounds, equal lengths.  Also returns
 // the payload and the number of slices the device splitter will produce.
 int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const tent_extent* se,
@@ -130,47 +128,6 @@ int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const ten
     *payload = total;
     *n_slices = slices;
     *len_bits = bits;
-    return TENT_OK;
-}
-
-// Destination extents sorted by device address (the scatter kernel walks them in this order so
-// that its writes are sequential).  With `check` set, also verify that a destination extent
-// overlaps neither another destination extent nor any source extent of the batch (addresses are
-// compared, so aliasing segments are caught as well).
-int order_destinations(const tent_ctx* ctx, uint64_t ns, const tent_extent* se, uint64_t nd, const tent_extent* de,
-                       bool check, std::vector<uint32_t>* order, uint64_t* addr_bits)
-{
-    std::vector<Interval> iv;
-    try {
-        iv.reserve(nd + (check ? ns : 0));
-        order->resize(nd);
-    } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
-    uint64_t bits = 0;
-    for (uint64_t e = 0; e < nd; ++e) {
-        const uint64_t a = (uint64_t)ctx->segments[de[e].seg].base + de[e].off;
-        bits |= a;
-        iv.push_back({a, a + de[e].len, (uint32_t)e, 1});
-    }
-    if (check)
-        for (uint64_t e = 0; e < ns; ++e) {
-            const uint64_t a = (uint64_t)ctx->segments[se[e].seg].base + se[e].off;
-            iv.push_back({a, a + se[e].len, (uint32_t)e, 0});
-        }
-    std::sort(iv.begin(), iv.end(), [](const Interval& x, const Interval& y) {
-        return x.lo != y.lo ? x.lo < y.lo : x.idx < y.idx;
-    });
-    // sweep: remember the furthest end seen so far among destinations and among all intervals
-    uint64_t far_any = 0, far_dst = 0, k = 0;
-    for (const Interval& x : iv) {
-        if (check) {
-            if (x.is_dst) { if (x.lo < far_any) return TENT_ERR_INVALID; }
-            else          { if (x.lo < far_dst) return TENT_ERR_INVALID; }
-            far_any = std::max(far_any, x.hi);
-            if (x.is_dst) far_dst = std::max(far_dst, x.hi);
-        }
-        if (x.is_dst) (*order)[k++] = x.idx;
-    }
-    *addr_bits = bits;
     return TENT_OK;
 }
 
@@ -309,11 +266,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc != TENT_OK) return rc;
     if (n_slices >= 0xFFFFFFFEull || n_desc >= 0x7FFFFFFFu) return TENT_ERR_RANGE;
     const uint64_t ns = src_ptr[n_desc], nd = dst_ptr[n_desc];
-    std::vector<uint32_t> dst_order;
-    uint64_t dst_addr_bits = 0;
-    rc = order_destinations(ctx, ns, src_ext, nd, dst_ext, !(ctx->cfg.flags & TENT_FLAG_SKIP_OVERLAP_CHECK),
-                            &dst_order, &dst_addr_bits);
-    if (rc != TENT_OK) return rc;
+    if (ns + nd >= 0xFFFFFFFFull) return TENT_ERR_RANGE;
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
 
@@ -382,8 +335,8 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc == TENT_OK) rc = dev_alloc(b, &d.run_T, (uint64_t)d.run_capacity * d.run_stride);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.run_K, (uint64_t)d.run_capacity * d.run_stride);
     uint32_t* order_dev = nullptr;
+    if (rc == TENT_OK) rc = dev_alloc(b, &order_dev, nd);
     if (d.n_sc_tiles) {
-        if (rc == TENT_OK) rc = dev_alloc(b, &order_dev, nd);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.ord_pre, nd + 1);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_dst, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_lin, d.n_sc_tiles);
@@ -398,12 +351,6 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     d.src_ptr = sp; d.dst_ptr = dp; d.src_ext = se; d.dst_ext = de;
     d.dst_order = order_dev;
     d.self = self_dev;
-    if (order_dev &&
-        hipMemcpy(order_dev, dst_order.data(), sizeof(uint32_t) * nd, hipMemcpyHostToDevice) != hipSuccess) {
-        (void)hipGetLastError();
-        free_batch(b);
-        return TENT_ERR_HIP;
-    }
 
     if (hipMemcpy(sp, src_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(dp, dst_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
@@ -414,6 +361,18 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
         (void)hipGetLastError();
         free_batch(b);
         return TENT_ERR_HIP;
+    }
+    // destination extents in address order (for the scatter) and the overlap check, on the device
+    const bool check = !(ctx->cfg.flags & TENT_FLAG_SKIP_OVERLAP_CHECK);
+    if (check || d.n_sc_tiles) {
+        uint32_t overlap = 0;
+        if (device_order_destinations(de, nd, se, ns, ctx->seg_base_dev, check, order_dev, &overlap, nullptr) !=
+            hipSuccess) {
+            (void)hipGetLastError();
+            free_batch(b);
+            return TENT_ERR_HIP;
+        }
+        if (overlap) { free_batch(b); return TENT_ERR_INVALID; }
     }
     b.alive = true;
     *out = ((uint64_t)b.generation << 32) | (uint64_t)(slot + 1);

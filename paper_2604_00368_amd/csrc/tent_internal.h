@@ -149,4 +149,8 @@ hipError_t launch_probe(const BatchDev& b, const ProbeParams& pp, hipStream_t s)
 
 uint64_t scan_partials_capacity(uint64_t n);
 
+hipError_t device_order_destinations(const tent_extent* dst_ext, uint64_t n_dst, const tent_extent* src_ext,
+                                     uint64_t n_src, const uint64_t* seg_base, bool check, uint32_t* order_out,
+                                     uint32_t* overlap_out, hipStream_t s);
+
 }  // namespace tent
