@@ -67,7 +67,7 @@ def make_workload(name):
     from paper_2604_00368_amd import workloads as W
     if name == "many_small_x6":
         return W.many_small(layers=6)
-    if name == "kv_skewed":          # a quarter of config 2 with every page at an odd address (generic copy path)
+    if name == "kv_skewed":          # a quarter of config 2 with every page at an odd address (unaligned 16-byte accesses)
         return W.kv_migration(n_req=8, skew=(3, 5))
     return W.CONFIGS[name]()
 
@@ -248,7 +248,7 @@ def main():
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
-        "config": {"workload": w.name, "payload_bytes": w.payload, "n_desc": w.n_desc,
+        "config": {"workload": args.workload, "payload_bytes": w.payload, "n_desc": w.n_desc,
                    "n_extents": int(w.src_ext.shape[0]), "n_slices": n_slices, "slice_bytes": w.slice_bytes,
                    "n_rails": int(w.rails.shape[0]), "binding": "serial" if args.serial_binding else "default",
                    "streams": "single" if args.single_stream else
@@ -264,9 +264,9 @@ def main():
         "feedback": {"window_slices": n_slices, "ms_per_window": round(fb_ms / max(1, fb_n), 4),
                      "bytes_per_slice": 17},
         "plain_copy_GBps": round(plain_copy_GBps, 2),
-        "roofline": {"bound": "hbm", "kernel": "copy_kernel<gather>" if dom == "gather" else "scatter_ordered_kernel", "achieved": round(achieved, 2),
+        "roofline": {"bound": "hbm", "kernel": "ordered_copy_kernel (%s launch)" % dom, "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic(w.name, dom),
+                     "traffic": measured_traffic(args.workload, dom),
                      "algorithmic_bytes_per_launch": 2 * w.payload,
                      "avg_launch_ms": round(dom_avg, 4),
                      "gather_GBps": round(2 * w.payload / (gather_avg * 1e-3) / 1e9, 2),

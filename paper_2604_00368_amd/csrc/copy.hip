@@ -147,27 +147,29 @@ static hipError_t launch_copy_lanes(const BatchDev& b, hipStream_t s)
     return hipGetLastError();
 }
 
-// Scatter in ascending destination address: workgroup w moves 4 KiB of the destination bytes laid
-// end to end in address order, so consecutive workgroups write consecutive destination addresses
-// while the reads hop between staging regions (HBM tolerates scattered reads better than scattered
-// writes).  Only used when every tile is whole (no extent boundary inside a tile).
-__global__ void __launch_bounds__(256) scatter_ordered_kernel(const uint64_t* __restrict__ sc_dst,
-                                                              const uint64_t* __restrict__ sc_lin,
-                                                              uint64_t n_tiles, uint32_t tile_shift)
+// Table-driven copy: workgroup w moves the 4 KiB block w of an enumeration of the payload in tiles;
+// `from` and `to` hold the two addresses of every tile (0 = tile not to be moved).  Gather walks the
+// source bytes in declaration order (reads hop between pages, every rail region is written front to
+// back); scatter walks the destination bytes in ascending device address (reads hop between the
+// rail regions, writes are sequential) -- HBM tolerates scattered reads better than scattered
+// writes.  Only used when no tile crosses an extent boundary.
+__global__ void __launch_bounds__(256) ordered_copy_kernel(const uint64_t* __restrict__ from,
+                                                           const uint64_t* __restrict__ to,
+                                                           uint64_t n_tiles, uint32_t tile_shift)
 {
     const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
-    const uint64_t at = w * kCopyBlockBytes + (uint64_t)threadIdx.x * 16;     // byte in destination order
+    const uint64_t at = w * kCopyBlockBytes + (uint64_t)threadIdx.x * 16;     // byte in enumeration order
     const uint64_t q = at >> tile_shift;
     if (q >= n_tiles) return;
-    const uint64_t lin = sc_lin[q];
-    const uint64_t dst = sc_dst[q];
-    if (lin == 0) return;
+    const uint64_t src = from[q];
+    const uint64_t dst = to[q];
+    if (src == 0 || dst == 0) return;
     const uint64_t in_tile = at & ((1ull << tile_shift) - 1);
-    vec4u v = __builtin_nontemporal_load((const vec4u_any*)(lin + in_tile));
+    vec4u v = __builtin_nontemporal_load((const vec4u_any*)(src + in_tile));
     __builtin_nontemporal_store(v, (vec4u_any*)(dst + in_tile));
 }
 
-hipError_t launch_scatter_ordered(const BatchDev& b, hipStream_t s)
+hipError_t launch_copy_ordered(const BatchDev& b, bool gather, hipStream_t s)
 {
     uint32_t tile_shift = 0;
     while ((1u << tile_shift) < b.tile_bytes) ++tile_shift;
@@ -177,8 +179,8 @@ hipError_t launch_scatter_ordered(const BatchDev& b, hipStream_t s)
     const uint32_t gx = blocks < 65536 ? (uint32_t)blocks : 65536u;
     const uint64_t gy = (blocks + gx - 1) / gx;
     if (gy > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(scatter_ordered_kernel, dim3(gx, (uint32_t)gy), dim3(256), 0, s, b.sc_dst, b.sc_lin,
-                       b.n_sc_tiles, tile_shift);
+    hipLaunchKernelGGL(ordered_copy_kernel, dim3(gx, (uint32_t)gy), dim3(256), 0, s,
+                       gather ? b.ga_src : b.sc_lin, gather ? b.ga_lin : b.sc_dst, b.n_sc_tiles, tile_shift);
     return hipGetLastError();
 }
 

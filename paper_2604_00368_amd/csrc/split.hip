@@ -147,18 +147,42 @@ __global__ void __launch_bounds__(256) scatter_table_kernel(BatchDev b)
     }
 }
 
+// Source-ordered tiles: tile q covers bytes [q*tile, (q+1)*tile) of the source extents laid end to
+// end in declaration order, i.e. of the transfers' logical bytes one after the other.
+__global__ void __launch_bounds__(256) gather_table_kernel(BatchDev b)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < b.n_sc_tiles; q += stride) {
+        const uint64_t at = q * b.tile_bytes;
+        const uint64_t e = last_not_above(b.src_pre, 0, b.n_src_ext, at);
+        const tent_extent ex = b.src_ext[e];
+        uint32_t lo = 0, hi = b.n_desc;                   // owning transfer: last j with src_ptr[j] <= e
+        while (hi - lo > 1) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            if (b.src_ptr[mid] <= e) lo = mid; else hi = mid;
+        }
+        const uint64_t off = at - b.src_pre[b.src_ptr[lo]];
+        const uint64_t k = off / b.slice_bytes;
+        b.ga_src[q] = b.seg_base[ex.seg] + ex.off + (at - b.src_pre[e]);
+        b.ga_slice[q] = (uint32_t)(b.first[lo] + k);
+        b.ga_x[q] = (uint32_t)(off - k * b.slice_bytes);
+    }
+}
+
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s)
 {
-    uint64_t blocks = (b.n_slices * (uint64_t)b.tiles_per_slice + 255) / 256;
-    if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(tile_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
-    if (b.n_sc_tiles) {
-        hipError_t e = exclusive_scan(OrderedLen{b.dst_ext, b.dst_order}, b.n_dst_ext, b.ord_pre, b.scan_partials, s);
-        if (e != hipSuccess) return e;
-        blocks = (b.n_sc_tiles + 255) / 256;
+    if (b.n_sc_tiles == 0) {
+        uint64_t blocks = (b.n_slices * (uint64_t)b.tiles_per_slice + 255) / 256;
         if (blocks > 65536) blocks = 65536;
-        hipLaunchKernelGGL(scatter_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+        hipLaunchKernelGGL(tile_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+        return hipGetLastError();
     }
+    hipError_t e = exclusive_scan(OrderedLen{b.dst_ext, b.dst_order}, b.n_dst_ext, b.ord_pre, b.scan_partials, s);
+    if (e != hipSuccess) return e;
+    uint64_t blocks = (b.n_sc_tiles + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(gather_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    hipLaunchKernelGGL(scatter_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
     return hipGetLastError();
 }
 
@@ -177,11 +201,14 @@ __global__ void __launch_bounds__(256) finalize_kernel(BatchDev b, uint8_t* aren
     }
 }
 
-// Staging address of every destination-ordered tile whose slice is about to move (0 otherwise).
-__global__ void __launch_bounds__(256) finalize_scatter_kernel(BatchDev b)
+// Staging address of every source-ordered and destination-ordered tile whose slice is about to
+// move (0 otherwise).
+__global__ void __launch_bounds__(256) finalize_tiles_kernel(BatchDev b)
 {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < b.n_sc_tiles; q += stride) {
+        const SliceRec g = b.s_rec[b.ga_slice[q]];
+        b.ga_lin[q] = g.len ? g.lin + b.ga_x[q] : 0;
         const SliceRec r = b.s_rec[b.sc_slice[q]];
         b.sc_lin[q] = r.len ? r.lin + b.sc_x[q] : 0;
     }
@@ -195,7 +222,7 @@ hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s)
     if (b.n_sc_tiles) {
         blocks = (b.n_sc_tiles + 255) / 256;
         if (blocks > 65536) blocks = 65536;
-        hipLaunchKernelGGL(finalize_scatter_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+        hipLaunchKernelGGL(finalize_tiles_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
     }
     return hipGetLastError();
 }

@@ -327,8 +327,10 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_rec, n_slices);
     BatchDev* self_dev = nullptr;
     if (rc == TENT_OK) rc = dev_alloc(b, &self_dev, 1);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.src_tile, n_tiles);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.dst_tile, n_tiles);
+    if (d.n_sc_tiles == 0) {                              // per-slice tile tables only for untiled geometry
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.src_tile, n_tiles);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.dst_tile, n_tiles);
+    }
     d.run_capacity = 2u * n_desc;
     d.run_stride = ctx->max_rails;
     if (rc == TENT_OK) rc = dev_alloc(b, &d.run_start, (uint64_t)d.run_capacity + 1);
@@ -338,6 +340,10 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc == TENT_OK) rc = dev_alloc(b, &order_dev, nd);
     if (d.n_sc_tiles) {
         if (rc == TENT_OK) rc = dev_alloc(b, &d.ord_pre, nd + 1);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_src, d.n_sc_tiles);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_lin, d.n_sc_tiles);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_slice, d.n_sc_tiles);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_x, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_dst, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_lin, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_slice, d.n_sc_tiles);
@@ -553,11 +559,12 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     HIP_TRY(launch_finalize(b->dev, static_cast<uint8_t*>(ctx->cfg.staging_arena), s));
     {
         StageTimer t(ctx, TENT_T_GATHER, s);
-        HIP_TRY(launch_copy(b->dev, true, s));
+        if (b->dev.n_sc_tiles) HIP_TRY(launch_copy_ordered(b->dev, true, s));
+        else                   HIP_TRY(launch_copy(b->dev, true, s));
     }
     {
         StageTimer t(ctx, TENT_T_SCATTER, s);
-        if (b->dev.n_sc_tiles) HIP_TRY(launch_scatter_ordered(b->dev, s));
+        if (b->dev.n_sc_tiles) HIP_TRY(launch_copy_ordered(b->dev, false, s));
         else                   HIP_TRY(launch_copy(b->dev, false, s));
     }
     HIP_TRY(launch_mark_done(b->dev, s));

@@ -99,16 +99,21 @@ struct BatchDev {
     uint32_t  tile_bytes;          // 1 KiB, 2 KiB or 4 KiB
     uint32_t  tiles_per_slice;
 
-    // Destination-ordered scatter (only when every boundary falls on a tile boundary;
-    // n_sc_tiles = 0 otherwise): tiles of the destination bytes in
-    // ascending device address, so that the scatter kernel writes sequentially.
+    // Table-driven copies (only when every boundary falls on a tile boundary; n_sc_tiles = 0
+    // otherwise and the per-slice tile tables above are used instead).  Two enumerations of the
+    // payload in tiles: source bytes in declaration order (gather: each rail region is written front
+    // to back) and destination bytes in ascending device address (scatter: sequential writes).
     const uint32_t* dst_order;     // [n_dst_ext] destination extents sorted by device address
     uint64_t* ord_pre;             // [n_dst_ext+1] exclusive prefix of their lengths in that order
     uint64_t  n_sc_tiles;          // payload / tile_bytes
-    uint64_t* sc_dst;              // [n_sc_tiles] destination address of the tile
-    uint64_t* sc_lin;              // [n_sc_tiles] staging address of the tile, 0 = not to be moved
-    uint32_t* sc_slice;            // [n_sc_tiles] slice that holds the tile
-    uint32_t* sc_x;                // [n_sc_tiles] byte offset of the tile inside that slice
+    uint64_t* ga_src;              // [n_sc_tiles] gather: source address of the tile
+    uint64_t* ga_lin;              // [n_sc_tiles] gather: staging address, 0 = not to be moved
+    uint32_t* ga_slice;            // [n_sc_tiles] slice that holds the tile
+    uint32_t* ga_x;                // [n_sc_tiles] byte offset of the tile inside that slice
+    uint64_t* sc_dst;              // [n_sc_tiles] scatter: destination address of the tile
+    uint64_t* sc_lin;              // [n_sc_tiles] scatter: staging address, 0 = not to be moved
+    uint32_t* sc_slice;
+    uint32_t* sc_x;
 
     // Run-parallel binding: maximal runs of equal-length pending slices (at most two per transfer)
     uint32_t* run_start;           // [run_capacity + 1] first pending position of every run
@@ -139,7 +144,7 @@ hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, bool use_pe
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
 hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s);
 hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s);
-hipError_t launch_scatter_ordered(const BatchDev& b, hipStream_t s);
+hipError_t launch_copy_ordered(const BatchDev& b, bool gather, hipStream_t s);
 hipError_t launch_mark_done(const BatchDev& b, hipStream_t s);
 hipError_t launch_retire(const BatchDev& b, const BudgetParams& bp, hipStream_t s);
 hipError_t launch_count_remaining(const BatchDev& b, hipStream_t s);
