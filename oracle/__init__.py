@@ -51,6 +51,11 @@ def lib():
         L.ora_execute.restype = None
         L.ora_sim_latency.restype = None
         L.ora_probe.restype = None
+        L.ora_fail.restype = C.c_uint64
+        L.ora_rotation_candidates.restype = C.c_uint32
+        L.ora_plan.restype = C.c_int
+        L.ora_monitor_init.restype = None
+        L.ora_monitor_step.restype = None
         _lib = L
     return _lib
 
@@ -130,6 +135,67 @@ def bind(slice_len, rails, ids=None, rail=None, stage_off=None) -> Binding:
     base = np.zeros(R, dtype=np.uint64)
     L.ora_stage_bases(_p(T), C.c_uint32(R), _p(base))
     return Binding(int(st), rail, stage_off, T, cnt, A, base)
+
+
+def fail(b: Binding, rail_failed, retry, ids=None):
+    """Hard errors on the rails flagged in rail_failed: the listed slices bound to them get one
+    more retry (retry is updated in place).  Returns (failed flags per listed slice, count per rail)."""
+    L = lib()
+    R = len(rail_failed)
+    n = b.rail.shape[0] if ids is None else ids.shape[0]
+    failed = np.zeros(n, dtype=np.uint8)
+    per_rail = np.zeros(R, dtype=np.uint64)
+    L.ora_fail(C.c_uint64(n), _p(ids), _p(b.rail), C.c_uint32(R),
+               _p(np.ascontiguousarray(rail_failed, dtype=np.uint8)), _p(retry), _p(failed), _p(per_rail))
+    return failed, per_rail
+
+
+def rotation_candidates(rails) -> np.ndarray:
+    cand = np.zeros(64, dtype=np.uint32)
+    n = lib().ora_rotation_candidates(_p(np.ascontiguousarray(rails)), C.c_uint32(rails.shape[0]), _p(cand))
+    return cand[:n].copy()
+
+
+def plan(slice_len, retry, rails, ids=None, rail=None, stage_off=None) -> Binding:
+    """Plan with retried slices: rotation for retry counts > 0, predicted cost for the rest."""
+    L = lib()
+    R = rails.shape[0]
+    N = slice_len.shape[0]
+    c0, c1, ex, A = coeffs(rails)
+    T = np.zeros(R, dtype=np.uint64)
+    cnt = np.zeros(R, dtype=np.uint64)
+    if rail is None:
+        rail = np.full(N, 0xFFFFFFFF, dtype=np.uint32)
+    if stage_off is None:
+        stage_off = np.zeros(N, dtype=np.uint64)
+    n = N if ids is None else ids.shape[0]
+    st = L.ora_plan(C.c_uint64(n), _p(ids), _p(slice_len), _p(retry), _p(np.ascontiguousarray(rails)),
+                    C.c_uint32(R), _p(c0), _p(c1), _p(ex), _p(A), _p(T), _p(cnt), _p(rail), _p(stage_off))
+    base = np.zeros(R, dtype=np.uint64)
+    L.ora_stage_bases(_p(T), C.c_uint32(R), _p(base))
+    return Binding(int(st), rail, stage_off, T, cnt, A, base)
+
+
+MONITOR_PARAMS_DTYPE = np.dtype([("err_threshold", "<u4"), ("recover_windows", "<u4"),
+                                 ("cooldown_windows", "<u4"), ("degrade_q8", "<u4")])
+MONITOR_DTYPE = np.dtype([("state", "<u4"), ("score", "<u4"), ("clean", "<u4"),
+                          ("cooldown_left", "<u4"), ("cooldown_next", "<u4")])
+
+
+def monitor_init(R: int, mp) -> np.ndarray:
+    mon = np.zeros(R, dtype=MONITOR_DTYPE)
+    lib().ora_monitor_init(C.c_uint32(R), _p(np.ascontiguousarray(mp)), _p(mon))
+    return mon
+
+
+def monitor_step(mp, mon, hard, congestion, probe_MBps, bw_MBps) -> None:
+    """One measurement window of the rail health monitor; mon is updated in place."""
+    R = mon.shape[0]
+    lib().ora_monitor_step(C.c_uint32(R), _p(np.ascontiguousarray(mp)), _p(mon),
+                           _p(np.ascontiguousarray(hard, dtype=np.uint32)),
+                           _p(np.ascontiguousarray(congestion, dtype=np.uint32)),
+                           _p(np.ascontiguousarray(probe_MBps, dtype=np.uint32)),
+                           _p(np.ascontiguousarray(bw_MBps, dtype=np.uint32)))
 
 
 def execute(w, s: Slices, b: Binding, pools, staging: np.ndarray, ids=None) -> None:

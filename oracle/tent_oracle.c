@@ -30,7 +30,7 @@
  *   c1_d   = floor(1e6 * beta1_q8 * penalty_q8 / bw_MBps)   picoseconds per byte, Q16
  *   c0_d   = (lat_ns * 1000 * penalty_q8) >> 8              picoseconds
  *   cost_d = c0_d + (((A_d + L) * c1_d) >> 16)
- *   a DEGRADED rail (Section 4.3: "0.5x weight penalty but remains eligible") has both
+ *   a DEGRADED rail (Section 4.3: it keeps half its weight and stays eligible) has both
  *   coefficients doubled, i.e. its predicted cost counts twice;
  *   ties go to the lowest rail index; slices are bound in ascending index order;
  *   a rail's staging region packs its slices in bind order; region bases are the
@@ -118,19 +118,11 @@ uint64_t ora_cost(uint64_t c0, uint64_t c1, uint64_t A, uint64_t L)
  * ids == NULL binds slices 0..n-1; otherwise slices ids[0..n-1] in that order.
  * A[] is read and updated (bytes in flight); T[] receives the per-rail byte
  * totals of this call; slices[] receives the per-rail slice counts. */
-int ora_bind(uint64_t n, const uint32_t *ids, const uint32_t *s_len, uint32_t R,
-             const uint64_t *c0, const uint64_t *c1, const uint8_t *excluded,
-             uint64_t *A, uint64_t *T, uint64_t *slices,
-             uint32_t *s_rail, uint64_t *s_stage_off)
+static void bind_by_cost(uint64_t n, const uint32_t *ids, const uint32_t *s_len, uint32_t R,
+                         const uint64_t *c0, const uint64_t *c1, const uint8_t *excluded,
+                         uint64_t *A, uint64_t *T, uint64_t *slices,
+                         uint32_t *s_rail, uint64_t *s_stage_off)
 {
-    int admitted = 0;
-    for (uint32_t d = 0; d < R; ++d) {
-        T[d] = 0;
-        slices[d] = 0;
-        if (!excluded[d]) admitted = 1;
-    }
-    if (!admitted) return ORA_DEFER;
-
     for (uint64_t q = 0; q < n; ++q) {
         uint64_t i = ids ? ids[q] : q;
         int best = -1;
@@ -146,7 +138,159 @@ int ora_bind(uint64_t n, const uint32_t *ids, const uint32_t *s_len, uint32_t R,
         A[best] += s_len[i];
         slices[best] += 1;
     }
+}
+
+int ora_bind(uint64_t n, const uint32_t *ids, const uint32_t *s_len, uint32_t R,
+             const uint64_t *c0, const uint64_t *c1, const uint8_t *excluded,
+             uint64_t *A, uint64_t *T, uint64_t *slices,
+             uint32_t *s_rail, uint64_t *s_stage_off)
+{
+    int admitted = 0;
+    for (uint32_t d = 0; d < R; ++d) {
+        T[d] = 0;
+        slices[d] = 0;
+        if (!excluded[d]) admitted = 1;
+    }
+    if (!admitted) return ORA_DEFER;
+    bind_by_cost(n, ids, s_len, R, c0, c1, excluded, A, T, slices, s_rail, s_stage_off);
     return ORA_OK;
+}
+
+/* ---- link-level resilience (Section 4.3, "Link-Level Resilience") -----------
+ * A slice whose rail reports a hard error goes back to the pending set with its
+ * retry count raised by one (counts saturate at 255).  rail_failed[d] != 0 marks
+ * the rails that failed; failed[q] is written for the q-th listed slice and
+ * per_rail[d] receives the number of slices that failed on rail d. */
+uint64_t ora_fail(uint64_t n, const uint32_t *ids, const uint32_t *s_rail, uint32_t R,
+                  const uint8_t *rail_failed, uint8_t *s_retry, uint8_t *failed, uint64_t *per_rail)
+{
+    uint64_t n_failed = 0;
+    for (uint32_t d = 0; d < R; ++d) per_rail[d] = 0;
+    for (uint64_t q = 0; q < n; ++q) {
+        uint64_t i = ids ? ids[q] : q;
+        uint32_t d = s_rail[i];
+        failed[q] = 0;
+        if (d < R && rail_failed[d]) {
+            failed[q] = 1;
+            if (s_retry[i] < 255) s_retry[i] += 1;
+            per_rail[d] += 1;
+            n_failed += 1;
+        }
+    }
+    return n_failed;
+}
+
+/* Candidate rails of a retried slice, in rotation order.  Two passes (Section 4.3): HEALTHY
+ * rails first; only when there is none, DEGRADED rails, and among those the affinity-matched
+ * ones (no topology penalty: penalty_q8 <= 256) before any other reachable rail.  Reading:
+ * the first non-empty of the three groups is the candidate set, in ascending rail index.
+ * Returns the number of candidates (0: every rail is excluded). */
+uint32_t ora_rotation_candidates(const ora_rail *rails, uint32_t R, uint32_t *cand)
+{
+    uint32_t n = 0;
+    for (uint32_t d = 0; d < R; ++d) if (rails[d].health == 0) cand[n++] = d;
+    if (n) return n;
+    for (uint32_t d = 0; d < R; ++d) if (rails[d].health == 1 && rails[d].penalty_q8 <= 256) cand[n++] = d;
+    if (n) return n;
+    for (uint32_t d = 0; d < R; ++d) if (rails[d].health == 1) cand[n++] = d;
+    return n;
+}
+
+/* Plan with retried slices (Section 4.3): retries do not go through the cost model but their
+ * bytes count in the queue statistics the cost model reads.  Reading: the retried slices
+ * (retry count k > 0) are issued first, in ascending slice index; slice i takes candidate
+ * number (i + k) mod |candidates|, so that successive retries of one slice walk round the
+ * candidate set and slices that failed together spread over it; then the slices with k = 0
+ * are bound by predicted cost with A_d and the staging offsets continuing from there.
+ * ids lists the slices to plan (NULL = 0..n-1) in ascending order. */
+int ora_plan(uint64_t n, const uint32_t *ids, const uint32_t *s_len, const uint8_t *s_retry,
+             const ora_rail *rails, uint32_t R,
+             const uint64_t *c0, const uint64_t *c1, const uint8_t *excluded,
+             uint64_t *A, uint64_t *T, uint64_t *slices,
+             uint32_t *s_rail, uint64_t *s_stage_off)
+{
+    uint32_t cand[64];
+    uint32_t n_cand = ora_rotation_candidates(rails, R, cand);
+    for (uint32_t d = 0; d < R; ++d) { T[d] = 0; slices[d] = 0; }
+    if (n_cand == 0) return ORA_DEFER;
+
+    for (uint64_t q = 0; q < n; ++q) {                 /* pass over the retried slices */
+        uint64_t i = ids ? ids[q] : q;
+        if (s_retry[i] == 0) continue;
+        uint32_t d = cand[(i + s_retry[i]) % n_cand];
+        s_rail[i] = d;
+        s_stage_off[i] = T[d];
+        T[d] += s_len[i];
+        A[d] += s_len[i];
+        slices[d] += 1;
+    }
+    for (uint64_t q = 0; q < n; ++q) {                 /* everything else: by predicted cost */
+        uint64_t i = ids ? ids[q] : q;
+        if (s_retry[i] != 0) continue;
+        uint32_t one = (uint32_t)i;
+        bind_by_cost(1, &one, s_len, R, c0, c1, excluded, A, T, slices, s_rail, s_stage_off);
+    }
+    return ORA_OK;
+}
+
+/* ---- rail health monitor (Section 4.3, "Health Monitoring") ------------------
+ * Three states per rail: HEALTHY (0), DEGRADED (1: half weight, still eligible), PAUSED (2:
+ * excluded while a cooldown runs).  The paper gives the states and the rules in words; the
+ * reading below fixes them per measurement window, all integers:
+ *   - error score of a window = 2 * hard errors + congestion errors, accumulated over
+ *     consecutive windows that saw errors (a window without errors clears it); the rail is
+ *     paused when the score exceeds 2 * err_threshold, i.e. hard errors beyond the threshold
+ *     or congestion errors beyond twice the threshold;
+ *   - a pause lasts cooldown_next windows and cooldown_next doubles with every pause; the rail
+ *     then re-enters as DEGRADED (gradual re-admission);
+ *   - any error below the pause level, or a degradation event, makes the rail DEGRADED; a
+ *     window is a degradation event when even its cleanest sample is slow: the bandwidth probe
+ *     of the window (Eq. 2; 0 = no sample) is below degrade_q8/256 of the estimate the planner
+ *     held before the window;
+ *   - a DEGRADED rail is promoted to HEALTHY after recover_windows consecutive windows without
+ *     errors and degradation events; promotion resets cooldown_next to cooldown_windows.
+ * Errors and events reported for a PAUSED rail are ignored (it carries no traffic). */
+typedef struct { uint32_t err_threshold; uint32_t recover_windows; uint32_t cooldown_windows; uint32_t degrade_q8; } ora_monitor_params;
+typedef struct { uint32_t state; uint32_t score; uint32_t clean; uint32_t cooldown_left; uint32_t cooldown_next; } ora_monitor;
+
+void ora_monitor_init(uint32_t R, const ora_monitor_params *mp, ora_monitor *mon)
+{
+    for (uint32_t d = 0; d < R; ++d) {
+        mon[d].state = 0; mon[d].score = 0; mon[d].clean = 0;
+        mon[d].cooldown_left = 0; mon[d].cooldown_next = mp->cooldown_windows;
+    }
+}
+
+void ora_monitor_step(uint32_t R, const ora_monitor_params *mp, ora_monitor *mon,
+                      const uint32_t *hard, const uint32_t *congestion,
+                      const uint32_t *probe_MBps, const uint32_t *bw_MBps)
+{
+    for (uint32_t d = 0; d < R; ++d) {
+        ora_monitor *m = &mon[d];
+        if (m->state == 2) {
+            if (m->cooldown_left > 0) m->cooldown_left -= 1;
+            if (m->cooldown_left == 0) { m->state = 1; m->clean = 0; m->score = 0; }
+            continue;
+        }
+        uint64_t errors = 2ull * hard[d] + congestion[d];
+        int event = probe_MBps[d] != 0 && (uint64_t)probe_MBps[d] * 256 < (uint64_t)mp->degrade_q8 * bw_MBps[d];
+        if (errors == 0) m->score = 0;
+        else m->score = (uint32_t)(m->score + errors > 0xFFFFFFFFull ? 0xFFFFFFFFull : m->score + errors);
+        if ((uint64_t)m->score > 2ull * mp->err_threshold) {
+            m->state = 2;
+            m->score = 0;
+            m->clean = 0;
+            m->cooldown_left = m->cooldown_next;
+            m->cooldown_next = m->cooldown_next >= (1u << 30) ? (1u << 31) : m->cooldown_next * 2;
+            if (m->cooldown_left == 0) { m->state = 1; }      /* a zero-length cooldown pauses nothing */
+        } else if (errors > 0 || event) {
+            m->state = 1;
+            m->clean = 0;
+        } else if (m->state == 1) {
+            m->clean += 1;
+            if (m->clean >= mp->recover_windows) { m->state = 0; m->clean = 0; m->cooldown_next = mp->cooldown_windows; }
+        }
+    }
 }
 
 /* Staging region of rail d starts where the regions of rails < d end (256-byte aligned). */
