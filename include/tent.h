@@ -96,6 +96,23 @@ typedef struct {
     uint32_t ewma_q8;          /* weight of the new probe in Q8.8, 0..256 (256 replaces the estimate) */
 } tent_probe_params;
 
+/* Rail health monitor (Section 4.3, "Health Monitoring"): parameters and the record kept per rail. */
+typedef struct {
+    uint32_t err_threshold;    /* a rail pauses once 2*hard + congestion errors exceed 2*err_threshold */
+    uint32_t recover_windows;  /* clean windows after which a DEGRADED rail is HEALTHY again           */
+    uint32_t cooldown_windows; /* length of the first pause; every further pause is twice as long      */
+    uint32_t degrade_q8;       /* a window whose probe is below degrade_q8/256 of the estimate is a
+                                  degradation event (Q8.8; 0 switches the test off)                   */
+} tent_monitor_params;
+
+typedef struct {
+    uint32_t state;            /* 0 HEALTHY, 1 DEGRADED, 2 PAUSED: the value for tent_rail_state.health */
+    uint32_t score;            /* weighted errors of the current run of windows with errors            */
+    uint32_t clean;            /* consecutive clean windows of a DEGRADED rail                         */
+    uint32_t cooldown_left;    /* windows a PAUSED rail stays excluded                                 */
+    uint32_t cooldown_next;    /* length of the next pause                                             */
+} tent_rail_monitor;
+
 /* One row of the slice table: the task triple <path, offset, length> of
  * Algorithm 1 plus the bookkeeping of the staging hop. */
 typedef struct {
@@ -150,7 +167,7 @@ int tent_declare(tent_ctx *ctx, uint32_t n_desc,
 
 /*
  * Split and bind (Section 4.2; Algorithm 1 Stages 1-2; Eq. 1).
- * On a batch without DONE slices the slice table is (re)built on the device:
+ * On a batch without DONE or failed slices the slice table is (re)built on the device:
  * slice k of transfer j covers bytes [k*S, min((k+1)*S, len_j)).  Then every
  * slice that is not DONE is bound, in ascending slice index, to the admitted
  * rail (health != 2) with the smallest
@@ -160,7 +177,8 @@ int tent_declare(tent_ctx *ctx, uint32_t n_desc,
  * health = 1: Section 4.3, a degraded rail keeps half its weight), after which A_d += len.  The
  * slice's staging offset is the number of bytes bound to that rail earlier in
  * this call.  Rail d's staging region starts at the sum over d' < d of the
- * rail totals rounded up to 256 bytes.
+ * rail totals rounded up to 256 bytes.  Slices that failed on a rail (tent_sim_fail) are
+ * bound by rotation ahead of this pass; see there.
  * `rails` is host memory (n_rails <= TENT_MAX_RAILS).  `info` is host memory or
  * NULL; when it is non-NULL the call waits for the stream and fills it, when it
  * is NULL the call only enqueues work on `stream`.
@@ -182,6 +200,51 @@ int tent_plan(tent_ctx *ctx, tent_batch_t batch, const tent_rail_state *rails, u
  */
 int tent_sim_advance(tent_ctx *ctx, tent_batch_t batch, const uint64_t *budget_bytes,
                      uint64_t *n_done, void *stream);
+
+/*
+ * Rail simulator, hard errors (Section 4.3, "Link-Level Resilience"; the injection itself is not an
+ * operation of the paper): every BOUND slice on a rail d with rail_failed[d] != 0 returns to PENDING
+ * and its retry count goes up by one (saturating at 255).  Call it after tent_plan and before
+ * tent_sim_advance / tent_execute.  `rail_failed` is host memory with one entry per rail of the last
+ * tent_plan; `failed_per_rail` (host, same length, or NULL) receives the number of slices that failed
+ * on each rail, and when it is non-NULL the call waits for the stream.
+ *
+ * The next tent_plan treats slices with a retry count differently: they are issued first, in
+ * ascending slice index, without the cost model -- slice i on its k-th retry takes candidate number
+ * (i + k) mod |C| of the candidate set C = the HEALTHY rails, or, when there is none, the DEGRADED
+ * rails with penalty_q8 <= 256, or, when there is none either, all DEGRADED rails (ascending rail
+ * index) -- and their bytes are added to A_d and to the rails' staging regions before the remaining
+ * slices are bound by predicted cost.
+ */
+int tent_sim_fail(tent_ctx *ctx, tent_batch_t batch, const uint8_t *rail_failed,
+                  uint64_t *failed_per_rail, void *stream);
+
+/* Copy the slices' retry counts (one byte per slice) to host memory for verification.  Waits for
+ * the device.  TENT_ERR_RANGE if cap is smaller than the slice count. */
+int tent_get_retries(tent_ctx *ctx, tent_batch_t batch, uint8_t *host_out, uint64_t cap);
+
+/*
+ * Rail health monitor (Section 4.3, "Health Monitoring"), host arithmetic only, no context needed.
+ * tent_monitor_init sets n_rails records to HEALTHY.  tent_monitor_update advances them by one
+ * measurement window and writes each rail's state into rails[d].health:
+ *   - a PAUSED rail ignores its inputs; its cooldown runs down by one and at zero it returns as
+ *     DEGRADED;
+ *   - otherwise errors = 2*hard_errors[d] + congestion_errors[d] are added to the score (a window
+ *     without errors clears the score); a score above 2*err_threshold pauses the rail for
+ *     cooldown_next windows and doubles cooldown_next;
+ *   - otherwise any error, or a probe with probe_MBps[d] != 0 and
+ *     256*probe_MBps[d] < degrade_q8*bw_before_MBps[d], makes the rail DEGRADED;
+ *   - otherwise a DEGRADED rail counts a clean window and after recover_windows of them becomes
+ *     HEALTHY, with cooldown_next back at cooldown_windows.
+ * All arrays are host memory with n_rails entries (probe_MBps as returned by tent_update_bandwidth,
+ * bw_before_MBps the estimates the planner held during the window).
+ * TENT_ERR_INVALID for null pointers or a record with an unknown state, TENT_ERR_RANGE for n_rails
+ * outside [1, TENT_MAX_RAILS].
+ */
+int tent_monitor_init(const tent_monitor_params *params, tent_rail_monitor *mon, uint32_t n_rails);
+int tent_monitor_update(const tent_monitor_params *params, tent_rail_monitor *mon, tent_rail_state *rails,
+                        uint32_t n_rails, const uint32_t *hard_errors, const uint32_t *congestion_errors,
+                        const uint32_t *probe_MBps, const uint32_t *bw_before_MBps);
 
 /*
  * Rail simulator, second half (not an operation of the paper): the end-to-end latency of

@@ -270,6 +270,58 @@ def run_epochs_closed_loop(w, s: Slices, params, pools=None, staging=None):
     return records, pending
 
 
+def run_epochs_resilient(w, s: Slices, params, mp, rail_fails, congestion, pools=None, staging=None, max_passes=64):
+    """Re-planning with the telemetry loop closed and hard errors injected (Section 4.3).  Per window:
+    plan (rotation for retried slices, predicted cost for the rest) under the monitor's health states,
+    fail the slices on the rails that report a hard error, retire what the budgets allow, probe, move
+    the completed slices, step the health monitor.  rail_fails[e] / congestion[e] give the failing
+    rails and congestion-error counts of window e (none after the listed windows); after the
+    workload's epochs the drain telemetry repeats until nothing is pending."""
+    R = w.rails.shape[0]
+    pending = np.arange(s.n, dtype=np.uint32)
+    retry = np.zeros(s.n, dtype=np.uint8)
+    est = w.rails["bw_MBps"].astype(np.uint32).copy()
+    mon = monitor_init(R, mp)
+    records = []
+    e = 0
+    while e < len(w.epochs) or pending.shape[0]:
+        assert e < len(w.epochs) + max_passes, "the workload does not drain"
+        ep = w.epochs[e] if e < len(w.epochs) else w.drain
+        fails = rail_fails[e] if e < len(rail_fails) else np.zeros(R, dtype=np.uint8)
+        cong = congestion[e] if e < len(congestion) else np.zeros(R, dtype=np.uint32)
+        rails = ep.rails.copy()
+        rails["bw_MBps"] = est
+        rails["health"] = np.where(ep.rails["health"] == 2, 2, mon["state"]).astype(np.uint8)
+        rec = dict(pending=pending, rails=rails, retry=retry.copy(), status=OK, rail=None, stage_off=None,
+                   failed_per_rail=np.zeros(R, dtype=np.uint64), done_ids=pending[:0], probe=np.zeros(R, dtype=np.uint32),
+                   T=None, base=None, tau=None)
+        est_before = est.copy()
+        hard = np.zeros(R, dtype=np.uint32)
+        b = plan(s.len, retry, rails, ids=pending) if pending.shape[0] else None
+        if b is not None:
+            rec["status"] = b.status
+        if b is not None and b.status == OK:
+            failed, per_rail = fail(b, fails, retry, ids=pending)
+            hard = np.minimum(per_rail, 0xFFFFFFFF).astype(np.uint32)
+            live = np.ascontiguousarray(pending[failed == 0])
+            done = retire(s, b, rails["queued_bytes"], ep.budget, ids=live).astype(bool)
+            done_ids = np.ascontiguousarray(live[done])
+            tau = sim_latency(s, b, rails, ep.rails["bw_MBps"], ids=done_ids)
+            est, pr = probe(s, b, tau, params, est, ids=done_ids)
+            if pools is not None and done_ids.shape[0]:
+                execute(w, s, b, pools, staging, ids=done_ids)
+            rec.update(rail=b.rail[pending].copy(), stage_off=b.stage_off[pending].copy(), failed_per_rail=per_rail,
+                       done_ids=done_ids, probe=pr, tau=tau[done_ids].copy(), T=b.T, base=b.base,
+                       n_slices=b.n_slices, A_after=b.A_after)
+            pending = np.ascontiguousarray(np.setdiff1d(pending, done_ids).astype(np.uint32))
+        monitor_step(mp, mon, hard, cong, rec["probe"], est_before)
+        rec.update(retry_after=retry.copy(), est_after=est.copy(), mon_after=mon.copy(), hard=hard, cong=cong,
+                   est_before=est_before, epoch=ep)
+        records.append(rec)
+        e += 1
+    return records
+
+
 def run_epochs(w, s: Slices, pools=None, staging=None):
     """Re-planning workload: per epoch bind the pending slices under that epoch's
     telemetry, retire what the rails' byte budgets allow, move the retired slices,

@@ -11,7 +11,7 @@ import os
 
 import numpy as np
 
-from .workloads import EXTENT_DTYPE, PROBE_DTYPE, RAIL_DTYPE
+from .workloads import EXTENT_DTYPE, MONITOR_PARAMS_DTYPE, PROBE_DTYPE, RAIL_DTYPE
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libtent.so")
@@ -25,7 +25,8 @@ TENT_T_NAMES = ["extent_scan", "slice_scan", "expand", "compact", "bind", "gathe
 
 EXPORTS = ["tent_create", "tent_destroy", "tent_register_segment", "tent_declare", "tent_plan",
            "tent_sim_advance", "tent_sim_latency", "tent_update_bandwidth", "tent_get_latencies", "tent_execute", "tent_poll", "tent_reset", "tent_slice_count",
-           "tent_get_plan", "tent_get_timings", "tent_release", "tent_strerror"]
+           "tent_get_plan", "tent_get_timings", "tent_release", "tent_strerror",
+           "tent_sim_fail", "tent_get_retries", "tent_monitor_init", "tent_monitor_update"]
 
 
 class tent_config(C.Structure):
@@ -38,6 +39,9 @@ class tent_plan_info(C.Structure):
                 ("rail_bytes", C.c_uint64 * TENT_MAX_RAILS), ("rail_slices", C.c_uint64 * TENT_MAX_RAILS),
                 ("queued_after", C.c_uint64 * TENT_MAX_RAILS), ("stage_base", C.c_uint64 * TENT_MAX_RAILS)]
 
+
+MONITOR_DTYPE = np.dtype([("state", "<u4"), ("score", "<u4"), ("clean", "<u4"),
+                          ("cooldown_left", "<u4"), ("cooldown_next", "<u4")])
 
 SLICE_DTYPE = np.dtype(
     {"names": ["desc", "len", "off", "stage_off", "rail", "state"],
@@ -85,6 +89,11 @@ def lib():
         L.tent_get_plan.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
         L.tent_get_timings.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_uint32)]
         L.tent_release.argtypes = [C.c_void_p, C.c_uint64]
+        L.tent_sim_fail.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.tent_get_retries.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
+        L.tent_monitor_init.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32]
+        L.tent_monitor_update.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -151,6 +160,43 @@ def tent_sim_advance(ctx, batch: int, budget_bytes, stream=None) -> int:
     n = C.c_uint64()
     _check(lib().tent_sim_advance(ctx, batch, bp, C.byref(n), _stream(stream)), "tent_sim_advance")
     return n.value
+
+
+def tent_sim_fail(ctx, batch: int, rail_failed, want_counts: bool = True, stream=None):
+    """Returns the number of slices that failed per rail (None when not requested)."""
+    f, fp = _host(rail_failed, np.uint8)
+    out = np.zeros(f.shape[0], dtype=np.uint64) if want_counts else None
+    _check(lib().tent_sim_fail(ctx, batch, fp, out.ctypes.data_as(C.c_void_p) if want_counts else None,
+                               _stream(stream)), "tent_sim_fail")
+    return out
+
+
+def tent_get_retries(ctx, batch: int) -> np.ndarray:
+    n = tent_slice_count(ctx, batch)
+    out = np.zeros(max(n, 1), dtype=np.uint8)
+    _check(lib().tent_get_retries(ctx, batch, out.ctypes.data_as(C.c_void_p), n), "tent_get_retries")
+    return out[:n]
+
+
+def tent_monitor_init(params, n_rails: int) -> np.ndarray:
+    p, pp = _host(params, MONITOR_PARAMS_DTYPE)
+    mon = np.zeros(n_rails, dtype=MONITOR_DTYPE)
+    _check(lib().tent_monitor_init(pp, mon.ctypes.data_as(C.c_void_p), n_rails), "tent_monitor_init")
+    return mon
+
+
+def tent_monitor_update(params, mon, rails, hard_errors, congestion_errors, probe_MBps, bw_before_MBps):
+    """Advances `mon` in place by one window; returns the rails with their health fields updated."""
+    p, pp = _host(params, MONITOR_PARAMS_DTYPE)
+    r = np.ascontiguousarray(rails, dtype=RAIL_DTYPE).copy()
+    h, hp = _host(hard_errors, np.uint32)
+    c, cp = _host(congestion_errors, np.uint32)
+    pr, prp = _host(probe_MBps, np.uint32)
+    bw, bwp = _host(bw_before_MBps, np.uint32)
+    assert mon.dtype == MONITOR_DTYPE and mon.flags["C_CONTIGUOUS"]
+    _check(lib().tent_monitor_update(pp, mon.ctypes.data_as(C.c_void_p), r.ctypes.data_as(C.c_void_p), r.shape[0],
+                                     hp, cp, prp, bwp), "tent_monitor_update")
+    return r
 
 
 def tent_sim_latency(ctx, batch: int, true_bw_MBps, stream=None):

@@ -45,14 +45,22 @@ __device__ __forceinline__ uint64_t read_lane64(uint64_t v, int lane)
     return ((uint64_t)hi << 32) | lo;
 }
 
-__global__ void __launch_bounds__(64) bind_serial_kernel(BatchDev b, RailParams rp, int use_pending)
+__global__ void __launch_bounds__(64) bind_serial_kernel(BatchDev b, RailParams rp, int mode)
 {
+    const bool use_pending = (mode & kBindUsePending) != 0;
     const int lane = threadIdx.x;
     const uint64_t n = use_pending ? b.plan->n_pending : b.n_slices;
     const bool live = lane < (int)rp.n_rails && ((rp.admitted >> lane) & 1);
     const uint64_t c0 = rp.c0[lane];
     const uint32_t c1 = (uint32_t)rp.c1[lane];
     uint64_t A = rp.A[lane], T = 0, cnt = 0;
+    uint64_t n_before = 0;
+    if (mode & kBindAfterRotation) {          // the rotation pass went first: its bytes are queued and staged ahead
+        T = b.plan->Tr[lane];
+        cnt = b.plan->cr[lane];
+        A += T;
+        n_before = b.plan->n_retry;
+    }
 
     uint32_t id_next = 0, len_next = 0;
     if ((uint64_t)lane < n) {
@@ -100,14 +108,14 @@ __global__ void __launch_bounds__(64) bind_serial_kernel(BatchDev b, RailParams 
     ps->A_after[lane] = A;
     ps->base[lane] = inc - rounded;
     if (lane == 0) {
-        ps->n_bound = n;
+        ps->n_bound = n + n_before;
         if (!use_pending) ps->n_pending = n;
     }
 }
 
-hipError_t launch_bind_serial(const BatchDev& b, const RailParams& rp, bool use_pending, hipStream_t s)
+hipError_t launch_bind_serial(const BatchDev& b, const RailParams& rp, int mode, hipStream_t s)
 {
-    hipLaunchKernelGGL(bind_serial_kernel, dim3(1), dim3(64), 0, s, b, rp, use_pending ? 1 : 0);
+    hipLaunchKernelGGL(bind_serial_kernel, dim3(1), dim3(64), 0, s, b, rp, mode);
     return hipGetLastError();
 }
 

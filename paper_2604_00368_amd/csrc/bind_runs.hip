@@ -231,8 +231,9 @@ __device__ __forceinline__ uint32_t slots_upto_fast(const Rail& r, uint64_t A, u
 
 // kWide = 16, 32 or 64: lanes that can hold a rail; with 16 every reduction stays inside one DPP row.
 template <int kWide>
-__global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams rp, int use_pending)
+__global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams rp, int mode)
 {
+    const bool use_pending = (mode & kBindUsePending) != 0;
     const int lane = threadIdx.x;
     constexpr int R = kWide;                                  // reduction width
     const int n_rails = (int)rp.n_rails;
@@ -247,6 +248,13 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
     const double g = (double)rail.c0 * G;                     // its fixed latency expressed in bytes
     const double c0d1 = 1.0 - (double)rail.c0;               // 1 - c0 as a double (c0 < 2^53)
     uint64_t A = rp.A[lane], T = 0, cnt = 0;
+    uint64_t n_before = 0;
+    if (mode & kBindAfterRotation) {          // the rotation pass went first: its bytes are queued and staged ahead
+        T = b.plan->Tr[lane];
+        cnt = b.plan->cr[lane];
+        A += T;
+        n_before = b.plan->n_retry;
+    }
     double Ad = (double)A;                                    // floating-point shadow of A, estimates only
     const uint64_t n_runs = b.plan->n_runs;
     const uint32_t stride = b.run_stride;
@@ -466,7 +474,7 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
     ps->cnt[lane] = cnt;
     ps->A_after[lane] = A;
     ps->base[lane] = inc - rounded;
-    if (lane == 0) ps->n_bound = ps->n_pending;
+    if (lane == 0) ps->n_bound = ps->n_pending + n_before;
 }
 
 // ---- step 3: emit -----------------------------------------------------------------------------
@@ -535,8 +543,9 @@ __global__ void __launch_bounds__(256) bind_emit_kernel(BatchDev b, RailParams r
 
 }  // namespace
 
-hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, bool use_pending, hipStream_t s)
+hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, hipStream_t s)
 {
+    const bool use_pending = (mode & kBindUsePending) != 0;
     const int up = use_pending ? 1 : 0;
     if (!use_pending) hipLaunchKernelGGL(set_pending_all_kernel, dim3(1), dim3(1), 0, s, b);
     RunHead head{b.s_len, use_pending ? b.pending : nullptr, &b.plan->n_pending};
@@ -545,9 +554,9 @@ hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, bool use_pe
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(run_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, up);
-    if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, up);
-    else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, up);
-    else                       hipLaunchKernelGGL(bind_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, up);
+    if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, mode);
+    else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, mode);
+    else                       hipLaunchKernelGGL(bind_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, mode);
     hipLaunchKernelGGL(bind_emit_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, rp, up);
     return hipGetLastError();
 }

@@ -227,24 +227,38 @@ hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s)
     return hipGetLastError();
 }
 
-// ---- E1: ascending list of slices that are not DONE -----------------------------------------
-struct NotDone {
+// ---- E1: ascending lists of slices that are not DONE ------------------------------------------
+// Two lists from one scan: slices that never failed (bound by predicted cost) are counted in the
+// low half of the scanned word, slices with a retry count (bound by rotation) in the high half.
+struct NotDoneSplit {
     const uint8_t* state;
-    __device__ uint64_t operator()(uint64_t i) const { return state[i] != TENT_SLICE_DONE; }
+    const uint8_t* retry;
+    __device__ uint64_t operator()(uint64_t i) const
+    {
+        if (state[i] == TENT_SLICE_DONE) return 0;
+        return retry[i] ? (1ull << 32) : 1ull;
+    }
 };
 
 __global__ void __launch_bounds__(256) compact_kernel(BatchDev b)
 {
     const uint64_t n = b.n_slices;
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
-        if (b.s_state[i] != TENT_SLICE_DONE) b.pending[b.scan_tmp[i]] = (uint32_t)i;
-    if (blockIdx.x == 0 && threadIdx.x == 0) b.plan->n_pending = b.scan_tmp[n];
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        if (b.s_state[i] == TENT_SLICE_DONE) continue;
+        const uint64_t at = b.scan_tmp[i];
+        if (b.s_retry[i]) b.retry_ids[at >> 32] = (uint32_t)i;
+        else              b.pending[at & 0xFFFFFFFFu] = (uint32_t)i;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        b.plan->n_pending = b.scan_tmp[n] & 0xFFFFFFFFu;
+        b.plan->n_retry = b.scan_tmp[n] >> 32;
+    }
 }
 
 hipError_t launch_compact(const BatchDev& b, hipStream_t s)
 {
-    hipError_t e = exclusive_scan(NotDone{b.s_state}, b.n_slices, b.scan_tmp, b.scan_partials, s);
+    hipError_t e = exclusive_scan(NotDoneSplit{b.s_state, b.s_retry}, b.n_slices, b.scan_tmp, b.scan_partials, s);
     if (e != hipSuccess) return e;
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
@@ -271,8 +285,10 @@ hipError_t launch_mark_done(const BatchDev& b, hipStream_t s)
 __global__ void __launch_bounds__(256) reset_kernel(BatchDev b)
 {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slices; i += stride)
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slices; i += stride) {
         b.s_state[i] = TENT_SLICE_PENDING;
+        b.s_retry[i] = 0;
+    }
 }
 
 hipError_t launch_reset(const BatchDev& b, hipStream_t s)

@@ -18,6 +18,7 @@ struct Batch {
     bool alive = false;
     bool planned = false;        // a plan has been enqueued since declare / reset
     bool has_done = false;       // execute ran since declare / reset: DONE slices may exist
+    bool has_retry = false;      // a rail failed since declare / reset: slices with a retry count may exist
     uint32_t generation = 0;
     uint64_t payload = 0;
     RailParams last_rails{};     // telemetry of the last plan (for the rail simulator)
@@ -325,6 +326,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_state, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_tau, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_rec, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_retry, n_slices);
     BatchDev* self_dev = nullptr;
     if (rc == TENT_OK) rc = dev_alloc(b, &self_dev, 1);
     if (d.n_sc_tiles == 0) {                              // per-slice tile tables only for untiled geometry
@@ -350,6 +352,10 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_x, d.n_sc_tiles);
     }
     if (rc == TENT_OK) rc = dev_alloc(b, &d.pending, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.retry_ids, n_slices);
+    const uint64_t rot_chunks = (n_slices + kRotChunk - 1) / kRotChunk;
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.rot_bytes, rot_chunks * TENT_MAX_RAILS);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.rot_cnt, rot_chunks * TENT_MAX_RAILS);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_tmp, scan_n + 1);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_partials, scan_partials_capacity(scan_n));
     if (rc == TENT_OK) rc = dev_alloc(b, &d.plan, 1);
@@ -363,6 +369,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
         hipMemcpy(se, src_ext, sizeof(tent_extent) * ns, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(de, dst_ext, sizeof(tent_extent) * nd, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(self_dev, &d, sizeof(BatchDev), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemset(d.s_retry, 0, std::max<uint64_t>(n_slices, 1)) != hipSuccess ||
         hipMemset(d.plan, 0, sizeof(PlanState)) != hipSuccess) {
         (void)hipGetLastError();
         free_batch(b);
@@ -403,7 +410,21 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BatchDev& d = b->dev;
 
-    const bool replan = b->has_done;
+    // Retry rotation (Section 4.3, "Link-Level Resilience"): candidates are the HEALTHY rails, else the
+    // DEGRADED rails without topology penalty, else every DEGRADED rail, in ascending index.
+    RotateParams rot;
+    std::memset(&rot, 0, sizeof(rot));
+    if (b->has_retry) {
+        for (int pass = 0; pass < 3 && rot.n_cand == 0; ++pass)
+            for (uint32_t r = 0; r < n_rails; ++r) {
+                const bool take = pass == 0 ? rails[r].health == 0
+                                : pass == 1 ? rails[r].health == 1 && rails[r].penalty_q8 <= 256
+                                            : rails[r].health == 1;
+                if (take) rot.cand[rot.n_cand++] = (uint8_t)r;
+            }
+    }
+
+    const bool replan = b->has_done || b->has_retry;
     if (!replan) {
         {
             StageTimer t(ctx, TENT_T_EXTENT_SCAN, s);
@@ -423,6 +444,12 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
         StageTimer t(ctx, TENT_T_COMPACT, s);
         HIP_TRY(launch_compact(d, s));
     }
+    int mode = replan ? kBindUsePending : 0;
+    if (b->has_retry) {
+        StageTimer t(ctx, TENT_T_BIND, s);
+        HIP_TRY(launch_rotate(d, rot, s));
+        mode |= kBindAfterRotation;
+    }
     {
         StageTimer t(ctx, TENT_T_BIND, s);
         // the run-parallel chain divides by c1, so a rail whose cost does not grow with bytes
@@ -430,8 +457,8 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
         bool serial = (ctx->cfg.flags & TENT_FLAG_SERIAL_BINDING) != 0;
         for (uint32_t r = 0; r < n_rails; ++r)
             if (((rp.admitted >> r) & 1) && rp.c1[r] == 0) serial = true;
-        if (serial) HIP_TRY(launch_bind_serial(d, rp, replan, s));
-        else        HIP_TRY(launch_bind_runs(d, rp, replan, s));
+        if (serial) HIP_TRY(launch_bind_serial(d, rp, mode, s));
+        else        HIP_TRY(launch_bind_runs(d, rp, mode, s));
     }
     b->planned = true;
     b->last_rails = rp;
@@ -474,6 +501,52 @@ int tent_sim_advance(tent_ctx* ctx, tent_batch_t batch, const uint64_t* budget_b
     HIP_TRY(hipMemcpyAsync(ctx->host_plan, b->dev.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     if (n_done) *n_done = ctx->host_plan->n_done;
+    return TENT_OK;
+}
+
+int tent_sim_fail(tent_ctx* ctx, tent_batch_t batch, const uint8_t* rail_failed, uint64_t* failed_per_rail,
+                  void* stream)
+{
+    if (!ctx || !rail_failed) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (!b->planned) return TENT_ERR_STATE;
+    const uint32_t n_rails = b->last_rails.n_rails;
+    FailParams fp;
+    std::memset(&fp, 0, sizeof(fp));
+    bool any = false;
+    for (uint32_t d = 0; d < n_rails; ++d) {
+        fp.failed[d] = rail_failed[d] ? 1 : 0;
+        any = any || rail_failed[d];
+    }
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (any) {
+        HIP_TRY(launch_fail(b->dev, fp, s));
+        b->has_retry = true;
+    }
+    if (failed_per_rail) {
+        for (uint32_t d = 0; d < n_rails; ++d) failed_per_rail[d] = 0;
+        if (any) {
+            HIP_TRY(hipMemcpyAsync(ctx->host_plan, b->dev.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
+            HIP_TRY(hipStreamSynchronize(s));
+            for (uint32_t d = 0; d < n_rails; ++d) failed_per_rail[d] = ctx->host_plan->fail_cnt[d];
+        }
+    }
+    return TENT_OK;
+}
+
+int tent_get_retries(tent_ctx* ctx, tent_batch_t batch, uint8_t* host_out, uint64_t cap)
+{
+    if (!ctx || !host_out) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (cap < b->dev.n_slices) return TENT_ERR_RANGE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(host_out, b->dev.s_retry, b->dev.n_slices, hipMemcpyDeviceToHost));
     return TENT_OK;
 }
 
@@ -598,6 +671,7 @@ int tent_reset(tent_ctx* ctx, tent_batch_t batch, void* stream)
     if (b->planned) HIP_TRY(launch_reset(b->dev, static_cast<hipStream_t>(stream)));
     b->planned = false;
     b->has_done = false;
+    b->has_retry = false;
     return TENT_OK;
 }
 

@@ -40,6 +40,17 @@ struct BudgetParams {
     uint64_t budget[TENT_MAX_RAILS];
 };
 
+// Candidate rails of the retry rotation (Section 4.3, "Link-Level Resilience"), in rotation order.
+struct RotateParams {
+    uint8_t  cand[TENT_MAX_RAILS];
+    uint32_t n_cand;
+};
+
+// Rails that report a hard error to the rail simulator.
+struct FailParams {
+    uint8_t failed[TENT_MAX_RAILS];
+};
+
 // Device-resident result block of one plan (read back only when the caller asks for it).
 struct PlanState {
     uint64_t n_pending;                   // slices considered by the plan
@@ -54,6 +65,10 @@ struct PlanState {
     uint64_t peak[TENT_MAX_RAILS];        // bandwidth probe: 1 + best sample of the window, 0 = no sample
     uint32_t probe[TENT_MAX_RAILS];       // B_probe per rail (0 = no sample)
     uint32_t bw_next[TENT_MAX_RAILS];     // smoothed estimate after the window
+    uint64_t n_retry;                     // retried slices considered by the plan (bound by rotation)
+    uint64_t Tr[TENT_MAX_RAILS];          // bytes the rotation pass bound per rail
+    uint64_t cr[TENT_MAX_RAILS];          // slices the rotation pass bound per rail
+    uint64_t fail_cnt[TENT_MAX_RAILS];    // tent_sim_fail: slices that failed per rail
 };
 
 // What a copy workgroup needs to know about its slice, in one 16-byte scalar load.
@@ -87,6 +102,7 @@ struct BatchDev {
     uint64_t* s_stage_off;
     uint8_t*  s_state;
     uint64_t* s_tau;               // recorded end-to-end latency in ns (rail simulator / telemetry)
+    uint8_t*  s_retry;             // times the slice failed on a rail (saturates at 255)
 
     struct SliceRec* s_rec;        // packed copy record per slice, rebuilt by every tent_execute
     const BatchDev* self;          // device copy of this structure (generic copy path)
@@ -122,7 +138,10 @@ struct BatchDev {
     uint32_t  run_capacity;        // 2 * n_desc
     uint32_t  run_stride;          // rails per row
 
-    uint32_t* pending;             // [n_slices] ascending ids of slices not DONE (re-planning)
+    uint32_t* pending;             // [n_slices] ascending ids of slices not DONE and never failed (re-planning)
+    uint32_t* retry_ids;           // [n_slices] ascending ids of slices not DONE with a retry count > 0
+    uint64_t* rot_bytes;           // [ceil(n_slices / kRotChunk) * TENT_MAX_RAILS] rotation pass: bytes per chunk and rail
+    uint32_t* rot_cnt;             // same shape: slices per chunk and rail
     uint64_t* scan_tmp;            // [max(n_ext, n_slices, n_desc)+1] scan workspace
     uint64_t* scan_partials;       // per-block partial sums of the scans
     PlanState* plan;               // one result block
@@ -132,6 +151,9 @@ struct BatchDev {
 enum : uint32_t { kScanBlock = 256, kScanItems = 8, kScanTile = kScanBlock * kScanItems };
 enum : uint32_t { kCopyBlockBytes = 4096 };          // bytes one copy workgroup moves (256 lanes x 16 B)
 constexpr uint64_t kTileSlow = 1ull << 63;
+enum : uint32_t { kRotChunk = 1024 };                // retried slices one rotation workgroup handles
+// `mode` argument of the bind kernels
+enum : int { kBindUsePending = 1, kBindAfterRotation = 2 };
 
 // ---- launch wrappers (each enqueues on `s` and returns the launch status) -------------------
 hipError_t launch_extent_scan(const tent_extent* ext, uint64_t n_ext, uint64_t* pre, uint64_t* partials,
@@ -139,8 +161,10 @@ hipError_t launch_extent_scan(const tent_extent* ext, uint64_t n_ext, uint64_t* 
 hipError_t launch_slice_scan(const BatchDev& b, hipStream_t s);
 hipError_t launch_expand(const BatchDev& b, hipStream_t s);
 hipError_t launch_compact(const BatchDev& b, hipStream_t s);
-hipError_t launch_bind_serial(const BatchDev& b, const RailParams& rp, bool use_pending, hipStream_t s);
-hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, bool use_pending, hipStream_t s);
+hipError_t launch_bind_serial(const BatchDev& b, const RailParams& rp, int mode, hipStream_t s);
+hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, hipStream_t s);
+hipError_t launch_rotate(const BatchDev& b, const RotateParams& rot, hipStream_t s);
+hipError_t launch_fail(const BatchDev& b, const FailParams& fp, hipStream_t s);
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
 hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s);
 hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s);

@@ -34,6 +34,8 @@ RAIL_DTYPE = np.dtype(
      "offsets": [0, 4, 8, 16, 18, 20], "itemsize": 24})
 
 # struct { uint32 hw_MBps; uint32 alpha_q8; uint32 delta_ns; uint32 ewma_q8; }  -- 16 bytes
+MONITOR_PARAMS_DTYPE = np.dtype([("err_threshold", "<u4"), ("recover_windows", "<u4"),
+                                 ("cooldown_windows", "<u4"), ("degrade_q8", "<u4")])
 PROBE_DTYPE = np.dtype(
     {"names": ["hw_MBps", "alpha_q8", "delta_ns", "ewma_q8"], "formats": ["<u4"] * 4,
      "offsets": [0, 4, 8, 12], "itemsize": 16})
@@ -57,6 +59,21 @@ def make_rails(bw_MBps, lat_ns=5000, queued=0, health=0, beta1_q8=256, penalty_q
     r["penalty_q8"] = penalty_q8
     r["health"] = health
     return r
+
+
+def make_monitor_params(err_threshold=8, recover_windows=2, cooldown_windows=1, degrade_q8=128):
+    """Parameters of the rail health monitor (thresholds in events, times in measurement windows)."""
+    return np.array([(err_threshold, recover_windows, cooldown_windows, degrade_q8)], dtype=MONITOR_PARAMS_DTYPE)
+
+
+def failure_schedule(seed, n_windows, n_rails, p_fail=0.08, p_congestion=0.15, max_congestion=12):
+    """Seeded fault injection: per window and rail, whether the rail reports a hard error and how many
+    congestion errors it reports.  Returns (uint8[n_windows, n_rails], uint32[n_windows, n_rails])."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    fails = (rng.random((n_windows, n_rails)) < p_fail).astype(np.uint8)
+    cong = (rng.integers(1, max_congestion + 1, size=(n_windows, n_rails)) *
+            (rng.random((n_windows, n_rails)) < p_congestion)).astype(np.uint32)
+    return fails, cong
 
 
 def make_probe_params(hw_MBps, alpha_q8=256, delta_ns=5000, ewma_q8=64):

@@ -1,0 +1,172 @@
+"""GPU parity for the resilience path (Section 4.3): failure marking, retry rotation ahead of the cost
+model, and the rail health monitor, against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2604_00368_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_harness
+    return gpu_harness
+
+
+def run_resilient_and_compare(H, oracle, w, params, mp, fails, cong, flags=0, bytes_too=True):
+    from paper_2604_00368_amd import binding as T
+    R = w.rails.shape[0]
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    src = W.fill_numpy(w, 0) if bytes_too else None
+    dst0 = W.fill_numpy(w, 1) if bytes_too else None
+    dst_want = dst0.copy() if bytes_too else None
+    staging_want = np.zeros(w.staging_bytes, dtype=np.uint8) if bytes_too else None
+    recs = oracle.run_epochs_resilient(w, s, params, mp, fails, cong, [src, dst_want] if bytes_too else None,
+                                       staging_want)
+    eng = H.Engine(w, src, dst0, flags=flags) if bytes_too else H.Engine(w, flags=flags)
+    try:
+        eng.declare()
+        mon = T.tent_monitor_init(mp, R)
+        est = w.rails["bw_MBps"].astype(np.uint32).copy()
+        health = np.zeros(R, dtype=np.uint8)
+        for e, rec in enumerate(recs):
+            ep = rec["epoch"]
+            print("resilient window", e, "pending", rec["pending"].shape[0], "retried",
+                  int((rec["retry"][rec["pending"]] > 0).sum()), "health", rec["rails"]["health"].tolist(), flush=True)
+            rails = ep.rails.copy()
+            rails["bw_MBps"] = est
+            rails["health"] = np.where(ep.rails["health"] == 2, 2, health).astype(np.uint8)
+            assert np.array_equal(rails, rec["rails"])
+            assert np.array_equal(T.tent_get_retries(eng.ctx, eng.batch), rec["retry"])
+            hard = np.zeros(R, dtype=np.uint32)
+            probe = np.zeros(R, dtype=np.uint32)
+            if rec["pending"].shape[0]:
+                st, info = eng.plan(rails=rails)
+                assert st == rec["status"]
+            else:
+                st = -99
+            if st == 0:
+                pend = rec["pending"]
+                assert info.n_slices == pend.shape[0]
+                tab = eng.table()
+                assert np.array_equal(np.nonzero(tab["state"] != 2)[0], pend)
+                assert np.array_equal(tab["rail"][pend], rec["rail"])
+                assert np.array_equal(tab["stage_off"][pend], rec["stage_off"])
+                assert list(info.rail_bytes)[:R] == rec["T"].tolist()
+                assert list(info.rail_slices)[:R] == rec["n_slices"].tolist()
+                assert list(info.queued_after)[:R] == rec["A_after"].tolist()
+                assert list(info.stage_base)[:R] == rec["base"].tolist()
+                fl = fails[e] if e < len(fails) else np.zeros(R, dtype=np.uint8)
+                per_rail = T.tent_sim_fail(eng.ctx, eng.batch, fl, True, eng.stream)
+                assert np.array_equal(per_rail, rec["failed_per_rail"])
+                hard = np.minimum(per_rail, 0xFFFFFFFF).astype(np.uint32)
+                n_done = T.tent_sim_advance(eng.ctx, eng.batch, ep.budget, eng.stream)
+                assert n_done == rec["done_ids"].shape[0]
+                tab = eng.table()
+                assert np.array_equal(np.nonzero(tab["state"] == 1)[0], rec["done_ids"])
+                T.tent_sim_latency(eng.ctx, eng.batch, ep.rails["bw_MBps"], eng.stream)
+                new_rails, probe = T.tent_update_bandwidth(eng.ctx, eng.batch, params, rails, eng.stream)
+                assert np.array_equal(probe, rec["probe"])
+                tau = T.tent_get_latencies(eng.ctx, eng.batch)
+                assert np.array_equal(tau[rec["done_ids"]], rec["tau"])
+                eng.execute()
+                est_before = est
+                est = new_rails["bw_MBps"].astype(np.uint32)
+            else:
+                est_before = est
+            assert np.array_equal(est, rec["est_after"])
+            cg = cong[e] if e < len(cong) else np.zeros(R, dtype=np.uint32)
+            out = T.tent_monitor_update(mp, mon, rails, hard, cg, probe, est_before)
+            for f in mon.dtype.names:
+                assert np.array_equal(mon[f], rec["mon_after"][f]), f
+            health = out["health"].copy()
+            assert np.array_equal(health, rec["mon_after"]["state"].astype(np.uint8))
+            assert np.array_equal(T.tent_get_retries(eng.ctx, eng.batch), rec["retry_after"])
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        if bytes_too:
+            assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+            assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+    finally:
+        eng.close()
+    return recs
+
+
+@pytest.mark.parametrize("seed", [5, 6])
+def test_faulty_rails_closed_loop_bit_exact(H, oracle, seed):
+    from paper_2604_00368_amd import binding as T
+    w = W.replanning(n_req=6, layers=4, ctx_lo=400, ctx_hi=2000, queued_hi=1 << 20)
+    R = w.rails.shape[0]
+    params = W.make_probe_params(2 * w.rails["bw_MBps"].astype(np.uint64), ewma_q8=128)
+    fails, cong = W.failure_schedule(seed, len(w.epochs), R)
+    recs = run_resilient_and_compare(H, oracle, w, params, W.make_monitor_params(), fails, cong)
+    assert any((r["retry"][r["pending"]] > 0).any() for r in recs)
+    if seed == 5:
+        run_resilient_and_compare(H, oracle, w, params, W.make_monitor_params(), fails, cong,
+                                  flags=T.TENT_FLAG_SERIAL_BINDING)
+
+
+def test_everything_fails_at_once(H, oracle):
+    # every rail reports a hard error in the first window: the whole batch is retried by rotation, the
+    # cost-model pass has nothing left to bind, and the rails are paused for a window
+    w = W.small_variant("kv_migration")
+    R = w.rails.shape[0]
+    w.epochs = [W.Epoch(w.rails.copy(), np.full(R, np.iinfo(np.uint64).max, dtype=np.uint64)) for _ in range(2)]
+    w.drain = w.epochs[0]
+    params = W.make_probe_params(2 * w.rails["bw_MBps"].astype(np.uint64))
+    fails = np.zeros((2, R), dtype=np.uint8)
+    fails[0, :] = 1
+    cong = np.zeros((2, R), dtype=np.uint32)
+    mp = W.make_monitor_params(err_threshold=2, cooldown_windows=0)       # zero-length pause: straight to DEGRADED
+    recs = run_resilient_and_compare(H, oracle, w, params, mp, fails, cong)
+    assert (recs[1]["retry"] == 1).all() and (recs[1]["rails"]["health"] == 1).all()
+    mp = W.make_monitor_params(err_threshold=2, cooldown_windows=1)       # one window with every rail paused: deferred
+    recs = run_resilient_and_compare(H, oracle, w, params, mp, fails, cong)
+    assert recs[1]["status"] == 1
+
+
+def test_many_small_retries_span_rotation_chunks(H, oracle):
+    # enough retried slices of mixed lengths for several rotation workgroups, 16 rails, no byte movement
+    w = W.many_small(n_req=640)
+    R = w.rails.shape[0]
+    rng = np.random.Generator(np.random.PCG64(31))
+    epochs = []
+    t_us = -(-w.payload // int(4 * int(w.rails["bw_MBps"].astype(np.uint64).sum())))
+    for e in range(5):
+        bw = np.maximum(1, np.rint(w.rails["bw_MBps"] * np.exp(0.3 * rng.standard_normal(R)))).astype(np.uint64)
+        rails = W.make_rails(bw, queued=rng.integers(0, 1 << 20, size=R),
+                             penalty_q8=rng.choice([256, 256, 320], size=R))
+        epochs.append(W.Epoch(rails, bw * np.uint64(t_us)))
+    w.epochs = epochs
+    w.drain = W.Epoch(epochs[-1].rails.copy(), np.full(R, np.iinfo(np.uint64).max, dtype=np.uint64))
+    params = W.make_probe_params(2 * w.rails["bw_MBps"].astype(np.uint64), ewma_q8=64)
+    fails, cong = W.failure_schedule(9, len(epochs), R, p_fail=0.3)
+    recs = run_resilient_and_compare(H, oracle, w, params, W.make_monitor_params(err_threshold=4), fails, cong,
+                                     bytes_too=False)
+    assert max(int((r["retry"][r["pending"]] > 0).sum()) for r in recs) > 2 * 1024
+
+
+def test_fail_argument_errors(H, oracle):
+    from paper_2604_00368_amd import binding as T
+    w = W.tiny()
+    with H.Engine(w, W.fill_numpy(w, 0), W.fill_numpy(w, 1)) as eng:
+        h = eng.declare()
+        with pytest.raises(T.TentError) as ei:
+            T.tent_sim_fail(eng.ctx, h, np.zeros(4, dtype=np.uint8))
+        assert ei.value.status == T.TENT_ERR_STATE
+        assert not T.tent_get_retries(eng.ctx, h).any()
+        eng.plan()
+        assert T.tent_sim_fail(eng.ctx, h, np.zeros(4, dtype=np.uint8)).tolist() == [0, 0, 0, 0]
+        counts = T.tent_sim_fail(eng.ctx, h, np.array([0, 0, 1, 0], dtype=np.uint8))
+        tab = eng.table()
+        assert counts.tolist() == [0, 0, int(((tab["rail"] == 2)).sum()), 0]
+        assert np.array_equal(T.tent_get_retries(eng.ctx, h), (tab["rail"] == 2).astype(np.uint8))
+        T.tent_reset(eng.ctx, h, eng.stream)                      # reset forgets the retry counts
+        assert not T.tent_get_retries(eng.ctx, h).any()
+        s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+        st, info = eng.plan()
+        H.assert_plan_equal(eng.table(), s, oracle.bind(s.len, w.rails), info)

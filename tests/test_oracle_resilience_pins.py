@@ -287,3 +287,35 @@ def test_monitor_states_steer_the_plan(oracle):
     lens = np.full(300, 64 * KiB, dtype=np.uint32)
     b = oracle.bind(lens, rails)
     assert b.n_slices.tolist() == [200, 100, 0]
+
+
+# ------------------------------------------------------------------------------ the loop as a whole
+def test_resilient_epochs_deliver_every_byte_exactly_once(oracle):
+    # Section 4.3: faults are absorbed below the batch; whatever fails, the destination ends up as the plain
+    # definition says and every slice completes exactly once.
+    from helpers import expected_destination
+    w = W.small_variant("replanning")
+    R = w.rails.shape[0]
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
+    dst = dst0.copy()
+    staging = np.zeros(w.staging_bytes, dtype=np.uint8)
+    params = W.make_probe_params(2 * w.rails["bw_MBps"].astype(np.uint64), ewma_q8=128)
+    fails, cong = W.failure_schedule(5, len(w.epochs), R)
+    assert fails.any() and cong.any()
+    recs = oracle.run_epochs_resilient(w, s, params, W.make_monitor_params(), fails, cong, [src, dst], staging)
+    assert np.array_equal(dst, expected_destination(w, src, dst0))
+    done = np.concatenate([r["done_ids"] for r in recs])
+    assert np.array_equal(np.sort(done), np.arange(s.n))
+    assert sum(int(r["failed_per_rail"].sum()) for r in recs) == int(recs[-1]["retry_after"].astype(int).sum()) > 0
+    states = np.stack([r["mon_after"]["state"] for r in recs])
+    assert (states == 1).any() and (states == 2).any()            # the schedule reaches every health state
+    for r in recs:
+        if r["rail"] is None:
+            continue
+        # a slice never rides a rail that was excluded when it was planned
+        assert (r["rails"]["health"][r["rail"]] != 2).all()
+        # retried slices sit on HEALTHY rails whenever one exists
+        k = r["retry"][r["pending"]]
+        if (r["rails"]["health"] == 0).any():
+            assert (r["rails"]["health"][r["rail"][k > 0]] == 0).all()
