@@ -218,6 +218,29 @@ def main():
         T.tent_update_bandwidth(ctx, h_fb, fb_params, w.rails, stream)
     fb_ms, fb_n = T.tent_get_timings(ctx)["feedback"]
 
+    # Recovery after a hard error (Section 4.3), outside the timed region: the fastest rail fails with the
+    # whole batch bound, its slices come back with a retry count, and the next plan (compaction into
+    # retried and fresh slices, rotation pass, cost-model pass) is timed.
+    R = int(w.rails.shape[0])
+    fastest = int(np.argmax(w.rails["bw_MBps"]))
+    failed_mask = np.zeros(R, dtype=np.uint8)
+    failed_mask[fastest] = 1
+    after = w.rails.copy()
+    after["health"][fastest] = 2
+    rec_ms, n_retried = [], 0
+    if R > 1:
+        for _ in range(3):
+            T.tent_reset(ctx, h_fb, stream)
+            T.tent_plan(ctx, h_fb, w.rails, want_info=False, stream=stream)
+            n_retried = int(T.tent_sim_fail(ctx, h_fb, failed_mask, True, stream)[fastest])
+            torch.cuda.synchronize(dev)
+            T.tent_get_timings(ctx)
+            T.tent_plan(ctx, h_fb, after, want_info=False, stream=stream)
+            torch.cuda.synchronize(dev)
+            tm_rec = T.tent_get_timings(ctx)
+            rec_ms.append(tm_rec["compact"][0] + tm_rec["bind"][0])
+    T.tent_reset(ctx, h_fb, stream)
+
     # Plain copy of known size (1 GiB read + 1 GiB written by one elementwise kernel), outside the
     # timed region: the practical copy ceiling of the box and the reference dispatch that scales
     # hardware byte counters when this script runs under a counter-collecting profiler.
@@ -263,6 +286,8 @@ def main():
         "declare_ms": round(declare_ms, 3),
         "feedback": {"window_slices": n_slices, "ms_per_window": round(fb_ms / max(1, fb_n), 4),
                      "bytes_per_slice": 17},
+        "recovery": {"failed_rail": fastest, "retried_slices": n_retried, "replanned_slices": n_slices,
+                     "replan_ms": round(min(rec_ms), 4) if rec_ms else None},
         "plain_copy_GBps": round(plain_copy_GBps, 2),
         "roofline": {"bound": "hbm", "kernel": "ordered_copy_kernel (%s launch)" % dom, "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),

@@ -154,3 +154,20 @@ def test_full_size_closed_loop(H, oracle):
     P.run_closed_loop_and_compare(H, oracle, w, params, bytes_too=False)
     gc.collect()
     torch.cuda.empty_cache()
+
+
+def test_full_size_faulty_rails(H, oracle):
+    # config 4 with hard errors injected, the telemetry loop closed and the health monitor in charge of the
+    # rails' states: every window's plan (rotation pass included), failures, probes and monitor records
+    # against the oracle; at the end every destination byte by the plain definition
+    import test_gpu_resilience as Rz
+    print("full-size faulty rails", flush=True)
+    w = W.replanning()
+    R = w.rails.shape[0]
+    params = W.make_probe_params(2 * w.rails["bw_MBps"].astype(np.uint64), ewma_q8=64)
+    fails, cong = W.failure_schedule(12, len(w.epochs), R)
+    recs = Rz.run_resilient_and_compare(H, oracle, w, params, W.make_monitor_params(), fails, cong, bytes_too=False,
+                                        final_check=lambda eng: device_definition_check(w, eng.src, eng.dst))
+    assert max(int((r["retry"][r["pending"]] > 0).sum()) for r in recs) > 4 * 1024
+    gc.collect()
+    torch.cuda.empty_cache()

@@ -18,7 +18,7 @@ def H():
     return gpu_harness
 
 
-def run_resilient_and_compare(H, oracle, w, params, mp, fails, cong, flags=0, bytes_too=True):
+def run_resilient_and_compare(H, oracle, w, params, mp, fails, cong, flags=0, bytes_too=True, final_check=None):
     from paper_2604_00368_amd import binding as T
     R = w.rails.shape[0]
     s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
@@ -91,6 +91,8 @@ def run_resilient_and_compare(H, oracle, w, params, mp, fails, cong, flags=0, by
         if bytes_too:
             assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
             assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+        if final_check is not None:
+            final_check(eng)
     finally:
         eng.close()
     return recs
