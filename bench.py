@@ -29,21 +29,23 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per copy launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
 # plain-copy calibration dispatch of the same run; summaries under profiles/).  The figures belong
-# to one version of the copy kernel source: when copy.hip changes they are reported as null.
+# to one version of the copy kernels and of the kernels that build their tables: when copy.hip or
+# split.hip changes they are reported as null.
 PMC_TRAFFIC = {
-    "copy_hip_sha256": "e0d8de25db98adf0b620fd6a59409e6ea88291c8e46d68551c96c5f180f74c5d",
-    "kv_migration": {"gather": 42713234077, "scatter": 43019354183},
+    "copy_sources_sha256": "b8d8e760afa366467806bca88108ba534c87cb511efbf1825e1b504c762d56f6",
+    "kv_migration": {"gather": 43019338055, "scatter": 43019354695},
 }
 
 
 def measured_traffic(workload, kernel):
     import hashlib
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_00368_amd", "csrc", "copy.hip")
+    csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_00368_amd", "csrc")
     try:
-        digest = hashlib.sha256(open(path, "rb").read()).hexdigest()
+        digest = hashlib.sha256(open(os.path.join(csrc, "copy.hip"), "rb").read() +
+                                open(os.path.join(csrc, "split.hip"), "rb").read()).hexdigest()
     except OSError:
         return None
-    if digest != PMC_TRAFFIC["copy_hip_sha256"]:
+    if digest != PMC_TRAFFIC["copy_sources_sha256"]:
         return None
     return PMC_TRAFFIC.get(workload, {}).get(kernel)
 
@@ -289,7 +291,7 @@ def main():
         "recovery": {"failed_rail": fastest, "retried_slices": n_retried, "replanned_slices": n_slices,
                      "replan_ms": round(min(rec_ms), 4) if rec_ms else None},
         "plain_copy_GBps": round(plain_copy_GBps, 2),
-        "roofline": {"bound": "hbm", "kernel": "ordered_copy_kernel (%s launch)" % dom, "achieved": round(achieved, 2),
+        "roofline": {"bound": "hbm", "kernel": "ordered_copy_kernel<%s>" % ("true" if dom == "gather" else "false"), "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": measured_traffic(args.workload, dom),
                      "algorithmic_bytes_per_launch": 2 * w.payload,

@@ -152,7 +152,9 @@ static hipError_t launch_copy_lanes(const BatchDev& b, hipStream_t s)
 // source bytes in declaration order (reads hop between pages, every rail region is written front to
 // back); scatter walks the destination bytes in ascending device address (reads hop between the
 // rail regions, writes are sequential) -- HBM tolerates scattered reads better than scattered
-// writes.  Only used when no tile crosses an extent boundary.
+// writes.  Only used when no tile crosses an extent boundary.  kGather only names the direction
+// (the two launches show up separately in a kernel trace); the code is the same.
+template <bool kGather>
 __global__ void __launch_bounds__(256) ordered_copy_kernel(const uint64_t* __restrict__ from,
                                                            const uint64_t* __restrict__ to,
                                                            uint64_t n_tiles, uint32_t tile_shift)
@@ -179,8 +181,12 @@ hipError_t launch_copy_ordered(const BatchDev& b, bool gather, hipStream_t s)
     const uint32_t gx = blocks < 65536 ? (uint32_t)blocks : 65536u;
     const uint64_t gy = (blocks + gx - 1) / gx;
     if (gy > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(ordered_copy_kernel, dim3(gx, (uint32_t)gy), dim3(256), 0, s,
-                       gather ? b.ga_src : b.sc_lin, gather ? b.ga_lin : b.sc_dst, b.n_sc_tiles, tile_shift);
+    if (gather)
+        hipLaunchKernelGGL(ordered_copy_kernel<true>, dim3(gx, (uint32_t)gy), dim3(256), 0, s,
+                           b.ga_src, b.ga_lin, b.n_sc_tiles, tile_shift);
+    else
+        hipLaunchKernelGGL(ordered_copy_kernel<false>, dim3(gx, (uint32_t)gy), dim3(256), 0, s,
+                           b.sc_lin, b.sc_dst, b.n_sc_tiles, tile_shift);
     return hipGetLastError();
 }
 
