@@ -56,6 +56,7 @@ def lib():
         L.ora_plan.restype = C.c_int
         L.ora_monitor_init.restype = None
         L.ora_monitor_step.restype = None
+        L.ora_dispatch.restype = C.c_int
         _lib = L
     return _lib
 
@@ -174,6 +175,45 @@ def plan(slice_len, retry, rails, ids=None, rail=None, stage_off=None) -> Bindin
     base = np.zeros(R, dtype=np.uint64)
     L.ora_stage_bases(_p(T), C.c_uint32(R), _p(base))
     return Binding(int(st), rail, stage_off, T, cnt, A, base)
+
+
+DISPATCH_PARAMS_DTYPE = np.dtype([("theta_bytes", "<u8"), ("gamma_q8", "<u4"), ("window", "<u4"), ("rr_start", "<u8")])
+
+
+@dataclass
+class Dispatch:
+    binding: Binding
+    bound: np.ndarray      # uint8[N]  slices dealt by this call
+    mode: np.ndarray       # uint8[D]  0 nothing pending, 1 mice, 2 elephant, 3 deferred
+    rr_end: int            # round-robin counter after the call
+
+
+def dispatch(s: Slices, rails, dp, priority=None, done=None, rail=None, stage_off=None) -> Dispatch:
+    """Algorithm 1 per request: QoS admission, mice / elephant dispatch (see tent_oracle.c)."""
+    L = lib()
+    R = rails.shape[0]
+    D = s.first.shape[0] - 1
+    c0, c1, ex, A = coeffs(rails)
+    T = np.zeros(R, dtype=np.uint64)
+    cnt = np.zeros(R, dtype=np.uint64)
+    if rail is None:
+        rail = np.full(s.n, 0xFFFFFFFF, dtype=np.uint32)
+    if stage_off is None:
+        stage_off = np.zeros(s.n, dtype=np.uint64)
+    if done is None:
+        done = np.zeros(s.n, dtype=np.uint8)
+    req_len = np.zeros(D, dtype=np.uint64)
+    np.add.at(req_len, s.desc, s.len.astype(np.uint64))
+    bound = np.zeros(s.n, dtype=np.uint8)
+    mode = np.zeros(D, dtype=np.uint8)
+    rr_end = C.c_uint64()
+    st = L.ora_dispatch(C.c_uint32(D), _p(s.first), _p(s.len), _p(np.ascontiguousarray(done, dtype=np.uint8)),
+                        _p(req_len), _p(None if priority is None else np.ascontiguousarray(priority, dtype=np.uint8)),
+                        C.c_uint32(R), _p(c0), _p(c1), _p(ex), _p(np.ascontiguousarray(dp)),
+                        _p(A), _p(T), _p(cnt), _p(rail), _p(stage_off), _p(bound), _p(mode), C.byref(rr_end))
+    base = np.zeros(R, dtype=np.uint64)
+    L.ora_stage_bases(_p(T), C.c_uint32(R), _p(base))
+    return Dispatch(Binding(int(st), rail, stage_off, T, cnt, A, base), bound, mode, int(rr_end.value))
 
 
 MONITOR_PARAMS_DTYPE = np.dtype([("err_threshold", "<u4"), ("recover_windows", "<u4"),

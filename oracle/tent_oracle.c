@@ -156,6 +156,108 @@ int ora_bind(uint64_t n, const uint32_t *ids, const uint32_t *s_len, uint32_t R,
     return ORA_OK;
 }
 
+/* ---- request-level dispatch (Algorithm 1, Stages 1-3; Section 4.2 "Slice Dispatching" and
+ * "Quality of Service") -----------------------------------------------------------------------
+ * Algorithm 1 is run once per request (here: per declared transfer), in declaration order.
+ *   Stage 1: the admitted rails of the request are the non-excluded rails whose current
+ *            priority slot accepts the request's priority.  Reading: priorities 0 LOW, 1 MID,
+ *            2 HIGH; in window w rail d sits in slot (w + d) mod 3, where slot 0 accepts HIGH
+ *            only, slot 1 HIGH and MID, slot 2 everything.  No admitted rail: the request is
+ *            deferred, its slices stay pending.
+ *   Stage 2: s_d = predicted cost of one slice on rail d (Eq. 1 times the penalty) with the
+ *            queue state A_d at the start of the request; s_min its minimum.
+ *   Stage 3, mice (request length < theta): candidates are the admitted rails with
+ *            s_d <= s_min + floor(gamma_q8 * s_min / 256); the request goes as a whole to the
+ *            candidate picked round robin (a counter that advances with every mice request).
+ *            Here L of Eq. 1 is the request length.
+ *   Stage 3, elephants: weighted proportional spraying with efficiency weights W_d = 1 / s_d
+ *            (L of Eq. 1 = the length of the request's first slice).  Reading: the request's
+ *            pending slices are dealt in order, each to the admitted rail with the smallest
+ *            (m_d + 1) * max(s_d, 1), m_d = slices of this request already dealt to d, ties to
+ *            the lowest rail -- so the shares m_d track W_d to within one slice.
+ * Every dealt slice adds its bytes to A_d and to the rail's staging region, in dealing order.
+ * first[] (D+1 entries) delimits the requests' slices; done[i] != 0 marks slices that are not
+ * pending; mode[j] receives 0 (nothing pending), 1 (mice), 2 (elephant) or 3 (deferred);
+ * bound[i] is set for every slice dealt.  Returns ORA_DEFER when every rail is excluded. */
+typedef struct { uint64_t theta_bytes; uint32_t gamma_q8; uint32_t window; uint64_t rr_start; } ora_dispatch_params;
+
+int ora_dispatch(uint32_t D, const uint64_t *first, const uint32_t *s_len, const uint8_t *done,
+                 const uint64_t *req_len, const uint8_t *priority, uint32_t R,
+                 const uint64_t *c0, const uint64_t *c1, const uint8_t *excluded,
+                 const ora_dispatch_params *dp,
+                 uint64_t *A, uint64_t *T, uint64_t *slices,
+                 uint32_t *s_rail, uint64_t *s_stage_off, uint8_t *bound, uint8_t *mode, uint64_t *rr_end)
+{
+    static const uint8_t slot_needs[3] = { 2, 1, 0 };
+    uint64_t rr = dp->rr_start;
+    int any = 0;
+    for (uint32_t d = 0; d < R; ++d) { T[d] = 0; slices[d] = 0; if (!excluded[d]) any = 1; }
+    *rr_end = rr;
+    if (!any) return ORA_DEFER;
+
+    for (uint32_t j = 0; j < D; ++j) {
+        uint64_t n_pending = 0;
+        for (uint64_t i = first[j]; i < first[j + 1]; ++i) n_pending += !done[i];
+        mode[j] = 0;
+        if (n_pending == 0) continue;
+
+        uint8_t admitted[64];
+        uint8_t p = priority ? priority[j] : 2;
+        int n_adm = 0;
+        for (uint32_t d = 0; d < R; ++d) {
+            admitted[d] = !excluded[d] && p >= slot_needs[(dp->window + d) % 3];
+            n_adm += admitted[d];
+        }
+        if (n_adm == 0) { mode[j] = 3; continue; }
+
+        uint64_t s[64], s_min = 0;
+        int have = 0;
+        if (req_len[j] < dp->theta_bytes) {                       /* mice flow */
+            for (uint32_t d = 0; d < R; ++d) {
+                if (!admitted[d]) continue;
+                s[d] = ora_cost(c0[d], c1[d], A[d], req_len[j]);
+                if (!have || s[d] < s_min) { s_min = s[d]; have = 1; }
+            }
+            uint64_t limit = s_min + ((s_min * dp->gamma_q8) >> 8);
+            uint32_t cand[64], n_cand = 0;
+            for (uint32_t d = 0; d < R; ++d) if (admitted[d] && s[d] <= limit) cand[n_cand++] = d;
+            uint32_t pick = cand[rr % n_cand];
+            rr += 1;
+            for (uint64_t i = first[j]; i < first[j + 1]; ++i) {
+                if (done[i]) continue;
+                s_rail[i] = pick; s_stage_off[i] = T[pick]; bound[i] = 1;
+                T[pick] += s_len[i]; A[pick] += s_len[i]; slices[pick] += 1;
+            }
+            mode[j] = 1;
+        } else {                                                  /* elephant flow */
+            uint64_t m[64];
+            uint32_t L0 = s_len[first[j]];
+            for (uint32_t d = 0; d < R; ++d) {
+                m[d] = 0;
+                if (!admitted[d]) continue;
+                s[d] = ora_cost(c0[d], c1[d], A[d], L0);
+                if (s[d] == 0) s[d] = 1;
+            }
+            for (uint64_t i = first[j]; i < first[j + 1]; ++i) {
+                if (done[i]) continue;
+                int best = -1;
+                uint64_t best_key = 0;
+                for (uint32_t d = 0; d < R; ++d) {
+                    if (!admitted[d]) continue;
+                    uint64_t key = (m[d] + 1) * s[d];
+                    if (best < 0 || key < best_key) { best = (int)d; best_key = key; }
+                }
+                m[best] += 1;
+                s_rail[i] = (uint32_t)best; s_stage_off[i] = T[best]; bound[i] = 1;
+                T[best] += s_len[i]; A[best] += s_len[i]; slices[best] += 1;
+            }
+            mode[j] = 2;
+        }
+    }
+    *rr_end = rr;
+    return ORA_OK;
+}
+
 /* ---- link-level resilience (Section 4.3, "Link-Level Resilience") -----------
  * A slice whose rail reports a hard error goes back to the pending set with its
  * retry count raised by one (counts saturate at 255).  rail_failed[d] != 0 marks

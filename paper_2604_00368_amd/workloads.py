@@ -34,6 +34,7 @@ RAIL_DTYPE = np.dtype(
      "offsets": [0, 4, 8, 16, 18, 20], "itemsize": 24})
 
 # struct { uint32 hw_MBps; uint32 alpha_q8; uint32 delta_ns; uint32 ewma_q8; }  -- 16 bytes
+DISPATCH_PARAMS_DTYPE = np.dtype([("theta_bytes", "<u8"), ("gamma_q8", "<u4"), ("window", "<u4"), ("rr_start", "<u8")])
 MONITOR_PARAMS_DTYPE = np.dtype([("err_threshold", "<u4"), ("recover_windows", "<u4"),
                                  ("cooldown_windows", "<u4"), ("degrade_q8", "<u4")])
 PROBE_DTYPE = np.dtype(
@@ -59,6 +60,19 @@ def make_rails(bw_MBps, lat_ns=5000, queued=0, health=0, beta1_q8=256, penalty_q
     r["penalty_q8"] = penalty_q8
     r["health"] = health
     return r
+
+
+def make_dispatch_params(theta_bytes, gamma_q8=26, window=0, rr_start=0):
+    """Parameters of the request-level dispatch: mice/elephant threshold, cost tolerance (Q8.8, 26 = 10 %),
+    index of the current priority window, start value of the round-robin counter."""
+    return np.array([(theta_bytes, gamma_q8, window, rr_start)], dtype=DISPATCH_PARAMS_DTYPE)
+
+
+def make_priorities(seed, n_desc, p_high=0.3, p_mid=0.3):
+    """Seeded request priorities: 2 HIGH, 1 MID, 0 LOW."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    u = rng.random(n_desc)
+    return np.where(u < p_high, 2, np.where(u < p_high + p_mid, 1, 0)).astype(np.uint8)
 
 
 def make_monitor_params(err_threshold=8, recover_windows=2, cooldown_windows=1, degrade_q8=128):
