@@ -96,6 +96,26 @@ typedef struct {
     uint32_t ewma_q8;          /* weight of the new probe in Q8.8, 0..256 (256 replaces the estimate) */
 } tent_probe_params;
 
+/* Request-level dispatch (Algorithm 1, Stage 3; Section 4.2 "Slice Dispatching", "Quality of Service"). */
+typedef struct {
+    uint64_t theta_bytes;      /* theta: a transfer shorter than this is a mice flow                 */
+    uint32_t gamma_q8;         /* gamma in Q8.8 (at most 65535): mice candidates cost at most
+                                  s_min + floor(gamma_q8 * s_min / 256)                               */
+    uint32_t window;           /* index of the current priority window (see tent_plan_dispatch)      */
+    uint64_t rr_start;         /* round-robin counter before the call                                */
+} tent_dispatch_params;
+
+typedef struct {
+    tent_plan_info plan;       /* as for tent_plan; n_pending_before counts only slices of requests that were dispatched */
+    uint64_t n_mice;           /* requests dispatched as mice flows                                  */
+    uint64_t n_elephant;       /* requests dispatched as elephant flows                              */
+    uint64_t n_deferred;       /* requests left pending because no rail admitted their priority      */
+    uint64_t rr_next;          /* round-robin counter after the call = rr_start + n_mice             */
+} tent_dispatch_info;
+
+enum { TENT_PRIO_LOW = 0, TENT_PRIO_MID = 1, TENT_PRIO_HIGH = 2 };
+enum { TENT_MODE_NONE = 0, TENT_MODE_MICE = 1, TENT_MODE_ELEPHANT = 2, TENT_MODE_DEFERRED = 3 };
+
 /* Rail health monitor (Section 4.3, "Health Monitoring"): parameters and the record kept per rail. */
 typedef struct {
     uint32_t err_threshold;    /* a rail pauses once 2*hard + congestion errors exceed 2*err_threshold */
@@ -188,6 +208,39 @@ int tent_declare(tent_ctx *ctx, uint32_t n_desc,
  */
 int tent_plan(tent_ctx *ctx, tent_batch_t batch, const tent_rail_state *rails, uint32_t n_rails,
               tent_plan_info *info, void *stream);
+
+/*
+ * Split and dispatch request by request (Algorithm 1, Stages 1-3; Section 4.2 "Slice Dispatching"
+ * and "Quality of Service") -- the alternative to tent_plan's per-slice rule.  Transfers are taken
+ * in declaration order; for each one with slices that are not DONE:
+ *   Stage 1  admitted rails = rails with health != 2 whose priority slot accepts priority[j]
+ *            (TENT_PRIO_*; NULL = every transfer is HIGH): rail d sits in slot (window + d) mod 3,
+ *            slot 0 accepts HIGH only, slot 1 HIGH and MID, slot 2 everything.  With no admitted rail
+ *            the transfer is deferred: its slices are left PENDING.
+ *   Stage 2  s_d = c0_d + (((A_d + L) * c1_d) >> 16) with A_d as it stands before the transfer
+ *            (coefficients as for tent_plan).
+ *   Stage 3  transfer length < theta_bytes (mice, L = transfer length): the whole transfer goes to
+ *            candidate number rr mod |C| of C = admitted rails with
+ *            s_d <= s_min + floor(gamma_q8 * s_min / 256), ascending rail index, and rr advances by one;
+ *            otherwise (elephant, L = length of the transfer's first slice): its slices that are not
+ *            DONE are dealt in ascending index, each to the admitted rail with the smallest
+ *            (m_d + 1) * max(s_d, 1), m_d = slices of this transfer already dealt to d, ties to the
+ *            lowest rail index (weighted proportional spraying with weights 1 / s_d).
+ * Every dealt slice becomes BOUND, adds its bytes to A_d and takes the next bytes of the rail's
+ * staging region; region bases as for tent_plan.  Retry counts play no part here.
+ * `rails`, `params`, `priority` (n_desc bytes or NULL) and `info` (or NULL) are host memory; with
+ * info = NULL the call only enqueues.  Returns TENT_DEFER when every rail is excluded (nothing is
+ * touched); TENT_ERR_INVALID for a priority above 2; TENT_ERR_RANGE as for tent_plan, for
+ * gamma_q8 > 65535, and when (largest slice count of a transfer + 1) * (largest cost a rail can
+ * reach) is 2^57 or more.
+ */
+int tent_plan_dispatch(tent_ctx *ctx, tent_batch_t batch, const tent_rail_state *rails, uint32_t n_rails,
+                       const tent_dispatch_params *params, const uint8_t *priority,
+                       tent_dispatch_info *info, void *stream);
+
+/* Copy what the last tent_plan_dispatch did with every transfer (TENT_MODE_*, one byte each) to
+ * host memory for verification.  Waits for the device.  TENT_ERR_RANGE if cap < number of transfers. */
+int tent_get_modes(tent_ctx *ctx, tent_batch_t batch, uint8_t *host_out, uint64_t cap);
 
 /*
  * Rail simulator used by the re-planning workload (not an operation of the

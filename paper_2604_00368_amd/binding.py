@@ -11,7 +11,7 @@ import os
 
 import numpy as np
 
-from .workloads import EXTENT_DTYPE, MONITOR_PARAMS_DTYPE, PROBE_DTYPE, RAIL_DTYPE
+from .workloads import DISPATCH_PARAMS_DTYPE, EXTENT_DTYPE, MONITOR_PARAMS_DTYPE, PROBE_DTYPE, RAIL_DTYPE
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libtent.so")
@@ -26,7 +26,8 @@ TENT_T_NAMES = ["extent_scan", "slice_scan", "expand", "compact", "bind", "gathe
 EXPORTS = ["tent_create", "tent_destroy", "tent_register_segment", "tent_declare", "tent_plan",
            "tent_sim_advance", "tent_sim_latency", "tent_update_bandwidth", "tent_get_latencies", "tent_execute", "tent_poll", "tent_reset", "tent_slice_count",
            "tent_get_plan", "tent_get_timings", "tent_release", "tent_strerror",
-           "tent_sim_fail", "tent_get_retries", "tent_monitor_init", "tent_monitor_update"]
+           "tent_sim_fail", "tent_get_retries", "tent_monitor_init", "tent_monitor_update",
+           "tent_plan_dispatch", "tent_get_modes"]
 
 
 class tent_config(C.Structure):
@@ -38,6 +39,11 @@ class tent_plan_info(C.Structure):
     _fields_ = [("n_slices", C.c_uint64), ("n_pending_before", C.c_uint64),
                 ("rail_bytes", C.c_uint64 * TENT_MAX_RAILS), ("rail_slices", C.c_uint64 * TENT_MAX_RAILS),
                 ("queued_after", C.c_uint64 * TENT_MAX_RAILS), ("stage_base", C.c_uint64 * TENT_MAX_RAILS)]
+
+
+class tent_dispatch_info(C.Structure):
+    _fields_ = [("plan", tent_plan_info), ("n_mice", C.c_uint64), ("n_elephant", C.c_uint64),
+                ("n_deferred", C.c_uint64), ("rr_next", C.c_uint64)]
 
 
 MONITOR_DTYPE = np.dtype([("state", "<u4"), ("score", "<u4"), ("clean", "<u4"),
@@ -89,6 +95,9 @@ def lib():
         L.tent_get_plan.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
         L.tent_get_timings.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_uint32)]
         L.tent_release.argtypes = [C.c_void_p, C.c_uint64]
+        L.tent_plan_dispatch.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
+                                         C.POINTER(tent_dispatch_info), C.c_void_p]
+        L.tent_get_modes.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
         L.tent_sim_fail.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.tent_get_retries.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
         L.tent_monitor_init.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32]
@@ -160,6 +169,24 @@ def tent_sim_advance(ctx, batch: int, budget_bytes, stream=None) -> int:
     n = C.c_uint64()
     _check(lib().tent_sim_advance(ctx, batch, bp, C.byref(n), _stream(stream)), "tent_sim_advance")
     return n.value
+
+
+def tent_plan_dispatch(ctx, batch: int, rails, params, priority=None, want_info: bool = True, stream=None):
+    """Returns (status, info) with status TENT_OK or TENT_DEFER; info is None when not requested."""
+    r, rp = _host(rails, RAIL_DTYPE)
+    p, pp = _host(params, DISPATCH_PARAMS_DTYPE)
+    pr = None if priority is None else np.ascontiguousarray(priority, dtype=np.uint8)
+    info = tent_dispatch_info() if want_info else None
+    st = lib().tent_plan_dispatch(ctx, batch, rp, r.shape[0], pp, None if pr is None else pr.ctypes.data_as(C.c_void_p),
+                                  C.byref(info) if want_info else None, _stream(stream))
+    _check(st, "tent_plan_dispatch", allow=(TENT_OK, TENT_DEFER))
+    return st, info
+
+
+def tent_get_modes(ctx, batch: int, n_desc: int) -> np.ndarray:
+    out = np.zeros(max(n_desc, 1), dtype=np.uint8)
+    _check(lib().tent_get_modes(ctx, batch, out.ctypes.data_as(C.c_void_p), n_desc), "tent_get_modes")
+    return out[:n_desc]
 
 
 def tent_sim_fail(ctx, batch: int, rail_failed, want_counts: bool = True, stream=None):

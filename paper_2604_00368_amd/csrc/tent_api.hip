@@ -21,6 +21,7 @@ struct Batch {
     bool has_retry = false;      // a rail failed since declare / reset: slices with a retry count may exist
     uint32_t generation = 0;
     uint64_t payload = 0;
+    uint64_t max_req_slices = 0; // most slices any one transfer has
     RailParams last_rails{};     // telemetry of the last plan (for the rail simulator)
     uint32_t last_lat_ns[TENT_MAX_RAILS] = {};
     BatchDev dev{};
@@ -98,11 +99,12 @@ void free_batch(Batch& b)
 // Walk both extent lists of every transfer: structure, bounds, equal lengths.  Also returns
 // the payload and the number of slices the device splitter will produce.
 int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const tent_extent* se,
-             const uint32_t* dp, const tent_extent* de, uint64_t* payload, uint64_t* n_slices, uint64_t* len_bits)
+             const uint32_t* dp, const tent_extent* de, uint64_t* payload, uint64_t* n_slices, uint64_t* len_bits,
+             uint64_t* max_req_slices)
 {
     if (sp[0] != 0 || dp[0] != 0) return TENT_ERR_INVALID;
     const uint64_t S = ctx->cfg.slice_bytes;
-    uint64_t total = 0, slices = 0, bits = 0;
+    uint64_t total = 0, slices = 0, bits = 0, most = 0;
     for (uint32_t j = 0; j < n_desc; ++j) {
         if (sp[j + 1] <= sp[j] || dp[j + 1] <= dp[j]) return TENT_ERR_INVALID;   // empty or non-monotone
         uint64_t ls = 0, ld = 0;
@@ -125,10 +127,12 @@ int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const ten
         if (ls != ld) return TENT_ERR_INVALID;
         total += ls;
         slices += (ls + S - 1) / S;
+        most = std::max(most, (ls + S - 1) / S);
     }
     *payload = total;
     *n_slices = slices;
     *len_bits = bits;
+    *max_req_slices = most;
     return TENT_OK;
 }
 
@@ -262,8 +266,8 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
 {
     if (!ctx || !src_ptr || !src_ext || !dst_ptr || !dst_ext || !out || n_desc == 0) return TENT_ERR_INVALID;
     *out = 0;
-    uint64_t payload = 0, n_slices = 0, len_bits = 0;
-    int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, &payload, &n_slices, &len_bits);
+    uint64_t payload = 0, n_slices = 0, len_bits = 0, max_req_slices = 0;
+    int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, &payload, &n_slices, &len_bits, &max_req_slices);
     if (rc != TENT_OK) return rc;
     if (n_slices >= 0xFFFFFFFEull || n_desc >= 0x7FFFFFFFu) return TENT_ERR_RANGE;
     const uint64_t ns = src_ptr[n_desc], nd = dst_ptr[n_desc];
@@ -282,6 +286,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     b = Batch{};
     b.generation = gen;
     b.payload = payload;
+    b.max_req_slices = max_req_slices;
     BatchDev& d = b.dev;
     d.n_desc = n_desc;
     d.n_src_ext = ns;
@@ -327,6 +332,8 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_tau, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_rec, n_slices);
     if (rc == TENT_OK) rc = dev_alloc(b, &d.s_retry, n_slices);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.priority, (uint64_t)n_desc);
+    if (rc == TENT_OK) rc = dev_alloc(b, &d.req_mode, (uint64_t)n_desc);
     BatchDev* self_dev = nullptr;
     if (rc == TENT_OK) rc = dev_alloc(b, &self_dev, 1);
     if (d.n_sc_tiles == 0) {                              // per-slice tile tables only for untiled geometry
@@ -370,6 +377,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
         hipMemcpy(de, dst_ext, sizeof(tent_extent) * nd, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(self_dev, &d, sizeof(BatchDev), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemset(d.s_retry, 0, std::max<uint64_t>(n_slices, 1)) != hipSuccess ||
+        hipMemset(d.req_mode, 0, n_desc) != hipSuccess ||
         hipMemset(d.plan, 0, sizeof(PlanState)) != hipSuccess) {
         (void)hipGetLastError();
         free_batch(b);
@@ -478,6 +486,114 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
             info->stage_base[r] = r < n_rails ? ps.base[r] : 0;
         }
     }
+    return TENT_OK;
+}
+
+int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, uint32_t n_rails,
+                       const tent_dispatch_params* params, const uint8_t* priority, tent_dispatch_info* info,
+                       void* stream)
+{
+    if (!ctx || !rails || !params) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (n_rails == 0 || n_rails > ctx->max_rails) return TENT_ERR_RANGE;
+    if (params->gamma_q8 > 65535u) return TENT_ERR_RANGE;
+    RailParams rp;
+    int rc = convert_rails(rails, n_rails, b->payload, &rp);
+    if (rc != TENT_OK) return rc;
+    if (rp.admitted == 0) return TENT_DEFER;
+    if (b->payload + 256ull * n_rails > ctx->cfg.staging_bytes) return TENT_ERR_RANGE;
+    if (priority)
+        for (uint32_t j = 0; j < b->dev.n_desc; ++j)
+            if (priority[j] > 2) return TENT_ERR_INVALID;
+    // The slot keys (m + 1) * s_d are packed with a 6-bit rail index and the tolerance multiplies a
+    // cost by gamma: bound the largest cost any rail can show during this plan.
+    {
+        unsigned __int128 worst = 0;
+        for (uint32_t d = 0; d < n_rails; ++d) {
+            if (!((rp.admitted >> d) & 1)) continue;
+            const unsigned __int128 c = (unsigned __int128)rp.c0[d] +
+                                        ((((unsigned __int128)rp.A[d] + b->payload) * rp.c1[d]) >> 16);
+            worst = std::max(worst, c);
+        }
+        if (worst * (b->max_req_slices + 1) >= ((unsigned __int128)1 << 57)) return TENT_ERR_RANGE;
+        if (worst * (params->gamma_q8 + 1u) >= ((unsigned __int128)1 << 63)) return TENT_ERR_RANGE;
+    }
+    DispatchParams dp;
+    std::memset(&dp, 0, sizeof(dp));
+    dp.theta = params->theta_bytes;
+    dp.rr_start = params->rr_start;
+    dp.gamma_q8 = params->gamma_q8;
+    // Priority slots (Section 4.2, "Quality of Service"): in window w rail d sits in slot (w + d) mod 3;
+    // slot 0 takes HIGH only, slot 1 HIGH and MID, slot 2 everything.
+    for (uint32_t d = 0; d < n_rails; ++d) {
+        if (!((rp.admitted >> d) & 1)) continue;
+        const uint32_t slot = (uint32_t)(((uint64_t)params->window + d) % 3);
+        const uint32_t lowest = slot == 0 ? 2 : slot == 1 ? 1 : 0;
+        for (uint32_t p = lowest; p <= 2; ++p) dp.adm[p] |= 1ull << d;
+    }
+
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const BatchDev& d = b->dev;
+    dp.all_high = priority ? 0u : 1u;
+    if (priority) HIP_TRY(hipMemcpyAsync(d.priority, priority, d.n_desc, hipMemcpyHostToDevice, s));
+    if (!b->planned) {
+        {
+            StageTimer t(ctx, TENT_T_EXTENT_SCAN, s);
+            HIP_TRY(launch_extent_scan(d.src_ext, d.n_src_ext, d.src_pre, d.scan_partials, s));
+            HIP_TRY(launch_extent_scan(d.dst_ext, d.n_dst_ext, d.dst_pre, d.scan_partials, s));
+        }
+        {
+            StageTimer t(ctx, TENT_T_SLICE_SCAN, s);
+            HIP_TRY(launch_slice_scan(d, s));
+        }
+        {
+            StageTimer t(ctx, TENT_T_EXPAND, s);
+            HIP_TRY(launch_expand(d, s));
+            HIP_TRY(launch_tile_tables(d, s));
+        }
+    }
+    {
+        StageTimer t(ctx, TENT_T_BIND, s);
+        HIP_TRY(launch_dispatch(d, rp, dp, s));
+    }
+    b->planned = true;
+    b->last_rails = rp;
+    for (uint32_t r = 0; r < n_rails; ++r) b->last_lat_ns[r] = rails[r].lat_ns;
+
+    if (info) {
+        HIP_TRY(hipMemcpyAsync(ctx->host_plan, d.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        const PlanState& ps = *ctx->host_plan;
+        std::memset(info, 0, sizeof(*info));
+        info->plan.n_slices = ps.n_bound;
+        info->plan.n_pending_before = ps.n_pending;
+        for (uint32_t r = 0; r < n_rails; ++r) {
+            info->plan.rail_bytes[r] = ps.T[r];
+            info->plan.rail_slices[r] = ps.cnt[r];
+            info->plan.queued_after[r] = ps.A_after[r];
+            info->plan.stage_base[r] = ps.base[r];
+        }
+        info->n_mice = ps.n_mice;
+        info->n_elephant = ps.n_elephant;
+        info->n_deferred = ps.n_deferred;
+        info->rr_next = ps.rr_next;
+    }
+    return TENT_OK;
+}
+
+int tent_get_modes(tent_ctx* ctx, tent_batch_t batch, uint8_t* host_out, uint64_t cap)
+{
+    if (!ctx || !host_out) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (cap < b->dev.n_desc) return TENT_ERR_RANGE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(host_out, b->dev.req_mode, b->dev.n_desc, hipMemcpyDeviceToHost));
     return TENT_OK;
 }
 

@@ -46,6 +46,16 @@ struct RotateParams {
     uint32_t n_cand;
 };
 
+// Request-level dispatch (Algorithm 1): thresholds and, per priority level, the rails whose current
+// priority slot admits a request of that level (already intersected with the non-excluded rails).
+struct DispatchParams {
+    uint64_t theta;              // requests shorter than this are mice flows
+    uint64_t rr_start;           // round-robin counter before the call
+    uint64_t adm[3];             // admitted-rail masks for priorities LOW, MID, HIGH
+    uint32_t gamma_q8;           // cost tolerance of the mice candidate set, Q8.8
+    uint32_t all_high;           // 1: no priority array was given, every request counts as HIGH
+};
+
 // Rails that report a hard error to the rail simulator.
 struct FailParams {
     uint8_t failed[TENT_MAX_RAILS];
@@ -69,6 +79,8 @@ struct PlanState {
     uint64_t Tr[TENT_MAX_RAILS];          // bytes the rotation pass bound per rail
     uint64_t cr[TENT_MAX_RAILS];          // slices the rotation pass bound per rail
     uint64_t fail_cnt[TENT_MAX_RAILS];    // tent_sim_fail: slices that failed per rail
+    uint64_t n_mice, n_elephant, n_deferred;   // tent_plan_dispatch: requests per mode
+    uint64_t rr_next;                     // round-robin counter after the call
 };
 
 // What a copy workgroup needs to know about its slice, in one 16-byte scalar load.
@@ -103,6 +115,8 @@ struct BatchDev {
     uint8_t*  s_state;
     uint64_t* s_tau;               // recorded end-to-end latency in ns (rail simulator / telemetry)
     uint8_t*  s_retry;             // times the slice failed on a rail (saturates at 255)
+    uint8_t*  priority;            // [n_desc] request priority of the last tent_plan_dispatch (0 LOW, 1 MID, 2 HIGH)
+    uint8_t*  req_mode;            // [n_desc] what the last tent_plan_dispatch did with the request
 
     struct SliceRec* s_rec;        // packed copy record per slice, rebuilt by every tent_execute
     const BatchDev* self;          // device copy of this structure (generic copy path)
@@ -165,6 +179,7 @@ hipError_t launch_bind_serial(const BatchDev& b, const RailParams& rp, int mode,
 hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, hipStream_t s);
 hipError_t launch_rotate(const BatchDev& b, const RotateParams& rot, hipStream_t s);
 hipError_t launch_fail(const BatchDev& b, const FailParams& fp, hipStream_t s);
+hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, hipStream_t s);
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
 hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s);
 hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s);
