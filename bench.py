@@ -243,6 +243,19 @@ def main():
             rec_ms.append(tm_rec["compact"][0] + tm_rec["bind"][0])
     T.tent_reset(ctx, h_fb, stream)
 
+    # Request-level dispatch (Algorithm 1: mice round robin / weighted spraying of elephants), outside the
+    # timed region: the whole batch, every transfer HIGH priority, theta = 4 slices.
+    disp_ms = []
+    dparams = W.make_dispatch_params(4 * w.slice_bytes)
+    for _ in range(3):
+        T.tent_reset(ctx, h_fb, stream)
+        torch.cuda.synchronize(dev)
+        T.tent_get_timings(ctx)
+        st_d, dinfo = T.tent_plan_dispatch(ctx, h_fb, w.rails, dparams, None, True, stream)
+        tm_d = T.tent_get_timings(ctx)
+        disp_ms.append(sum(tm_d[k][0] for k in ("extent_scan", "slice_scan", "expand", "bind")))
+    T.tent_reset(ctx, h_fb, stream)
+
     # Plain copy of known size (1 GiB read + 1 GiB written by one elementwise kernel), outside the
     # timed region: the practical copy ceiling of the box and the reference dispatch that scales
     # hardware byte counters when this script runs under a counter-collecting profiler.
@@ -290,6 +303,8 @@ def main():
                      "bytes_per_slice": 17},
         "recovery": {"failed_rail": fastest, "retried_slices": n_retried, "replanned_slices": n_slices,
                      "replan_ms": round(min(rec_ms), 4) if rec_ms else None},
+        "dispatch": {"theta_slices": 4, "mice": int(dinfo.n_mice), "elephants": int(dinfo.n_elephant),
+                     "plan_ms": round(min(disp_ms), 4), "slices_per_s": round(n_slices / (min(disp_ms) * 1e-3), 1)},
         "plain_copy_GBps": round(plain_copy_GBps, 2),
         "roofline": {"bound": "hbm", "kernel": "ordered_copy_kernel<%s>" % ("true" if dom == "gather" else "false"), "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),

@@ -17,54 +17,17 @@
 // floating-point estimate of the cut level, repaired with exact integer comparisons), and a second,
 // fully parallel kernel gives every slot its rank in the merge in closed form (R integer divisions).
 #include "scan.h"
+#include "wave.h"
 
 namespace tent {
 namespace {
 
-__device__ __forceinline__ uint64_t lane_read64(uint64_t v, int lane)
-{
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, lane);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), lane);
-    return ((uint64_t)hi << 32) | lo;
-}
-
-__device__ __forceinline__ uint64_t wave_min_u64(uint64_t k)
-{
-#pragma unroll
-    for (int step = 1; step < 64; step <<= 1) {
-        const uint64_t o = (uint64_t)__shfl_xor((unsigned long long)k, step, 64);
-        k = o < k ? o : k;
-    }
-    return k;
-}
-
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t k)
-{
-#pragma unroll
-    for (int step = 1; step < 64; step <<= 1) {
-        const uint64_t o = (uint64_t)__shfl_xor((unsigned long long)k, step, 64);
-        k = o > k ? o : k;
-    }
-    return k;
-}
-
-__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t k)
-{
-#pragma unroll
-    for (int step = 1; step < 64; step <<= 1) k += (uint64_t)__shfl_xor((unsigned long long)k, step, 64);
-    return k;
-}
-
-__device__ __forceinline__ double wave_sum_f64(double k)
-{
-#pragma unroll
-    for (int step = 1; step < 64; step <<= 1) k += __shfl_xor(k, step, 64);
-    return k;
-}
-
 constexpr uint64_t kNoKey = ~0ull;
 
 // ---- the chain over requests -------------------------------------------------------------------
+// kWide = 16, 32 or 64: smallest of these that covers the rails; lanes beyond the rails only tag along
+// (uniform decisions are read from lane 0's row).
+template <int kWide>
 __global__ void __launch_bounds__(64) dispatch_chain_kernel(BatchDev b, RailParams rp, DispatchParams dp)
 {
     const int lane = threadIdx.x;
@@ -103,7 +66,7 @@ __global__ void __launch_bounds__(64) dispatch_chain_kernel(BatchDev b, RailPara
                 ++n_deferred;
                 continue;
             }
-            const uint64_t L_req = lane_read64(my_len, t);
+            const uint64_t L_req = read_lane64(my_len, t);
             const uint32_t short_by = (uint32_t)__builtin_amdgcn_readlane((int)my_short, t);
             const bool live = (adm >> lane) & 1;
             const bool mice = L_req < dp.theta;
@@ -111,7 +74,7 @@ __global__ void __launch_bounds__(64) dispatch_chain_kernel(BatchDev b, RailPara
             uint64_t s = c0 + (((A + L) * c1) >> 16);                        // Stage 2
             uint64_t K = 0, bytes = 0;
             if (mice) {
-                const uint64_t s_min = wave_min_u64(live ? s : kNoKey);
+                const uint64_t s_min = wave_reduce64(live ? s : kNoKey, kWide, OpMin{});
                 const uint64_t limit = s_min + ((s_min * dp.gamma_q8) >> 8);
                 const uint64_t cand = __ballot(live && s <= limit);
                 const uint32_t idx = (uint32_t)(rr % (uint64_t)__popcll(cand));
@@ -124,45 +87,42 @@ __global__ void __launch_bounds__(64) dispatch_chain_kernel(BatchDev b, RailPara
                 if (s == 0) s = 1;
                 // cut level of the merge: x with sum_d floor(x / s_d) ~ n
                 const double inv = live ? 1.0 / (double)s : 0.0;
-                const double sum_inv = wave_sum_f64(inv);
+                const double sum_inv = wave_sum_f64(inv, kWide);
                 const double n_live = (double)__popcll(adm);
                 const double x = ((double)n + 0.5 * n_live) / sum_inv;
                 if (live) {
                     const double kf = x * inv;
                     K = kf >= (double)n ? n : (uint64_t)kf;
                 }
-                uint64_t total = wave_sum_u64(K);
-                // exact repair: grow by the cheapest next slot / shrink by the dearest held slot
+                uint64_t total = uniform64(wave_reduce64(K, kWide, OpAdd{}));
+                // exact repair: grow by the cheapest free slot / shrink by the dearest held slot
 #pragma clang loop unroll(disable)
                 while (total < n) {
-                    const uint64_t key = live ? (((K + 1) * s) << 6) | (uint32_t)lane : kNoKey;
-                    const uint64_t win = wave_min_u64(key);
-                    if (key == win) ++K;
+                    const int win = argmin_cost((K + 1) * s, live, lane, kWide);
+                    if (lane == win) ++K;
                     ++total;
                 }
 #pragma clang loop unroll(disable)
                 while (total > n) {
-                    const uint64_t key = (live && K) ? ((K * s) << 6) | (uint32_t)lane : 0;
-                    const uint64_t win = wave_max_u64(key);
-                    if (key == win && K) --K;
+                    const int win = argmax_cost(K * s, live && K, lane, kWide);
+                    if (lane == win) --K;
                     --total;
                 }
                 // the held slots must be exactly the first n of the merge: the dearest held slot
                 // (ties: highest rail last) precedes the cheapest free slot (ties: lowest rail first)
-                uint64_t hi = 0;
+                int last = 0;
 #pragma clang loop unroll(disable)
                 for (int guard = 0; guard < 4096; ++guard) {
-                    const uint64_t held = (live && K) ? ((K * s) << 6) | (uint32_t)lane : 0;
-                    const uint64_t free_ = live ? (((K + 1) * s) << 6) | (uint32_t)lane : kNoKey;
-                    hi = wave_max_u64(held);
-                    const uint64_t lo = wave_min_u64(free_);
-                    if (hi < lo) break;
-                    if (held == hi && K) --K;
-                    if (free_ == lo) ++K;
+                    last = argmax_cost(K * s, live && K, lane, kWide);
+                    const int next = argmin_cost((K + 1) * s, live, lane, kWide);
+                    const uint64_t held = read_lane64(K * s, last);
+                    const uint64_t free_ = read_lane64((K + 1) * s, next);
+                    if (held < free_ || (held == free_ && last < next)) break;
+                    if (lane == last) --K;
+                    if (lane == next) ++K;
                 }
                 // the request's last pending slice is the last element of the merge
-                const bool tail = live && K && (((K * s) << 6) | (uint32_t)lane) == hi;
-                bytes = K * S - (tail ? short_by : 0);
+                bytes = K * S - (lane == last ? short_by : 0);
                 if (lane == t) my_mode = 2;
                 ++n_elephant;
             }
@@ -275,7 +235,9 @@ hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const Dispat
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(pending_list_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
-    hipLaunchKernelGGL(dispatch_chain_kernel, dim3(1), dim3(64), 0, s, b, rp, dp);
+    if (rp.n_rails <= 16)      hipLaunchKernelGGL(dispatch_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, dp);
+    else if (rp.n_rails <= 32) hipLaunchKernelGGL(dispatch_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, dp);
+    else                       hipLaunchKernelGGL(dispatch_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, dp);
     hipLaunchKernelGGL(dispatch_emit_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, rp, dp);
     return hipGetLastError();
 }

@@ -171,3 +171,19 @@ def test_full_size_faulty_rails(H, oracle):
     assert max(int((r["retry"][r["pending"]] > 0).sum()) for r in recs) > 4 * 1024
     gc.collect()
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["kv_migration", "many_small_x6"])
+def test_full_size_dispatch(H, oracle, name):
+    # Algorithm 1 request by request at full size: three priority windows, plan compared in full each window,
+    # at the end every destination byte by the plain definition
+    import test_gpu_dispatch as Dz
+    print("full-size dispatch", name, flush=True)
+    w = full_config(name)
+    prio = W.make_priorities(21, w.n_desc)
+    done, modes = Dz.dispatch_windows_and_compare(
+        H, oracle, w, theta=16 * w.slice_bytes, gamma_q8=26, prio=prio, windows=[0, 1, 2], bytes_too=False,
+        final_check=lambda eng, done: device_definition_check(w, eng.src, eng.dst))
+    assert done.all() and 2 in modes
+    gc.collect()
+    torch.cuda.empty_cache()
