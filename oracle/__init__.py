@@ -57,6 +57,7 @@ def lib():
         L.ora_monitor_init.restype = None
         L.ora_monitor_step.restype = None
         L.ora_dispatch.restype = C.c_int
+        L.ora_execute_bounded.restype = C.c_int
         _lib = L
     return _lib
 
@@ -245,6 +246,19 @@ def execute(w, s: Slices, b: Binding, pools, staging: np.ndarray, ids=None) -> N
     seg = (C.c_void_p * len(pools))(*[p.ctypes.data for p in pools])
     L.ora_execute(C.c_uint64(n), _p(ids), _p(s.desc), _p(s.off), _p(s.len), _p(b.rail), _p(b.stage_off),
                   _p(b.base), _p(w.src_ptr), _p(w.src_ext), _p(w.dst_ptr), _p(w.dst_ext), seg, _p(staging))
+
+
+def execute_bounded(w, s: Slices, b: Binding, pools, staging: np.ndarray, chunk_bytes: int, ids=None) -> int:
+    """Move the listed slices chunk by chunk through a staging buffer of fixed size (see tent_oracle.c).
+    Returns 0, or -1 if some chunk does not fit the buffer (then nothing has moved)."""
+    L = lib()
+    n = s.n if ids is None else ids.shape[0]
+    seg = (C.c_void_p * len(pools))(*[p.ctypes.data for p in pools])
+    P = np.concatenate([[0], np.cumsum(s.len.astype(np.uint64))]).astype(np.uint64)
+    return int(L.ora_execute_bounded(C.c_uint64(s.n), C.c_uint64(n), _p(ids), _p(s.desc), _p(s.off),
+                                     _p(b.rail), _p(b.stage_off), C.c_uint32(b.T.shape[0]),
+                                     _p(w.src_ptr), _p(w.src_ext), _p(w.dst_ptr), _p(w.dst_ext), seg, _p(staging),
+                                     C.c_uint64(staging.shape[0]), C.c_uint64(chunk_bytes), _p(P)))
 
 
 def retire(s: Slices, b: Binding, queued, budget, ids=None) -> np.ndarray:

@@ -452,6 +452,67 @@ void ora_execute(uint64_t n, const uint32_t *ids,
     }
 }
 
+/* ---- bounded, pipelined staging (Section 4.1: the payload is partitioned into pipelined chunks
+ * that pass through an intermediate buffer of fixed size) -----------------------------------
+ * Reading: the payload is the transfers' logical bytes laid end to end in declaration order
+ * (slice i starts at payload position P_i = sum of the lengths of all slices before it);
+ * chunk c is the payload range [c * chunk_bytes, (c+1) * chunk_bytes).  Chunks pass through
+ * the staging buffer one after the other: all listed (moved) bytes of the chunk are gathered
+ * into the buffer, then written from the buffer to their destination.  Inside the buffer every
+ * rail still owns one contiguous region per chunk: the chunk's bytes on rail d occupy an interval
+ * [lo_d, hi_d) of rail d's staging region (offsets grow with the slice index), they are placed
+ * at region_base_d + (offset - lo_d), and region_base_d is the exclusive sum over rails of
+ * (hi_d - lo_d) rounded up to 256 bytes.
+ * Returns 0, or -1 when some chunk needs more than staging_cap bytes (nothing is moved then). */
+int ora_execute_bounded(uint64_t n_all, uint64_t n, const uint32_t *ids,
+                        const uint32_t *s_desc, const uint64_t *s_off,
+                        const uint32_t *s_rail, const uint64_t *s_stage_off, uint32_t R,
+                        const uint32_t *src_ptr, const ora_extent *src_ext,
+                        const uint32_t *dst_ptr, const ora_extent *dst_ext,
+                        uint8_t *const *seg_base, uint8_t *staging, uint64_t staging_cap,
+                        uint64_t chunk_bytes, const uint64_t *P /* n_all + 1 payload positions */)
+{
+    uint64_t payload = P[n_all];
+    uint64_t n_chunks = (payload + chunk_bytes - 1) / chunk_bytes;
+    for (int pass = 0; pass < 2; ++pass) {            /* pass 0 only checks the capacity */
+        uint64_t q_first = 0;
+        for (uint64_t c = 0; c < n_chunks; ++c) {
+            uint64_t c_lo = c * chunk_bytes, c_hi = c_lo + chunk_bytes;
+            uint64_t lo[64], hi[64], base[64];
+            for (uint32_t d = 0; d < R; ++d) { lo[d] = ~0ull; hi[d] = 0; }
+            while (q_first < n && P[(ids ? ids[q_first] : q_first) + 1] <= c_lo) ++q_first;
+            for (uint64_t q = q_first; q < n; ++q) {
+                uint64_t i = ids ? ids[q] : q;
+                if (P[i] >= c_hi) break;
+                uint64_t from = P[i] > c_lo ? P[i] : c_lo, to = P[i + 1] < c_hi ? P[i + 1] : c_hi;
+                uint64_t reg = s_stage_off[i] + (from - P[i]);
+                uint32_t d = s_rail[i];
+                if (reg < lo[d]) lo[d] = reg;
+                if (reg + (to - from) > hi[d]) hi[d] = reg + (to - from);
+            }
+            uint64_t at = 0;
+            for (uint32_t d = 0; d < R; ++d) {
+                base[d] = at;
+                if (hi[d] > lo[d] && lo[d] != ~0ull) at += (hi[d] - lo[d] + 255) / 256 * 256;
+            }
+            if (at > staging_cap) return -1;
+            if (pass == 0) continue;
+            for (int to_dst = 0; to_dst < 2; ++to_dst)
+                for (uint64_t q = q_first; q < n; ++q) {
+                    uint64_t i = ids ? ids[q] : q;
+                    if (P[i] >= c_hi) break;
+                    uint64_t from = P[i] > c_lo ? P[i] : c_lo, to = P[i + 1] < c_hi ? P[i + 1] : c_hi;
+                    uint64_t x = from - P[i];
+                    uint32_t d = s_rail[i], j = s_desc[i];
+                    uint8_t *st = staging + base[d] + (s_stage_off[i] + x - lo[d]);
+                    if (!to_dst) move_range(seg_base, src_ext, src_ptr[j], src_ptr[j + 1], s_off[i] + x, to - from, st, 1);
+                    else         move_range(seg_base, dst_ext, dst_ptr[j], dst_ptr[j + 1], s_off[i] + x, to - from, st, 0);
+                }
+        }
+    }
+    return 0;
+}
+
 /* ---- rail simulator for the re-planning workload ---------------------------
  * A rail drains its queue in order: the bytes that were already queued
  * (queued[d]) go first, then this plan's slices in staging order.  A slice
