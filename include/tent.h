@@ -48,7 +48,9 @@ enum { TENT_MAX_RAILS = 64 };
 enum {
     TENT_FLAG_SKIP_OVERLAP_CHECK = 1u << 0,   /* tent_declare does not test extents for overlap  */
     TENT_FLAG_PROFILE            = 1u << 1,   /* time every stage with HIP events (see tent_get_timings) */
-    TENT_FLAG_SERIAL_BINDING     = 1u << 2    /* bind slice by slice on one wavefront instead of run-parallel  */
+    TENT_FLAG_SERIAL_BINDING     = 1u << 2,   /* bind slice by slice on one wavefront instead of run-parallel  */
+    TENT_FLAG_BOUNDED_STAGING    = 1u << 3    /* the arena is a bounded buffer: plans do not require it to hold the
+                                                 payload and tent_execute_bounded becomes available             */
 };
 
 typedef struct {
@@ -337,6 +339,25 @@ int tent_get_latencies(tent_ctx *ctx, tent_batch_t batch, uint64_t *host_out, ui
  * never planned.  A batch with no BOUND slice is a no-op.
  */
 int tent_execute(tent_ctx *ctx, tent_batch_t batch, void *stream);
+
+/*
+ * Move every BOUND slice through a staging arena that is smaller than the payload (Section 4.1:
+ * the payload is partitioned into chunks that pass through an intermediate buffer).  The payload --
+ * the transfers' bytes laid end to end in declaration order -- is cut into chunks of chunk_bytes;
+ * for every chunk in turn the BOUND bytes of the chunk are gathered into the arena and then written
+ * to their destination.  Inside the arena every rail keeps one contiguous region per chunk: the
+ * chunk's bytes on rail d form an interval [lo_d, hi_d) of the rail's staging offsets and sit at
+ * region_base_d + (offset - lo_d), region_base_d being the exclusive sum over rails of (hi_d - lo_d)
+ * rounded up to 256 bytes.  Slices are marked DONE as by tent_execute.  Enqueues on `stream`.
+ * Needs a context created with TENT_FLAG_BOUNDED_STAGING (else TENT_ERR_STATE).  TENT_ERR_INVALID
+ * unless chunk_bytes is a positive multiple of 1 MiB; TENT_ERR_RANGE when some extent length or the
+ * slice size is not a multiple of 1 KiB, when chunk_bytes + 256 * n_rails exceeds the arena, or when
+ * the payload needs more than 4096 chunks.  Should a chunk's regions not fit the arena after all
+ * (possible only when the BOUND slices of a rail are not a contiguous run of its staging offsets),
+ * nothing is moved and the slices stay BOUND: tent_poll then still reports them.
+ * With the flag set tent_execute returns TENT_ERR_RANGE when the arena cannot hold the payload.
+ */
+int tent_execute_bounded(tent_ctx *ctx, tent_batch_t batch, uint64_t chunk_bytes, void *stream);
 
 /* Batch-level completion (Section 4.4): *remaining (host) receives the number of
  * slices not DONE.  Waits for `stream`. */

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libtent.so")
 TENT_OK, TENT_DEFER = 0, 1
 TENT_ERR_INVALID, TENT_ERR_RANGE, TENT_ERR_STATE, TENT_ERR_NOMEM, TENT_ERR_HIP = -1, -2, -3, -4, -5
 TENT_MAX_RAILS = 64
-TENT_FLAG_SKIP_OVERLAP_CHECK, TENT_FLAG_PROFILE, TENT_FLAG_SERIAL_BINDING = 1, 2, 4
+TENT_FLAG_SKIP_OVERLAP_CHECK, TENT_FLAG_PROFILE, TENT_FLAG_SERIAL_BINDING, TENT_FLAG_BOUNDED_STAGING = 1, 2, 4, 8
 TENT_SLICE_PENDING, TENT_SLICE_BOUND, TENT_SLICE_DONE = 0, 1, 2
 TENT_T_NAMES = ["extent_scan", "slice_scan", "expand", "compact", "bind", "gather", "scatter", "feedback"]
 
@@ -27,7 +27,7 @@ EXPORTS = ["tent_create", "tent_destroy", "tent_register_segment", "tent_declare
            "tent_sim_advance", "tent_sim_latency", "tent_update_bandwidth", "tent_get_latencies", "tent_execute", "tent_poll", "tent_reset", "tent_slice_count",
            "tent_get_plan", "tent_get_timings", "tent_release", "tent_strerror",
            "tent_sim_fail", "tent_get_retries", "tent_monitor_init", "tent_monitor_update",
-           "tent_plan_dispatch", "tent_get_modes"]
+           "tent_plan_dispatch", "tent_get_modes", "tent_execute_bounded"]
 
 
 class tent_config(C.Structure):
@@ -89,6 +89,7 @@ def lib():
                                             C.c_void_p]
         L.tent_get_latencies.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
         L.tent_execute.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
+        L.tent_execute_bounded.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p]
         L.tent_poll.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64), C.c_void_p]
         L.tent_reset.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
         L.tent_slice_count.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64)]
@@ -250,6 +251,10 @@ def tent_get_latencies(ctx, batch: int) -> np.ndarray:
 
 def tent_execute(ctx, batch: int, stream=None):
     _check(lib().tent_execute(ctx, batch, _stream(stream)), "tent_execute")
+
+
+def tent_execute_bounded(ctx, batch: int, chunk_bytes: int, stream=None):
+    _check(lib().tent_execute_bounded(ctx, batch, chunk_bytes, _stream(stream)), "tent_execute_bounded")
 
 
 def tent_poll(ctx, batch: int, stream=None) -> int:

@@ -1,0 +1,168 @@
+// Bounded, pipelined staging (Section 4.1 of the paper: the payload is partitioned into chunks that
+// pass through an intermediate buffer of fixed size).  The payload -- the transfers' bytes laid end to
+// end in declaration order -- is cut into chunks of chunk_bytes; chunks pass through the staging
+// arena one after the other (gather of the chunk, then scatter of the chunk).  Inside the arena every
+// rail keeps one contiguous region per chunk: the chunk's bytes on rail d form an interval
+// [lo_d, hi_d) of the rail's staging offsets, they sit at region_base_d + (offset - lo_d), and the
+// region bases are the exclusive sum of the interval lengths rounded up to 256 bytes.
+//
+// Both copies walk the chunk's tiles in declaration order (a chunk is a contiguous range of that
+// enumeration), so a chunk's launch touches only its own table entries.
+#include "tent_internal.h"
+
+namespace tent {
+namespace {
+
+constexpr uint64_t kNoTile = ~0ull;
+constexpr uint64_t kRegMask = (1ull << 56) - 1;
+
+__global__ void __launch_bounds__(256) bounded_clear_kernel(BatchDev b, uint32_t n_chunks)
+{
+    const uint32_t at = blockIdx.x * blockDim.x + threadIdx.x;
+    if (at < n_chunks * TENT_MAX_RAILS) {
+        b.ch_lo[at] = kNoTile;
+        b.ch_hi[at] = 0;
+    }
+    if (at == 0) b.plan->bounded_overflow = 0;
+}
+
+// Per tile (declaration order): rail and staging offset of its first byte, or kNoTile when its slice is
+// not BOUND; per (chunk, rail): the interval of staging offsets the chunk touches.  A workgroup covers
+// 256 consecutive tiles, which lie in one chunk because a chunk holds a multiple of 256 tiles.
+__global__ void __launch_bounds__(256) bounded_tiles_kernel(BatchDev b, uint64_t chunk_tiles)
+{
+    __shared__ unsigned long long lo[TENT_MAX_RAILS], hi[TENT_MAX_RAILS];
+    if (threadIdx.x < TENT_MAX_RAILS) { lo[threadIdx.x] = kNoTile; hi[threadIdx.x] = 0; }
+    __syncthreads();
+    const uint64_t first = ((uint64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256;
+    const uint64_t q = first + threadIdx.x;
+    if (q < b.n_sc_tiles) {
+        const uint32_t i = b.ga_slice[q];
+        uint64_t code = kNoTile;
+        if (b.s_state[i] == TENT_SLICE_BOUND) {
+            const uint32_t d = b.s_rail[i];
+            const uint64_t reg = b.s_stage_off[i] + b.ga_x[q];
+            code = ((uint64_t)d << 56) | reg;
+            atomicMin(&lo[d], (unsigned long long)reg);
+            atomicMax(&hi[d], (unsigned long long)(reg + b.tile_bytes));
+        }
+        b.ga_lin[q] = code;
+    }
+    __syncthreads();
+    if (first < b.n_sc_tiles && threadIdx.x < TENT_MAX_RAILS && lo[threadIdx.x] != kNoTile) {
+        const uint64_t c = first / chunk_tiles;
+        atomicMin((unsigned long long*)&b.ch_lo[c * TENT_MAX_RAILS + threadIdx.x], lo[threadIdx.x]);
+        atomicMax((unsigned long long*)&b.ch_hi[c * TENT_MAX_RAILS + threadIdx.x], hi[threadIdx.x]);
+    }
+}
+
+// One wavefront per chunk: region bases of the rails inside the arena for that chunk.
+__global__ void __launch_bounds__(64) bounded_bases_kernel(BatchDev b, uint64_t arena_bytes)
+{
+    const uint64_t row = (uint64_t)blockIdx.x * TENT_MAX_RAILS + threadIdx.x;
+    const uint64_t lo = b.ch_lo[row], hi = b.ch_hi[row];
+    const uint64_t need = (lo != kNoTile && hi > lo) ? ((hi - lo + 255) & ~255ull) : 0;
+    uint64_t inc = need;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint64_t up = (uint64_t)__shfl_up((unsigned long long)inc, d, 64);
+        if ((int)threadIdx.x >= d) inc += up;
+    }
+    b.ch_base[row] = inc - need;
+    if (threadIdx.x == 63 && inc > arena_bytes) atomicAdd((unsigned long long*)&b.plan->bounded_overflow, 1ull);
+}
+
+// Copy the tiles [q_begin, q_end) of one chunk between their paged side and the arena.
+template <bool kGather>
+__global__ void __launch_bounds__(256) bounded_copy_kernel(const uint64_t* __restrict__ paged,
+                                                           const uint64_t* __restrict__ code,
+                                                           const uint64_t* __restrict__ base_row,
+                                                           const uint64_t* __restrict__ lo_row,
+                                                           const uint64_t* __restrict__ overflow,
+                                                           uint8_t* arena, uint64_t q_begin, uint64_t q_end,
+                                                           uint32_t tile_shift)
+{
+    const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    const uint64_t at = w * kCopyBlockBytes + (uint64_t)threadIdx.x * 16;
+    const uint64_t q = q_begin + (at >> tile_shift);
+    if (q >= q_end) return;
+    const uint64_t c = code[q];
+    if (c == kNoTile || *overflow != 0) return;
+    const uint32_t d = (uint32_t)(c >> 56);
+    const uint64_t in_tile = at & ((1ull << tile_shift) - 1);
+    const uint64_t far = paged[q] + in_tile;
+    const uint64_t near = (uint64_t)arena + base_row[d] + ((c & kRegMask) - lo_row[d]) + in_tile;
+    typedef uint32_t vec4u __attribute__((ext_vector_type(4)));
+    typedef vec4u vec4u_any __attribute__((aligned(1)));
+    if (kGather) {
+        const vec4u v = __builtin_nontemporal_load((const vec4u_any*)far);
+        __builtin_nontemporal_store(v, (vec4u_any*)near);
+    } else {
+        const vec4u v = __builtin_nontemporal_load((const vec4u_any*)near);
+        __builtin_nontemporal_store(v, (vec4u_any*)far);
+    }
+}
+
+__global__ void __launch_bounds__(256) mark_done_bounded_kernel(BatchDev b)
+{
+    if (b.plan->bounded_overflow != 0) return;                      // nothing moved: leave the slices BOUND
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slices; i += stride)
+        if (b.s_state[i] == TENT_SLICE_BOUND) b.s_state[i] = TENT_SLICE_DONE;
+}
+
+bool grid_for(uint64_t blocks, dim3* grid)
+{
+    const uint32_t gx = blocks < 65536 ? (uint32_t)blocks : 65536u;
+    const uint64_t gy = (blocks + gx - 1) / gx;
+    if (gy > 0x7FFFFFFFull) return false;
+    *grid = dim3(gx, (uint32_t)gy);
+    return true;
+}
+
+}  // namespace
+
+hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint32_t n_chunks, uint64_t arena_bytes,
+                                  hipStream_t s)
+{
+    const uint32_t cells = n_chunks * TENT_MAX_RAILS;
+    hipLaunchKernelGGL(bounded_clear_kernel, dim3((cells + 255) / 256), dim3(256), 0, s, b, n_chunks);
+    dim3 grid;
+    if (!grid_for((b.n_sc_tiles + 255) / 256, &grid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(bounded_tiles_kernel, grid, dim3(256), 0, s, b, chunk_bytes / b.tile_bytes);
+    hipLaunchKernelGGL(bounded_bases_kernel, dim3(n_chunks), dim3(64), 0, s, b, arena_bytes);
+    return hipGetLastError();
+}
+
+hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t chunk_bytes, uint8_t* arena,
+                               hipStream_t s)
+{
+    uint32_t tile_shift = 0;
+    while ((1u << tile_shift) < b.tile_bytes) ++tile_shift;
+    const uint64_t chunk_tiles = chunk_bytes >> tile_shift;
+    const uint64_t q_begin = (uint64_t)chunk * chunk_tiles;
+    if (q_begin >= b.n_sc_tiles) return hipSuccess;
+    const uint64_t q_end = q_begin + chunk_tiles < b.n_sc_tiles ? q_begin + chunk_tiles : b.n_sc_tiles;
+    const uint64_t bytes = (q_end - q_begin) << tile_shift;
+    dim3 grid;
+    if (!grid_for((bytes + kCopyBlockBytes - 1) / kCopyBlockBytes, &grid)) return hipErrorInvalidValue;
+    const uint64_t* base_row = b.ch_base + (uint64_t)chunk * TENT_MAX_RAILS;
+    const uint64_t* lo_row = b.ch_lo + (uint64_t)chunk * TENT_MAX_RAILS;
+    if (gather)
+        hipLaunchKernelGGL(bounded_copy_kernel<true>, grid, dim3(256), 0, s, b.ga_src, b.ga_lin, base_row, lo_row,
+                           &b.plan->bounded_overflow, arena, q_begin, q_end, tile_shift);
+    else
+        hipLaunchKernelGGL(bounded_copy_kernel<false>, grid, dim3(256), 0, s, b.ga_dst, b.ga_lin, base_row, lo_row,
+                           &b.plan->bounded_overflow, arena, q_begin, q_end, tile_shift);
+    return hipGetLastError();
+}
+
+hipError_t launch_mark_done_bounded(const BatchDev& b, hipStream_t s)
+{
+    uint64_t blocks = (b.n_slices + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(mark_done_bounded_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    return hipGetLastError();
+}
+
+}  // namespace tent

@@ -166,6 +166,12 @@ __global__ void __launch_bounds__(256) gather_table_kernel(BatchDev b)
         b.ga_src[q] = b.seg_base[ex.seg] + ex.off + (at - b.src_pre[e]);
         b.ga_slice[q] = (uint32_t)(b.first[lo] + k);
         b.ga_x[q] = (uint32_t)(off - k * b.slice_bytes);
+        if (b.ga_dst) {                                   // same tile on the destination side
+            const uint64_t dpos = b.dst_pre[b.dst_ptr[lo]] + off;
+            const uint64_t de = last_not_above(b.dst_pre, b.dst_ptr[lo], b.dst_ptr[lo + 1], dpos);
+            const tent_extent dx = b.dst_ext[de];
+            b.ga_dst[q] = b.seg_base[dx.seg] + dx.off + (dpos - b.dst_pre[de]);
+        }
     }
 }
 

@@ -353,6 +353,12 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
         if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_lin, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_slice, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_x, d.n_sc_tiles);
+        if (ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING) {
+            if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_dst, d.n_sc_tiles);
+            if (rc == TENT_OK) rc = dev_alloc(b, &d.ch_lo, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
+            if (rc == TENT_OK) rc = dev_alloc(b, &d.ch_hi, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
+            if (rc == TENT_OK) rc = dev_alloc(b, &d.ch_base, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
+        }
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_dst, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_lin, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_slice, d.n_sc_tiles);
@@ -411,7 +417,8 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     int rc = convert_rails(rails, n_rails, b->payload, &rp);
     if (rc != TENT_OK) return rc;
     if (rp.admitted == 0) return TENT_DEFER;
-    if (b->payload + 256ull * n_rails > ctx->cfg.staging_bytes) return TENT_ERR_RANGE;
+    if (!(ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING) && b->payload + 256ull * n_rails > ctx->cfg.staging_bytes)
+        return TENT_ERR_RANGE;
 
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
@@ -502,7 +509,8 @@ int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state*
     int rc = convert_rails(rails, n_rails, b->payload, &rp);
     if (rc != TENT_OK) return rc;
     if (rp.admitted == 0) return TENT_DEFER;
-    if (b->payload + 256ull * n_rails > ctx->cfg.staging_bytes) return TENT_ERR_RANGE;
+    if (!(ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING) && b->payload + 256ull * n_rails > ctx->cfg.staging_bytes)
+        return TENT_ERR_RANGE;
     if (priority)
         for (uint32_t j = 0; j < b->dev.n_desc; ++j)
             if (priority[j] > 2) return TENT_ERR_INVALID;
@@ -742,6 +750,7 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     Batch* b = find_batch(ctx, batch);
     if (!b) return TENT_ERR_INVALID;
     if (!b->planned) return TENT_ERR_STATE;
+    if (b->payload + 256ull * b->last_rails.n_rails > ctx->cfg.staging_bytes) return TENT_ERR_RANGE;
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -757,6 +766,39 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
         else                   HIP_TRY(launch_copy(b->dev, false, s));
     }
     HIP_TRY(launch_mark_done(b->dev, s));
+    b->has_done = true;
+    return TENT_OK;
+}
+
+int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes, void* stream)
+{
+    if (!ctx) return TENT_ERR_INVALID;
+    Batch* b = find_batch(ctx, batch);
+    if (!b) return TENT_ERR_INVALID;
+    if (!b->planned || !(ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING)) return TENT_ERR_STATE;
+    const BatchDev& d = b->dev;
+    // chunks are cut on 1 MiB boundaries so that 256 consecutive tiles never straddle two chunks
+    if (chunk_bytes == 0 || (chunk_bytes & ((1ull << 20) - 1)) != 0) return TENT_ERR_INVALID;
+    if (d.n_sc_tiles == 0) return TENT_ERR_RANGE;             // geometry: some length is not a multiple of 1 KiB
+    if (chunk_bytes + 256ull * b->last_rails.n_rails > ctx->cfg.staging_bytes) return TENT_ERR_RANGE;
+    const uint64_t n_chunks = (b->payload + chunk_bytes - 1) / chunk_bytes;
+    if (n_chunks > kMaxChunks) return TENT_ERR_RANGE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* arena = static_cast<uint8_t*>(ctx->cfg.staging_arena);
+    HIP_TRY(launch_bounded_prepare(d, chunk_bytes, (uint32_t)n_chunks, ctx->cfg.staging_bytes, s));
+    for (uint32_t c = 0; c < n_chunks; ++c) {
+        {
+            StageTimer t(ctx, TENT_T_GATHER, s);
+            HIP_TRY(launch_bounded_copy(d, true, c, chunk_bytes, arena, s));
+        }
+        {
+            StageTimer t(ctx, TENT_T_SCATTER, s);
+            HIP_TRY(launch_bounded_copy(d, false, c, chunk_bytes, arena, s));
+        }
+    }
+    HIP_TRY(launch_mark_done_bounded(d, s));
     b->has_done = true;
     return TENT_OK;
 }

@@ -81,6 +81,7 @@ struct PlanState {
     uint64_t fail_cnt[TENT_MAX_RAILS];    // tent_sim_fail: slices that failed per rail
     uint64_t n_mice, n_elephant, n_deferred;   // tent_plan_dispatch: requests per mode
     uint64_t rr_next;                     // round-robin counter after the call
+    uint64_t bounded_overflow;            // tent_execute_bounded: chunks whose regions do not fit the arena
 };
 
 // What a copy workgroup needs to know about its slice, in one 16-byte scalar load.
@@ -140,6 +141,10 @@ struct BatchDev {
     uint64_t* ga_lin;              // [n_sc_tiles] gather: staging address, 0 = not to be moved
     uint32_t* ga_slice;            // [n_sc_tiles] slice that holds the tile
     uint32_t* ga_x;                // [n_sc_tiles] byte offset of the tile inside that slice
+    uint64_t* ga_dst;              // [n_sc_tiles] destination address of the tile in declaration order (bounded staging only)
+    uint64_t* ch_lo;               // [kMaxChunks * TENT_MAX_RAILS] bounded staging: first staging offset per chunk and rail
+    uint64_t* ch_hi;               // same shape: end of the interval
+    uint64_t* ch_base;             // same shape: region base inside the arena
     uint64_t* sc_dst;              // [n_sc_tiles] scatter: destination address of the tile
     uint64_t* sc_lin;              // [n_sc_tiles] scatter: staging address, 0 = not to be moved
     uint32_t* sc_slice;
@@ -165,6 +170,7 @@ struct BatchDev {
 enum : uint32_t { kScanBlock = 256, kScanItems = 8, kScanTile = kScanBlock * kScanItems };
 enum : uint32_t { kCopyBlockBytes = 4096 };          // bytes one copy workgroup moves (256 lanes x 16 B)
 constexpr uint64_t kTileSlow = 1ull << 63;
+enum : uint32_t { kMaxChunks = 4096 };               // most chunks one bounded execute may use
 enum : uint32_t { kRotChunk = 1024 };                // retried slices one rotation workgroup handles
 // `mode` argument of the bind kernels
 enum : int { kBindUsePending = 1, kBindAfterRotation = 2 };
@@ -179,6 +185,11 @@ hipError_t launch_bind_serial(const BatchDev& b, const RailParams& rp, int mode,
 hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, hipStream_t s);
 hipError_t launch_rotate(const BatchDev& b, const RotateParams& rot, hipStream_t s);
 hipError_t launch_fail(const BatchDev& b, const FailParams& fp, hipStream_t s);
+hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint32_t n_chunks, uint64_t arena_bytes,
+                                  hipStream_t s);
+hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t chunk_bytes, uint8_t* arena,
+                               hipStream_t s);
+hipError_t launch_mark_done_bounded(const BatchDev& b, hipStream_t s);
 hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, hipStream_t s);
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
 hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s);

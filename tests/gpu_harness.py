@@ -11,7 +11,7 @@ from paper_2604_00368_amd import workloads as W
 class Engine:
     """Device pools + one engine context for one workload (torch only provides memory and the stream)."""
 
-    def __init__(self, w, src_host=None, dst_host=None, flags=0, device="cuda:0", arena_skew=0):
+    def __init__(self, w, src_host=None, dst_host=None, flags=0, device="cuda:0", arena_skew=0, arena_bytes=None):
         self.w = w
         self.dev = torch.device(device)
         torch.cuda.set_device(self.dev)
@@ -24,7 +24,8 @@ class Engine:
         else:
             self.dst = torch.zeros(w.seg_bytes[1], dtype=torch.uint8, device=self.dev)
         # arena_skew > 0 hands the engine a staging arena that starts at an odd address
-        self.arena_full = torch.zeros(w.staging_bytes + arena_skew, dtype=torch.uint8, device=self.dev)
+        n_arena = w.staging_bytes if arena_bytes is None else arena_bytes
+        self.arena_full = torch.zeros(n_arena + arena_skew, dtype=torch.uint8, device=self.dev)
         self.arena = self.arena_full[arena_skew:]
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = T.tent_create(w.slice_bytes, self.arena.data_ptr(), self.arena.numel(), flags)

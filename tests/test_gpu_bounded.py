@@ -1,0 +1,125 @@
+"""GPU parity for bounded, pipelined staging (Section 4.1): chunks of the payload pass through an arena that
+is smaller than the payload; destination and arena bytes against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2604_00368_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+MiB = 1 << 20
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_harness
+    return gpu_harness
+
+
+@pytest.mark.parametrize("name,chunk", [("tiny", 1 * MiB), ("tiny", 3 * MiB), ("kv_migration", 2 * MiB),
+                                        ("rl_params", 1 * MiB), ("many_small", 1 * MiB)])
+def test_bounded_execute_bit_exact(H, oracle, name, chunk):
+    from paper_2604_00368_amd import binding as T
+    w = W.small_variant(name)
+    R = w.rails.shape[0]
+    assert chunk < w.payload
+    cap = chunk + 256 * R
+    src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    b = oracle.bind(s.len, w.rails)
+    dst_want, staging_want = dst0.copy(), np.zeros(cap, dtype=np.uint8)
+    assert oracle.execute_bounded(w, s, b, [src, dst_want], staging_want, chunk) == 0
+    with H.Engine(w, src, dst0, flags=T.TENT_FLAG_BOUNDED_STAGING, arena_bytes=cap) as eng:
+        eng.declare()
+        st, info = eng.plan()
+        assert st == 0
+        H.assert_plan_equal(eng.table(), s, b, info)
+        T.tent_execute_bounded(eng.ctx, eng.batch, chunk, eng.stream)
+        torch.cuda.synchronize()
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+        assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+        assert np.array_equal(eng.src.cpu().numpy(), src)
+
+
+def test_bounded_execute_over_replanning_epochs(H, oracle):
+    # every epoch only the slices that stayed bound move (a FIFO prefix per rail), through a 1 MiB buffer
+    from paper_2604_00368_amd import binding as T
+    w = W.replanning(n_req=6, layers=4, ctx_lo=400, ctx_hi=2000, queued_hi=1 << 20)
+    R = w.rails.shape[0]
+    chunk = 4 * MiB
+    cap = chunk + 256 * R
+    src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    dst_want, staging_want = dst0.copy(), np.zeros(cap, dtype=np.uint8)
+    pending = np.arange(s.n, dtype=np.uint32)
+    with H.Engine(w, src, dst0, flags=T.TENT_FLAG_BOUNDED_STAGING, arena_bytes=cap) as eng:
+        eng.declare()
+        for e, ep in enumerate(list(w.epochs) + [w.drain]):
+            if pending.shape[0] == 0:
+                break
+            b = oracle.bind(s.len, ep.rails, ids=pending)
+            assert b.status == 0
+            done = oracle.retire(s, b, ep.rails["queued_bytes"], ep.budget, ids=pending).astype(bool)
+            ids = np.ascontiguousarray(pending[done])
+            if ids.shape[0]:
+                assert oracle.execute_bounded(w, s, b, [src, dst_want], staging_want, chunk, ids=ids) == 0
+            print("bounded epoch", e, "pending", pending.shape[0], "moved", ids.shape[0], flush=True)
+            st, info = eng.plan(rails=ep.rails)
+            assert st == 0 and info.n_slices == pending.shape[0]
+            assert T.tent_sim_advance(eng.ctx, eng.batch, ep.budget, eng.stream) == ids.shape[0]
+            T.tent_execute_bounded(eng.ctx, eng.batch, chunk, eng.stream)
+            torch.cuda.synchronize()
+            assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+            assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+            pending = np.ascontiguousarray(pending[~done])
+            assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == pending.shape[0]
+        assert pending.shape[0] == 0
+
+
+def test_bounded_argument_errors(H, oracle):
+    from paper_2604_00368_amd import binding as T
+    w = W.tiny()
+    R = w.rails.shape[0]
+    src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
+    with H.Engine(w, src, dst0) as eng:                       # context without the flag
+        h = eng.declare()
+        eng.plan()
+        with pytest.raises(T.TentError) as ei:
+            T.tent_execute_bounded(eng.ctx, h, MiB, eng.stream)
+        assert ei.value.status == T.TENT_ERR_STATE
+    cap = 2 * MiB + 256 * R
+    with H.Engine(w, src, dst0, flags=T.TENT_FLAG_BOUNDED_STAGING, arena_bytes=cap) as eng:
+        h = eng.declare()
+        with pytest.raises(T.TentError) as ei:
+            T.tent_execute_bounded(eng.ctx, h, MiB, eng.stream)
+        assert ei.value.status == T.TENT_ERR_STATE             # not planned yet
+        st, _ = eng.plan()                                     # the arena is smaller than the payload: allowed here
+        assert st == 0
+        for bad in (0, MiB + 4096, MiB // 2):
+            with pytest.raises(T.TentError) as ei:
+                T.tent_execute_bounded(eng.ctx, h, bad, eng.stream)
+            assert ei.value.status == T.TENT_ERR_INVALID
+        with pytest.raises(T.TentError) as ei:
+            T.tent_execute_bounded(eng.ctx, h, 3 * MiB, eng.stream)     # chunk does not fit the arena
+        assert ei.value.status == T.TENT_ERR_RANGE
+        with pytest.raises(T.TentError) as ei:
+            T.tent_execute(eng.ctx, h, eng.stream)                      # the unbounded execute needs the whole payload
+        assert ei.value.status == T.TENT_ERR_RANGE
+        assert np.array_equal(eng.dst.cpu().numpy(), dst0)      # nothing has moved so far
+        T.tent_execute_bounded(eng.ctx, h, 2 * MiB, eng.stream)
+        torch.cuda.synchronize()
+        assert T.tent_poll(eng.ctx, h, eng.stream) == 0
+    wr = W.ragged(3)                                           # odd lengths: no tile size fits
+    with H.Engine(wr, W.fill_numpy(wr, 0), W.fill_numpy(wr, 1), flags=T.TENT_FLAG_BOUNDED_STAGING) as eng:
+        h = eng.declare()
+        eng.plan()
+        with pytest.raises(T.TentError) as ei:
+            T.tent_execute_bounded(eng.ctx, h, MiB, eng.stream)
+        assert ei.value.status == T.TENT_ERR_RANGE
+        eng.execute()                                          # the arena holds the payload: plain execute still works
+        assert T.tent_poll(eng.ctx, h, eng.stream) == 0

@@ -187,3 +187,46 @@ def test_full_size_dispatch(H, oracle, name):
     assert done.all() and 2 in modes
     gc.collect()
     torch.cuda.empty_cache()
+
+
+def test_full_size_bounded_staging(H, oracle):
+    # config 2 through an arena of one sixteenth of the payload: plan in full against the oracle, every
+    # destination byte by the plain definition, sampled transfers against the oracle's bounded execute
+    from paper_2604_00368_amd import binding as T
+    print("full-size bounded staging", flush=True)
+    w = full_config("kv_migration")
+    R = w.rails.shape[0]
+    chunk = 1280 << 20
+    cap = chunk + 256 * R
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    b = oracle.bind(s.len, w.rails)
+    eng = H.Engine(w, flags=T.TENT_FLAG_PROFILE | T.TENT_FLAG_BOUNDED_STAGING, arena_bytes=cap)
+    try:
+        eng.declare()
+        st, _ = eng.plan(want_info=False)
+        assert st == 0
+        T.tent_execute_bounded(eng.ctx, eng.batch, chunk, eng.stream)
+        torch.cuda.synchronize()
+        H.assert_plan_equal(eng.table(), s, b)
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        device_definition_check(w, eng.src, eng.dst)
+        # destination bytes of a few transfers, moved by the oracle on the host
+        sample = pick_sample(w, 6, seed=5)
+        src_h = np.zeros(w.seg_bytes[0], dtype=np.uint8)
+        dst_h = np.zeros(w.seg_bytes[1], dtype=np.uint8)
+        for j in sample:
+            for e in w.src_ext[w.src_ptr[j]:w.src_ptr[j + 1]]:
+                o, n = int(e["off"]), int(e["len"])
+                src_h[o:o + n] = eng.src[o:o + n].cpu().numpy()
+        ids = np.concatenate([np.arange(s.first[j], s.first[j + 1], dtype=np.uint32) for j in sample])
+        stg_h = np.zeros(cap, dtype=np.uint8)
+        assert oracle.execute_bounded(w, s, b, [src_h, dst_h], stg_h, chunk, ids=np.ascontiguousarray(ids)) == 0
+        for j in sample:
+            for e in w.dst_ext[w.dst_ptr[j]:w.dst_ptr[j + 1]]:
+                o, n = int(e["off"]), int(e["len"])
+                assert np.array_equal(eng.dst[o:o + n].cpu().numpy(), dst_h[o:o + n]), (j, o)
+    finally:
+        eng.close()
+        del eng
+        gc.collect()
+        torch.cuda.empty_cache()
