@@ -63,6 +63,21 @@ int main(void) {
          offsetof(tent_plan_info, rail_slices), offsetof(tent_plan_info, queued_after), offsetof(tent_plan_info, stage_base));
   printf("slice %zu %zu %zu %zu %zu %zu %zu\n", sizeof(tent_slice), offsetof(tent_slice, desc), offsetof(tent_slice, len),
          offsetof(tent_slice, off), offsetof(tent_slice, stage_off), offsetof(tent_slice, rail), offsetof(tent_slice, state));
+  printf("dparams %zu %zu %zu %zu %zu\n", sizeof(tent_dispatch_params), offsetof(tent_dispatch_params, theta_bytes),
+         offsetof(tent_dispatch_params, gamma_q8), offsetof(tent_dispatch_params, window), offsetof(tent_dispatch_params, rr_start));
+  printf("dinfo %zu %zu %zu %zu %zu %zu\n", sizeof(tent_dispatch_info), offsetof(tent_dispatch_info, plan),
+         offsetof(tent_dispatch_info, n_mice), offsetof(tent_dispatch_info, n_elephant),
+         offsetof(tent_dispatch_info, n_deferred), offsetof(tent_dispatch_info, rr_next));
+  printf("mparams %zu %zu %zu %zu %zu\n", sizeof(tent_monitor_params), offsetof(tent_monitor_params, err_threshold),
+         offsetof(tent_monitor_params, recover_windows), offsetof(tent_monitor_params, cooldown_windows),
+         offsetof(tent_monitor_params, degrade_q8));
+  printf("monitor %zu %zu %zu %zu %zu %zu\n", sizeof(tent_rail_monitor), offsetof(tent_rail_monitor, state),
+         offsetof(tent_rail_monitor, score), offsetof(tent_rail_monitor, clean), offsetof(tent_rail_monitor, cooldown_left),
+         offsetof(tent_rail_monitor, cooldown_next));
+  printf("probe %zu %zu %zu %zu %zu\n", sizeof(tent_probe_params), offsetof(tent_probe_params, hw_MBps),
+         offsetof(tent_probe_params, alpha_q8), offsetof(tent_probe_params, delta_ns), offsetof(tent_probe_params, ewma_q8));
+  printf("flags %d %d %d %d\n", TENT_FLAG_SKIP_OVERLAP_CHECK, TENT_FLAG_PROFILE, TENT_FLAG_SERIAL_BINDING,
+         TENT_FLAG_BOUNDED_STAGING);
   printf("consts %d %d %d %d %d %d %d\n", TENT_MAX_RAILS, TENT_T_COUNT, TENT_DEFER, TENT_ERR_INVALID, TENT_ERR_RANGE,
          TENT_ERR_STATE, TENT_FLAG_SERIAL_BINDING);
   return 0;
@@ -83,6 +98,13 @@ int main(void) {
     assert out["info"] == ct(T.tent_plan_info, "n_slices", "n_pending_before", "rail_bytes", "rail_slices",
                              "queued_after", "stage_base")
     assert out["slice"] == nd(T.SLICE_DTYPE, "desc", "len", "off", "stage_off", "rail", "state")
+    assert out["dparams"] == nd(W.DISPATCH_PARAMS_DTYPE, "theta_bytes", "gamma_q8", "window", "rr_start")
+    assert out["dinfo"] == ct(T.tent_dispatch_info, "plan", "n_mice", "n_elephant", "n_deferred", "rr_next")
+    assert out["mparams"] == nd(W.MONITOR_PARAMS_DTYPE, "err_threshold", "recover_windows", "cooldown_windows", "degrade_q8")
+    assert out["monitor"] == nd(T.MONITOR_DTYPE, "state", "score", "clean", "cooldown_left", "cooldown_next")
+    assert out["probe"] == nd(W.PROBE_DTYPE, "hw_MBps", "alpha_q8", "delta_ns", "ewma_q8")
+    assert out["flags"] == [T.TENT_FLAG_SKIP_OVERLAP_CHECK, T.TENT_FLAG_PROFILE, T.TENT_FLAG_SERIAL_BINDING,
+                            T.TENT_FLAG_BOUNDED_STAGING]
     assert out["consts"] == [T.TENT_MAX_RAILS, len(T.TENT_T_NAMES), T.TENT_DEFER, T.TENT_ERR_INVALID,
                              T.TENT_ERR_RANGE, T.TENT_ERR_STATE, T.TENT_FLAG_SERIAL_BINDING]
 
@@ -100,8 +122,51 @@ def test_argument_errors_need_no_device(T):
     assert L.tent_create(C.byref(ctx), C.byref(cfg)) == T.TENT_ERR_RANGE
     assert L.tent_destroy(None) == T.TENT_ERR_INVALID
     assert L.tent_execute(None, 1, None) == T.TENT_ERR_INVALID
+    assert L.tent_execute_bounded(None, 1, 1 << 20, None) == T.TENT_ERR_INVALID
+    assert L.tent_plan_dispatch(None, 1, None, 0, None, None, None, None) == T.TENT_ERR_INVALID
+    assert L.tent_sim_fail(None, 1, None, None, None) == T.TENT_ERR_INVALID
+    assert L.tent_get_retries(None, 1, None, 0) == T.TENT_ERR_INVALID
+    assert L.tent_get_modes(None, 1, None, 0) == T.TENT_ERR_INVALID
+    assert L.tent_monitor_init(None, None, 3) == T.TENT_ERR_INVALID
     for st, word in [(0, "ok"), (1, "defer"), (-1, "invalid"), (-2, "range"), (-3, "order"), (-4, "memory"), (-5, "HIP")]:
         assert word.lower() in T.tent_strerror(st).lower()
+
+
+def test_rail_monitor_matches_the_oracle(T):
+    # the health monitor is host arithmetic: the library's state machine against the oracle's, window by window
+    import oracle
+    from paper_2604_00368_amd import workloads as W
+    for seed in range(6):
+        rng = np.random.Generator(np.random.PCG64(600 + seed))
+        R = int(rng.integers(1, 65))
+        mp = W.make_monitor_params(err_threshold=int(rng.integers(0, 6)), recover_windows=int(rng.integers(0, 4)),
+                                   cooldown_windows=int(rng.integers(0, 4)), degrade_q8=int(rng.choice([0, 128, 200, 256])))
+        rails = W.make_rails(rng.integers(1000, 100000, R))
+        mon = T.tent_monitor_init(mp, R)
+        ref = oracle.monitor_init(R, mp)
+        for f in mon.dtype.names:
+            assert np.array_equal(mon[f], ref[f])
+        for window in range(60):
+            hard = (rng.integers(0, 8, R) * (rng.random(R) < 0.2)).astype(np.uint32)
+            cong = (rng.integers(0, 12, R) * (rng.random(R) < 0.3)).astype(np.uint32)
+            bw = rng.integers(1000, 100000, R).astype(np.uint32)
+            probe = (bw * rng.choice([0.0, 0.3, 0.49, 0.5, 0.9, 1.0], R)).astype(np.uint32)
+            out = T.tent_monitor_update(mp, mon, rails, hard, cong, probe, bw)
+            oracle.monitor_step(mp, ref, hard, cong, probe, bw)
+            for f in mon.dtype.names:
+                assert np.array_equal(mon[f], ref[f]), (seed, window, f)
+            assert np.array_equal(out["health"], ref["state"].astype(np.uint8))
+            assert np.array_equal(out["bw_MBps"], rails["bw_MBps"])      # only the health field changes
+    # argument errors
+    mp = W.make_monitor_params()
+    mon = T.tent_monitor_init(mp, 2)
+    with pytest.raises(T.TentError) as ei:
+        T.tent_monitor_init(mp, 65)
+    assert ei.value.status == T.TENT_ERR_RANGE
+    mon["state"][1] = 7
+    with pytest.raises(T.TentError) as ei:
+        T.tent_monitor_update(mp, mon, W.make_rails([1, 1]), [0, 0], [0, 0], [0, 0], [1, 1])
+    assert ei.value.status == T.TENT_ERR_INVALID
 
 
 def test_product_path_does_not_import_the_oracle():
