@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0
 # to one version of the copy kernels and of the kernels that build their tables: when copy.hip or
 # split.hip changes they are reported as null.
 PMC_TRAFFIC = {
-    "copy_sources_sha256": "b8d8e760afa366467806bca88108ba534c87cb511efbf1825e1b504c762d56f6",
-    "kv_migration": {"gather": 43019338055, "scatter": 43019354695},
+    "copy_sources_sha256": "f8c1b7167c4631110664103de29987d72fe682492916a0476eb06a003c3321c5",
+    "kv_migration": {"gather": 43019337927, "scatter": 43019354439},
 }
 
 
