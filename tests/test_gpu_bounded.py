@@ -123,3 +123,36 @@ def test_bounded_argument_errors(H, oracle):
         assert ei.value.status == T.TENT_ERR_RANGE
         eng.execute()                                          # the arena holds the payload: plain execute still works
         assert T.tent_poll(eng.ctx, h, eng.stream) == 0
+
+
+def test_bounded_execute_after_dispatch_with_odd_addresses(H, oracle):
+    # the bounded execute moves whatever is BOUND, whoever planned it: request-level dispatch with deferred
+    # transfers, pages and arena at odd addresses, 1 KiB tiles
+    from paper_2604_00368_amd import binding as T
+    w = W.kv_migration(n_req=5, layers=2, ctx_lo=300, ctx_hi=1200, page_tokens=1, head_dim=64, skew=(3, 5))   # 1 KiB pages
+    w.rails = w.rails[:2].copy()
+    R = w.rails.shape[0]
+    chunk = 2 * MiB
+    cap = chunk + 256 * R
+    src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    prio = W.make_priorities(8, w.n_desc)
+    dst_want, staging_want = dst0.copy(), np.zeros(cap, dtype=np.uint8)
+    done = np.zeros(s.n, dtype=np.uint8)
+    with H.Engine(w, src, dst0, flags=T.TENT_FLAG_BOUNDED_STAGING, arena_bytes=cap, arena_skew=7) as eng:
+        eng.declare()
+        for window in range(3):
+            dp = W.make_dispatch_params(4 * w.slice_bytes, window=window)
+            r = oracle.dispatch(s, w.rails, dp, priority=prio, done=done)
+            ids = np.flatnonzero(r.bound).astype(np.uint32)
+            if ids.shape[0]:
+                assert oracle.execute_bounded(w, s, r.binding, [src, dst_want], staging_want, chunk, ids=ids) == 0
+            st, info = T.tent_plan_dispatch(eng.ctx, eng.batch, w.rails, dp, prio, True, eng.stream)
+            assert st == 0 and info.plan.n_slices == ids.shape[0]
+            T.tent_execute_bounded(eng.ctx, eng.batch, chunk, eng.stream)
+            torch.cuda.synchronize()
+            done[ids] = 1
+            assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == int((done == 0).sum())
+            assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+            assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+        assert done.all()
