@@ -248,7 +248,8 @@ def execute(w, s: Slices, b: Binding, pools, staging: np.ndarray, ids=None) -> N
                   _p(b.base), _p(w.src_ptr), _p(w.src_ext), _p(w.dst_ptr), _p(w.dst_ext), seg, _p(staging))
 
 
-def execute_bounded(w, s: Slices, b: Binding, pools, staging: np.ndarray, chunk_bytes: int, ids=None) -> int:
+def execute_bounded(w, s: Slices, b: Binding, pools, staging: np.ndarray, chunk_bytes: int, ids=None,
+                    slots: int = 1, slot_bytes: Optional[int] = None) -> int:
     """Move the listed slices chunk by chunk through a staging buffer of fixed size (see tent_oracle.c).
     Returns 0, or -1 if some chunk does not fit the buffer (then nothing has moved)."""
     L = lib()
@@ -258,7 +259,8 @@ def execute_bounded(w, s: Slices, b: Binding, pools, staging: np.ndarray, chunk_
     return int(L.ora_execute_bounded(C.c_uint64(s.n), C.c_uint64(n), _p(ids), _p(s.desc), _p(s.off),
                                      _p(b.rail), _p(b.stage_off), C.c_uint32(b.T.shape[0]),
                                      _p(w.src_ptr), _p(w.src_ext), _p(w.dst_ptr), _p(w.dst_ext), seg, _p(staging),
-                                     C.c_uint64(staging.shape[0]), C.c_uint64(chunk_bytes), _p(P)))
+                                     C.c_uint64(staging.shape[0]), C.c_uint64(chunk_bytes), C.c_uint32(slots),
+                                     C.c_uint64(staging.shape[0] if slot_bytes is None else slot_bytes), _p(P)))
 
 
 def retire(s: Slices, b: Binding, queued, budget, ids=None) -> np.ndarray:

@@ -463,15 +463,22 @@ void ora_execute(uint64_t n, const uint32_t *ids,
  * [lo_d, hi_d) of rail d's staging region (offsets grow with the slice index), they are placed
  * at region_base_d + (offset - lo_d), and region_base_d is the exclusive sum over rails of
  * (hi_d - lo_d) rounded up to 256 bytes.
- * Returns 0, or -1 when some chunk needs more than staging_cap bytes (nothing is moved then). */
+ * With slots > 1 the buffer is divided into that many slots of slot_bytes each and chunk c uses
+ * slot c mod slots, so that a chunk can be filled while its predecessor is still being drained
+ * (the overlap of consecutive stages described in Section 4.1); the bytes that end up in every
+ * slot do not depend on how the stages overlap in time.
+ * Returns 0, or -1 when some chunk needs more than a slot or the slots exceed the buffer (nothing is
+ * moved then). */
 int ora_execute_bounded(uint64_t n_all, uint64_t n, const uint32_t *ids,
                         const uint32_t *s_desc, const uint64_t *s_off,
                         const uint32_t *s_rail, const uint64_t *s_stage_off, uint32_t R,
                         const uint32_t *src_ptr, const ora_extent *src_ext,
                         const uint32_t *dst_ptr, const ora_extent *dst_ext,
                         uint8_t *const *seg_base, uint8_t *staging, uint64_t staging_cap,
-                        uint64_t chunk_bytes, const uint64_t *P /* n_all + 1 payload positions */)
+                        uint64_t chunk_bytes, uint32_t slots, uint64_t slot_bytes,
+                        const uint64_t *P /* n_all + 1 payload positions */)
 {
+    if (slots == 0 || slot_bytes > staging_cap / slots) return -1;
     uint64_t payload = P[n_all];
     uint64_t n_chunks = (payload + chunk_bytes - 1) / chunk_bytes;
     for (int pass = 0; pass < 2; ++pass) {            /* pass 0 only checks the capacity */
@@ -495,7 +502,7 @@ int ora_execute_bounded(uint64_t n_all, uint64_t n, const uint32_t *ids,
                 base[d] = at;
                 if (hi[d] > lo[d] && lo[d] != ~0ull) at += (hi[d] - lo[d] + 255) / 256 * 256;
             }
-            if (at > staging_cap) return -1;
+            if (at > slot_bytes) return -1;
             if (pass == 0) continue;
             for (int to_dst = 0; to_dst < 2; ++to_dst)
                 for (uint64_t q = q_first; q < n; ++q) {
@@ -504,7 +511,7 @@ int ora_execute_bounded(uint64_t n_all, uint64_t n, const uint32_t *ids,
                     uint64_t from = P[i] > c_lo ? P[i] : c_lo, to = P[i + 1] < c_hi ? P[i + 1] : c_hi;
                     uint64_t x = from - P[i];
                     uint32_t d = s_rail[i], j = s_desc[i];
-                    uint8_t *st = staging + base[d] + (s_stage_off[i] + x - lo[d]);
+                    uint8_t *st = staging + (c % slots) * slot_bytes + base[d] + (s_stage_off[i] + x - lo[d]);
                     if (!to_dst) move_range(seg_base, src_ext, src_ptr[j], src_ptr[j + 1], s_off[i] + x, to - from, st, 1);
                     else         move_range(seg_base, dst_ext, dst_ptr[j], dst_ptr[j + 1], s_off[i] + x, to - from, st, 0);
                 }

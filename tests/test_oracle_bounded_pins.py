@@ -78,6 +78,49 @@ def test_bounded_execute_with_odd_lengths(oracle, seed):
     assert np.array_equal(staging, want) and peak > chunk
 
 
+def test_slots_hold_alternating_chunks(oracle):
+    # two slots: even chunks in the first, odd chunks in the second; each slot ends up exactly as a one-slot
+    # run over only its own chunks would leave it, and the destination is the same
+    w = W.small_variant("kv_migration")
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    b = oracle.bind(s.len, w.rails)
+    src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
+    chunk = 2 * MiB
+    slot = chunk + 256 * w.rails.shape[0]
+    dst, staging = dst0.copy(), np.zeros(2 * slot, dtype=np.uint8)
+    assert oracle.execute_bounded(w, s, b, [src, dst], staging, chunk, slots=2, slot_bytes=slot) == 0
+    assert np.array_equal(dst, expected_destination(w, src, dst0))
+    P = np.concatenate([[0], np.cumsum(s.len.astype(np.int64))])
+    for parity in (0, 1):
+        # brute force over the payload with the other parity's chunks blanked out
+        ids = [i for i in range(s.n)]
+        want = np.zeros(slot, dtype=np.uint8)
+        full, _ = None, None
+        rail = np.full(int(P[-1]), -1, dtype=np.int64)
+        reg = np.zeros(int(P[-1]), dtype=np.int64)
+        val = np.zeros(int(P[-1]), dtype=np.uint8)
+        for i in ids:
+            j = int(s.desc[i])
+            data = logical_bytes({0: src}, w.src_ext[w.src_ptr[j]:w.src_ptr[j + 1]])
+            lo, n = int(P[i]), int(s.len[i])
+            rail[lo:lo + n] = int(b.rail[i]); reg[lo:lo + n] = int(b.stage_off[i]) + np.arange(n)
+            val[lo:lo + n] = data[int(s.off[i]):int(s.off[i]) + n]
+        for c, c_lo in enumerate(range(0, int(P[-1]), chunk)):
+            if c % 2 != parity:
+                continue
+            sl = slice(c_lo, min(int(P[-1]), c_lo + chunk))
+            at = 0
+            for d in range(w.rails.shape[0]):
+                m = rail[sl] == d
+                if m.any():
+                    r = reg[sl][m]
+                    want[at + r - r.min()] = val[sl][m]
+                    at += -(-(int(r.max()) + 1 - int(r.min())) // 256) * 256
+        assert np.array_equal(staging[parity * slot:(parity + 1) * slot], want)
+    # slots that do not fit the buffer are refused
+    assert oracle.execute_bounded(w, s, b, [src, dst0.copy()], staging[:slot], chunk, slots=2, slot_bytes=slot) == -1
+
+
 def test_one_chunk_is_the_unbounded_execute(oracle):
     w = W.small_variant("kv_migration")
     s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
