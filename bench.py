@@ -266,23 +266,24 @@ def main():
         T.tent_register_segment(ctx_b, dst.data_ptr(), dst.numel())
         h_b = T.tent_declare(ctx_b, w.src_ptr, w.src_ext, w.dst_ptr, w.dst_ext)
         for chunk in sorted({max(1, (w.payload // 8) >> 20) << 20, 256 << 20}, reverse=True):
-            if chunk + 256 * R > arena.numel() or chunk >= w.payload:
-                continue
-            best = None
-            for _ in range(3):
-                T.tent_reset(ctx_b, h_b, stream)
-                T.tent_plan(ctx_b, h_b, w.rails, want_info=False, stream=stream)
-                torch.cuda.synchronize(dev)
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                T.tent_execute_bounded(ctx_b, h_b, chunk, stream)
-                e1.record()
-                torch.cuda.synchronize(dev)
-                ms = e0.elapsed_time(e1)
-                best = ms if best is None else min(best, ms)
-            assert T.tent_poll(ctx_b, h_b, stream) == 0
-            bounded.append({"arena_MiB": chunk >> 20, "chunks": -(-w.payload // chunk), "execute_ms": round(best, 4),
-                            "GBps": round(4 * w.payload / (best * 1e-3) / 1e9, 2)})
+            for slots in (1, 2):
+                if slots * (chunk + 256 * R) > arena.numel() or chunk >= w.payload:
+                    continue
+                best = None
+                for _ in range(3):
+                    T.tent_reset(ctx_b, h_b, stream)
+                    T.tent_plan(ctx_b, h_b, w.rails, want_info=False, stream=stream)
+                    torch.cuda.synchronize(dev)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    T.tent_execute_bounded(ctx_b, h_b, chunk, stream, slots=slots)
+                    e1.record()
+                    torch.cuda.synchronize(dev)
+                    ms = e0.elapsed_time(e1)
+                    best = ms if best is None else min(best, ms)
+                assert T.tent_poll(ctx_b, h_b, stream) == 0
+                bounded.append({"slot_MiB": chunk >> 20, "slots": slots, "chunks": -(-w.payload // chunk),
+                                "execute_ms": round(best, 4), "GBps": round(4 * w.payload / (best * 1e-3) / 1e9, 2)})
         T.tent_destroy(ctx_b)
 
     # Plain copy of known size (1 GiB read + 1 GiB written by one elementwise kernel), outside the

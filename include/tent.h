@@ -348,16 +348,21 @@ int tent_execute(tent_ctx *ctx, tent_batch_t batch, void *stream);
  * to their destination.  Inside the arena every rail keeps one contiguous region per chunk: the
  * chunk's bytes on rail d form an interval [lo_d, hi_d) of the rail's staging offsets and sit at
  * region_base_d + (offset - lo_d), region_base_d being the exclusive sum over rails of (hi_d - lo_d)
- * rounded up to 256 bytes.  Slices are marked DONE as by tent_execute.  Enqueues on `stream`.
+ * rounded up to 256 bytes.  The arena is used as `slots` (1 or 2) slots of chunk_bytes + 256 * n_rails
+ * bytes; chunk c lives in slot c mod slots.  With two slots the gather of chunk c + 1 overlaps the
+ * scatter of chunk c: gathers are enqueued on `stream`, scatters on a stream of the library's own
+ * (default priority), ordered by events, and `stream` is made to wait for the last scatter, so work
+ * enqueued on `stream` afterwards sees the batch complete.  Slices are marked DONE as by
+ * tent_execute.  Only enqueues.
  * Needs a context created with TENT_FLAG_BOUNDED_STAGING (else TENT_ERR_STATE).  TENT_ERR_INVALID
- * unless chunk_bytes is a positive multiple of 1 MiB; TENT_ERR_RANGE when some extent length or the
- * slice size is not a multiple of 1 KiB, when chunk_bytes + 256 * n_rails exceeds the arena, or when
- * the payload needs more than 4096 chunks.  Should a chunk's regions not fit the arena after all
+ * unless chunk_bytes is a positive multiple of 1 MiB and slots is 1 or 2; TENT_ERR_RANGE when some
+ * extent length or the slice size is not a multiple of 1 KiB, when the slots exceed the arena, or
+ * when the payload needs more than 4096 chunks.  Should a chunk's regions not fit the arena after all
  * (possible only when the BOUND slices of a rail are not a contiguous run of its staging offsets),
  * nothing is moved and the slices stay BOUND: tent_poll then still reports them.
  * With the flag set tent_execute returns TENT_ERR_RANGE when the arena cannot hold the payload.
  */
-int tent_execute_bounded(tent_ctx *ctx, tent_batch_t batch, uint64_t chunk_bytes, void *stream);
+int tent_execute_bounded(tent_ctx *ctx, tent_batch_t batch, uint64_t chunk_bytes, uint32_t slots, void *stream);
 
 /* Batch-level completion (Section 4.4): *remaining (host) receives the number of
  * slices not DONE.  Waits for `stream`. */

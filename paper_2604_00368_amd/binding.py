@@ -89,7 +89,7 @@ def lib():
                                             C.c_void_p]
         L.tent_get_latencies.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
         L.tent_execute.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
-        L.tent_execute_bounded.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p]
+        L.tent_execute_bounded.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint32, C.c_void_p]
         L.tent_poll.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64), C.c_void_p]
         L.tent_reset.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
         L.tent_slice_count.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64)]
@@ -253,8 +253,8 @@ def tent_execute(ctx, batch: int, stream=None):
     _check(lib().tent_execute(ctx, batch, _stream(stream)), "tent_execute")
 
 
-def tent_execute_bounded(ctx, batch: int, chunk_bytes: int, stream=None):
-    _check(lib().tent_execute_bounded(ctx, batch, chunk_bytes, _stream(stream)), "tent_execute_bounded")
+def tent_execute_bounded(ctx, batch: int, chunk_bytes: int, stream=None, slots: int = 1):
+    _check(lib().tent_execute_bounded(ctx, batch, chunk_bytes, slots, _stream(stream)), "tent_execute_bounded")
 
 
 def tent_poll(ctx, batch: int, stream=None) -> int:

@@ -2,7 +2,8 @@
 // pass through an intermediate buffer of fixed size).  The payload -- the transfers' bytes laid end to
 // end in declaration order -- is cut into chunks of chunk_bytes; chunks pass through the staging
 // arena one after the other (gather of the chunk, then scatter of the chunk).  Inside the arena every
-// rail keeps one contiguous region per chunk: the chunk's bytes on rail d form an interval
+// rail keeps one contiguous region per chunk (chunk c lives in slot c mod slots of the arena, so that
+// with two slots a chunk can be gathered while its predecessor is still being scattered): the chunk's bytes on rail d form an interval
 // [lo_d, hi_d) of the rail's staging offsets, they sit at region_base_d + (offset - lo_d), and the
 // region bases are the exclusive sum of the interval lengths rounded up to 256 bytes.
 //
@@ -57,7 +58,7 @@ __global__ void __launch_bounds__(256) bounded_tiles_kernel(BatchDev b, uint64_t
 }
 
 // One wavefront per chunk: region bases of the rails inside the arena for that chunk.
-__global__ void __launch_bounds__(64) bounded_bases_kernel(BatchDev b, uint64_t arena_bytes)
+__global__ void __launch_bounds__(64) bounded_bases_kernel(BatchDev b, uint64_t slot_bytes)
 {
     const uint64_t row = (uint64_t)blockIdx.x * TENT_MAX_RAILS + threadIdx.x;
     const uint64_t lo = b.ch_lo[row], hi = b.ch_hi[row];
@@ -69,7 +70,7 @@ __global__ void __launch_bounds__(64) bounded_bases_kernel(BatchDev b, uint64_t 
         if ((int)threadIdx.x >= d) inc += up;
     }
     b.ch_base[row] = inc - need;
-    if (threadIdx.x == 63 && inc > arena_bytes) atomicAdd((unsigned long long*)&b.plan->bounded_overflow, 1ull);
+    if (threadIdx.x == 63 && inc > slot_bytes) atomicAdd((unsigned long long*)&b.plan->bounded_overflow, 1ull);
 }
 
 // Copy the tiles [q_begin, q_end) of one chunk between their paged side and the arena.
@@ -122,7 +123,7 @@ bool grid_for(uint64_t blocks, dim3* grid)
 
 }  // namespace
 
-hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint32_t n_chunks, uint64_t arena_bytes,
+hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint32_t n_chunks, uint64_t slot_bytes,
                                   hipStream_t s)
 {
     const uint32_t cells = n_chunks * TENT_MAX_RAILS;
@@ -130,7 +131,7 @@ hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint3
     dim3 grid;
     if (!grid_for((b.n_sc_tiles + 255) / 256, &grid)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(bounded_tiles_kernel, grid, dim3(256), 0, s, b, chunk_bytes / b.tile_bytes);
-    hipLaunchKernelGGL(bounded_bases_kernel, dim3(n_chunks), dim3(64), 0, s, b, arena_bytes);
+    hipLaunchKernelGGL(bounded_bases_kernel, dim3(n_chunks), dim3(64), 0, s, b, slot_bytes);
     return hipGetLastError();
 }
 

@@ -45,6 +45,8 @@ struct tent_ctx {
     uint32_t seg_capacity = 0;
     std::vector<Batch> batches;
     PlanState* host_plan = nullptr;         // pinned read-back buffer
+    hipStream_t aux_stream = nullptr;       // second stream of the pipelined bounded execute (default priority)
+    std::vector<hipEvent_t> sync_events;    // ordering events of the pipelined bounded execute, reused
     Timing timing[TENT_T_COUNT];
 };
 
@@ -241,6 +243,8 @@ int tent_destroy(tent_ctx* ctx)
     for (Batch& b : ctx->batches) if (b.alive) free_batch(b);
     for (Timing& t : ctx->timing)
         for (auto& pr : t.pool) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
+    for (hipEvent_t e : ctx->sync_events) (void)hipEventDestroy(e);
+    if (ctx->aux_stream) (void)hipStreamDestroy(ctx->aux_stream);
     if (ctx->seg_base_dev) (void)hipFree(ctx->seg_base_dev);
     if (ctx->host_plan) (void)hipHostFree(ctx->host_plan);
     delete ctx;
@@ -770,7 +774,7 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     return TENT_OK;
 }
 
-int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes, void* stream)
+int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes, uint32_t slots, void* stream)
 {
     if (!ctx) return TENT_ERR_INVALID;
     Batch* b = find_batch(ctx, batch);
@@ -778,25 +782,69 @@ int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes
     if (!b->planned || !(ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING)) return TENT_ERR_STATE;
     const BatchDev& d = b->dev;
     // chunks are cut on 1 MiB boundaries so that 256 consecutive tiles never straddle two chunks
-    if (chunk_bytes == 0 || (chunk_bytes & ((1ull << 20) - 1)) != 0) return TENT_ERR_INVALID;
+    if (chunk_bytes == 0 || (chunk_bytes & ((1ull << 20) - 1)) != 0 || slots < 1 || slots > 2) return TENT_ERR_INVALID;
     if (d.n_sc_tiles == 0) return TENT_ERR_RANGE;             // geometry: some length is not a multiple of 1 KiB
-    if (chunk_bytes + 256ull * b->last_rails.n_rails > ctx->cfg.staging_bytes) return TENT_ERR_RANGE;
+    const uint64_t slot_bytes = chunk_bytes + 256ull * b->last_rails.n_rails;
+    if (slot_bytes > ctx->cfg.staging_bytes / slots) return TENT_ERR_RANGE;
     const uint64_t n_chunks = (b->payload + chunk_bytes - 1) / chunk_bytes;
     if (n_chunks > kMaxChunks) return TENT_ERR_RANGE;
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* arena = static_cast<uint8_t*>(ctx->cfg.staging_arena);
-    HIP_TRY(launch_bounded_prepare(d, chunk_bytes, (uint32_t)n_chunks, ctx->cfg.staging_bytes, s));
-    for (uint32_t c = 0; c < n_chunks; ++c) {
-        {
-            StageTimer t(ctx, TENT_T_GATHER, s);
-            HIP_TRY(launch_bounded_copy(d, true, c, chunk_bytes, arena, s));
+    HIP_TRY(launch_bounded_prepare(d, chunk_bytes, (uint32_t)n_chunks, slot_bytes, s));
+    if (slots == 1) {
+        for (uint32_t c = 0; c < n_chunks; ++c) {
+            {
+                StageTimer t(ctx, TENT_T_GATHER, s);
+                HIP_TRY(launch_bounded_copy(d, true, c, chunk_bytes, arena, s));
+            }
+            {
+                StageTimer t(ctx, TENT_T_SCATTER, s);
+                HIP_TRY(launch_bounded_copy(d, false, c, chunk_bytes, arena, s));
+            }
         }
-        {
-            StageTimer t(ctx, TENT_T_SCATTER, s);
-            HIP_TRY(launch_bounded_copy(d, false, c, chunk_bytes, arena, s));
+    } else {
+        // Two slots: gathers stay on the caller's stream, scatters go to a second stream.  Scatter c
+        // waits for gather c; gather c + 2 waits for scatter c, which frees its slot; gather c + 1
+        // overlaps scatter c (Section 4.1: consecutive stages of the staging pipeline overlap).
+        if (!ctx->aux_stream && hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking) != hipSuccess) {
+            (void)hipGetLastError();
+            ctx->aux_stream = nullptr;
+            return TENT_ERR_HIP;
         }
+        try {
+            while (ctx->sync_events.size() < 2 * n_chunks + 1) {
+                hipEvent_t e = nullptr;
+                if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+                    (void)hipGetLastError();
+                    return TENT_ERR_HIP;
+                }
+                ctx->sync_events.push_back(e);
+            }
+        } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
+        hipStream_t x = ctx->aux_stream;
+        hipEvent_t prepared = ctx->sync_events[2 * n_chunks];
+        HIP_TRY(hipEventRecord(prepared, s));
+        HIP_TRY(hipStreamWaitEvent(x, prepared, 0));
+        for (uint32_t c = 0; c < n_chunks; ++c) {
+            hipEvent_t gathered = ctx->sync_events[2 * c], scattered = ctx->sync_events[2 * c + 1];
+            if (c >= 2) HIP_TRY(hipStreamWaitEvent(s, ctx->sync_events[2 * (c - 2) + 1], 0));
+            {
+                StageTimer t(ctx, TENT_T_GATHER, s);
+                HIP_TRY(launch_bounded_copy(d, true, c, chunk_bytes, arena + (c & 1) * slot_bytes, s));
+            }
+            HIP_TRY(hipEventRecord(gathered, s));
+            HIP_TRY(hipStreamWaitEvent(x, gathered, 0));
+            {
+                StageTimer t(ctx, TENT_T_SCATTER, x);
+                HIP_TRY(launch_bounded_copy(d, false, c, chunk_bytes, arena + (c & 1) * slot_bytes, x));
+            }
+            HIP_TRY(hipEventRecord(scattered, x));
+        }
+        // the caller's stream continues once every scatter has finished
+        HIP_TRY(hipStreamWaitEvent(s, ctx->sync_events[2 * (n_chunks - 1) + 1], 0));
+        if (n_chunks >= 2) HIP_TRY(hipStreamWaitEvent(s, ctx->sync_events[2 * (n_chunks - 2) + 1], 0));
     }
     HIP_TRY(launch_mark_done_bounded(d, s));
     b->has_done = true;

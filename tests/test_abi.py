@@ -122,7 +122,7 @@ def test_argument_errors_need_no_device(T):
     assert L.tent_create(C.byref(ctx), C.byref(cfg)) == T.TENT_ERR_RANGE
     assert L.tent_destroy(None) == T.TENT_ERR_INVALID
     assert L.tent_execute(None, 1, None) == T.TENT_ERR_INVALID
-    assert L.tent_execute_bounded(None, 1, 1 << 20, None) == T.TENT_ERR_INVALID
+    assert L.tent_execute_bounded(None, 1, 1 << 20, 1, None) == T.TENT_ERR_INVALID
     assert L.tent_plan_dispatch(None, 1, None, 0, None, None, None, None) == T.TENT_ERR_INVALID
     assert L.tent_sim_fail(None, 1, None, None, None) == T.TENT_ERR_INVALID
     assert L.tent_get_retries(None, 1, None, 0) == T.TENT_ERR_INVALID

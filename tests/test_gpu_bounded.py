@@ -20,39 +20,44 @@ def H():
     return gpu_harness
 
 
+@pytest.mark.parametrize("slots", [1, 2])
 @pytest.mark.parametrize("name,chunk", [("tiny", 1 * MiB), ("tiny", 3 * MiB), ("kv_migration", 2 * MiB),
                                         ("rl_params", 1 * MiB), ("many_small", 1 * MiB)])
-def test_bounded_execute_bit_exact(H, oracle, name, chunk):
+def test_bounded_execute_bit_exact(H, oracle, name, chunk, slots):
     from paper_2604_00368_amd import binding as T
     w = W.small_variant(name)
     R = w.rails.shape[0]
     assert chunk < w.payload
-    cap = chunk + 256 * R
+    slot = chunk + 256 * R
+    cap = slots * slot
     src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
     s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
     b = oracle.bind(s.len, w.rails)
     dst_want, staging_want = dst0.copy(), np.zeros(cap, dtype=np.uint8)
-    assert oracle.execute_bounded(w, s, b, [src, dst_want], staging_want, chunk) == 0
+    assert oracle.execute_bounded(w, s, b, [src, dst_want], staging_want, chunk, slots=slots, slot_bytes=slot) == 0
     with H.Engine(w, src, dst0, flags=T.TENT_FLAG_BOUNDED_STAGING, arena_bytes=cap) as eng:
         eng.declare()
         st, info = eng.plan()
         assert st == 0
         H.assert_plan_equal(eng.table(), s, b, info)
-        T.tent_execute_bounded(eng.ctx, eng.batch, chunk, eng.stream)
-        torch.cuda.synchronize()
+        T.tent_execute_bounded(eng.ctx, eng.batch, chunk, eng.stream, slots=slots)
+        # no device-wide wait here: the caller's stream alone must see the batch complete
+        eng.stream.synchronize()
         assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
         assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
         assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
         assert np.array_equal(eng.src.cpu().numpy(), src)
 
 
-def test_bounded_execute_over_replanning_epochs(H, oracle):
+@pytest.mark.parametrize("slots", [1, 2])
+def test_bounded_execute_over_replanning_epochs(H, oracle, slots):
     # every epoch only the slices that stayed bound move (a FIFO prefix per rail), through a 1 MiB buffer
     from paper_2604_00368_amd import binding as T
     w = W.replanning(n_req=6, layers=4, ctx_lo=400, ctx_hi=2000, queued_hi=1 << 20)
     R = w.rails.shape[0]
     chunk = 4 * MiB
-    cap = chunk + 256 * R
+    slot = chunk + 256 * R
+    cap = slots * slot
     src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
     s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
     dst_want, staging_want = dst0.copy(), np.zeros(cap, dtype=np.uint8)
@@ -67,13 +72,14 @@ def test_bounded_execute_over_replanning_epochs(H, oracle):
             done = oracle.retire(s, b, ep.rails["queued_bytes"], ep.budget, ids=pending).astype(bool)
             ids = np.ascontiguousarray(pending[done])
             if ids.shape[0]:
-                assert oracle.execute_bounded(w, s, b, [src, dst_want], staging_want, chunk, ids=ids) == 0
+                assert oracle.execute_bounded(w, s, b, [src, dst_want], staging_want, chunk, ids=ids, slots=slots,
+                                              slot_bytes=slot) == 0
             print("bounded epoch", e, "pending", pending.shape[0], "moved", ids.shape[0], flush=True)
             st, info = eng.plan(rails=ep.rails)
             assert st == 0 and info.n_slices == pending.shape[0]
             assert T.tent_sim_advance(eng.ctx, eng.batch, ep.budget, eng.stream) == ids.shape[0]
-            T.tent_execute_bounded(eng.ctx, eng.batch, chunk, eng.stream)
-            torch.cuda.synchronize()
+            T.tent_execute_bounded(eng.ctx, eng.batch, chunk, eng.stream, slots=slots)
+            eng.stream.synchronize()
             assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
             assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
             pending = np.ascontiguousarray(pending[~done])
@@ -107,6 +113,12 @@ def test_bounded_argument_errors(H, oracle):
         with pytest.raises(T.TentError) as ei:
             T.tent_execute_bounded(eng.ctx, h, 3 * MiB, eng.stream)     # chunk does not fit the arena
         assert ei.value.status == T.TENT_ERR_RANGE
+        with pytest.raises(T.TentError) as ei:
+            T.tent_execute_bounded(eng.ctx, h, 2 * MiB, eng.stream, slots=2)   # two slots do not fit either
+        assert ei.value.status == T.TENT_ERR_RANGE
+        with pytest.raises(T.TentError) as ei:
+            T.tent_execute_bounded(eng.ctx, h, MiB, eng.stream, slots=3)
+        assert ei.value.status == T.TENT_ERR_INVALID
         with pytest.raises(T.TentError) as ei:
             T.tent_execute(eng.ctx, h, eng.stream)                      # the unbounded execute needs the whole payload
         assert ei.value.status == T.TENT_ERR_RANGE
