@@ -265,7 +265,7 @@ def main():
         T.tent_register_segment(ctx_b, src.data_ptr(), src.numel())
         T.tent_register_segment(ctx_b, dst.data_ptr(), dst.numel())
         h_b = T.tent_declare(ctx_b, w.src_ptr, w.src_ext, w.dst_ptr, w.dst_ext)
-        for chunk in sorted({max(1, (w.payload // 8) >> 20) << 20, 256 << 20}, reverse=True):
+        for chunk in sorted({max(1, (w.payload // 8) >> 20) << 20, 256 << 20, 128 << 20}, reverse=True):
             for slots in (1, 2):
                 if slots * (chunk + 256 * R) > arena.numel() or chunk >= w.payload:
                     continue

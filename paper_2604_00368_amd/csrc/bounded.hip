@@ -73,33 +73,48 @@ __global__ void __launch_bounds__(64) bounded_bases_kernel(BatchDev b, uint64_t 
     if (threadIdx.x == 63 && inc > slot_bytes) atomicAdd((unsigned long long*)&b.plan->bounded_overflow, 1ull);
 }
 
+// Turn every tile's (rail, staging offset) into its address inside the slot of its chunk (0 = tile not
+// to be moved), so that the copy kernels need no dependent look-ups.
+__global__ void __launch_bounds__(256) bounded_resolve_kernel(BatchDev b, uint64_t chunk_tiles, uint8_t* arena,
+                                                              uint64_t slot_bytes, uint32_t slots)
+{
+    const uint64_t q = ((uint64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
+    if (q >= b.n_sc_tiles) return;
+    const uint64_t c = b.ga_lin[q];
+    uint64_t addr = 0;
+    if (c != kNoTile) {
+        const uint64_t chunk = q / chunk_tiles;
+        const uint64_t row = chunk * TENT_MAX_RAILS + (c >> 56);
+        addr = (uint64_t)arena + (chunk % slots) * slot_bytes + b.ch_base[row] + ((c & kRegMask) - b.ch_lo[row]);
+    }
+    b.ga_lin[q] = addr;
+}
+
 // Copy the tiles [q_begin, q_end) of one chunk between their paged side and the arena.
 template <bool kGather>
 __global__ void __launch_bounds__(256) bounded_copy_kernel(const uint64_t* __restrict__ paged,
-                                                           const uint64_t* __restrict__ code,
-                                                           const uint64_t* __restrict__ base_row,
-                                                           const uint64_t* __restrict__ lo_row,
+                                                           const uint64_t* __restrict__ staged,
                                                            const uint64_t* __restrict__ overflow,
-                                                           uint8_t* arena, uint64_t q_begin, uint64_t q_end,
-                                                           uint32_t tile_shift)
+                                                           uint64_t q_begin, uint64_t q_end, uint32_t tile_shift)
 {
     const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
     const uint64_t at = w * kCopyBlockBytes + (uint64_t)threadIdx.x * 16;
     const uint64_t q = q_begin + (at >> tile_shift);
     if (q >= q_end) return;
-    const uint64_t c = code[q];
-    if (c == kNoTile || *overflow != 0) return;
-    const uint32_t d = (uint32_t)(c >> 56);
+    const uint64_t near_tile = staged[q];
+    const uint64_t far_tile = paged[q];
+    if (near_tile == 0 || *overflow != 0) return;
     const uint64_t in_tile = at & ((1ull << tile_shift) - 1);
-    const uint64_t far = paged[q] + in_tile;
-    const uint64_t near = (uint64_t)arena + base_row[d] + ((c & kRegMask) - lo_row[d]) + in_tile;
+    const uint64_t far = far_tile + in_tile, near = near_tile + in_tile;
     typedef uint32_t vec4u __attribute__((ext_vector_type(4)));
     typedef vec4u vec4u_any __attribute__((aligned(1)));
+    // the paged side is streamed (nontemporal); the arena side uses ordinary accesses so that a slot
+    // small enough for the memory-side cache can be served from it when the chunk is scattered
     if (kGather) {
         const vec4u v = __builtin_nontemporal_load((const vec4u_any*)far);
-        __builtin_nontemporal_store(v, (vec4u_any*)near);
+        *(vec4u_any*)near = v;
     } else {
-        const vec4u v = __builtin_nontemporal_load((const vec4u_any*)near);
+        const vec4u v = *(const vec4u_any*)near;
         __builtin_nontemporal_store(v, (vec4u_any*)far);
     }
 }
@@ -124,7 +139,7 @@ bool grid_for(uint64_t blocks, dim3* grid)
 }  // namespace
 
 hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint32_t n_chunks, uint64_t slot_bytes,
-                                  hipStream_t s)
+                                  uint32_t slots, uint8_t* arena, hipStream_t s)
 {
     const uint32_t cells = n_chunks * TENT_MAX_RAILS;
     hipLaunchKernelGGL(bounded_clear_kernel, dim3((cells + 255) / 256), dim3(256), 0, s, b, n_chunks);
@@ -132,11 +147,12 @@ hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint3
     if (!grid_for((b.n_sc_tiles + 255) / 256, &grid)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(bounded_tiles_kernel, grid, dim3(256), 0, s, b, chunk_bytes / b.tile_bytes);
     hipLaunchKernelGGL(bounded_bases_kernel, dim3(n_chunks), dim3(64), 0, s, b, slot_bytes);
+    hipLaunchKernelGGL(bounded_resolve_kernel, grid, dim3(256), 0, s, b, chunk_bytes / b.tile_bytes, arena, slot_bytes,
+                       slots);
     return hipGetLastError();
 }
 
-hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t chunk_bytes, uint8_t* arena,
-                               hipStream_t s)
+hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t chunk_bytes, hipStream_t s)
 {
     uint32_t tile_shift = 0;
     while ((1u << tile_shift) < b.tile_bytes) ++tile_shift;
@@ -147,14 +163,12 @@ hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, u
     const uint64_t bytes = (q_end - q_begin) << tile_shift;
     dim3 grid;
     if (!grid_for((bytes + kCopyBlockBytes - 1) / kCopyBlockBytes, &grid)) return hipErrorInvalidValue;
-    const uint64_t* base_row = b.ch_base + (uint64_t)chunk * TENT_MAX_RAILS;
-    const uint64_t* lo_row = b.ch_lo + (uint64_t)chunk * TENT_MAX_RAILS;
     if (gather)
-        hipLaunchKernelGGL(bounded_copy_kernel<true>, grid, dim3(256), 0, s, b.ga_src, b.ga_lin, base_row, lo_row,
-                           &b.plan->bounded_overflow, arena, q_begin, q_end, tile_shift);
+        hipLaunchKernelGGL(bounded_copy_kernel<true>, grid, dim3(256), 0, s, b.ga_src, b.ga_lin,
+                           &b.plan->bounded_overflow, q_begin, q_end, tile_shift);
     else
-        hipLaunchKernelGGL(bounded_copy_kernel<false>, grid, dim3(256), 0, s, b.ga_dst, b.ga_lin, base_row, lo_row,
-                           &b.plan->bounded_overflow, arena, q_begin, q_end, tile_shift);
+        hipLaunchKernelGGL(bounded_copy_kernel<false>, grid, dim3(256), 0, s, b.ga_dst, b.ga_lin,
+                           &b.plan->bounded_overflow, q_begin, q_end, tile_shift);
     return hipGetLastError();
 }
 

@@ -792,16 +792,16 @@ int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* arena = static_cast<uint8_t*>(ctx->cfg.staging_arena);
-    HIP_TRY(launch_bounded_prepare(d, chunk_bytes, (uint32_t)n_chunks, slot_bytes, s));
+    HIP_TRY(launch_bounded_prepare(d, chunk_bytes, (uint32_t)n_chunks, slot_bytes, slots, arena, s));
     if (slots == 1) {
         for (uint32_t c = 0; c < n_chunks; ++c) {
             {
                 StageTimer t(ctx, TENT_T_GATHER, s);
-                HIP_TRY(launch_bounded_copy(d, true, c, chunk_bytes, arena, s));
+                HIP_TRY(launch_bounded_copy(d, true, c, chunk_bytes, s));
             }
             {
                 StageTimer t(ctx, TENT_T_SCATTER, s);
-                HIP_TRY(launch_bounded_copy(d, false, c, chunk_bytes, arena, s));
+                HIP_TRY(launch_bounded_copy(d, false, c, chunk_bytes, s));
             }
         }
     } else {
@@ -832,13 +832,13 @@ int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes
             if (c >= 2) HIP_TRY(hipStreamWaitEvent(s, ctx->sync_events[2 * (c - 2) + 1], 0));
             {
                 StageTimer t(ctx, TENT_T_GATHER, s);
-                HIP_TRY(launch_bounded_copy(d, true, c, chunk_bytes, arena + (c & 1) * slot_bytes, s));
+                HIP_TRY(launch_bounded_copy(d, true, c, chunk_bytes, s));
             }
             HIP_TRY(hipEventRecord(gathered, s));
             HIP_TRY(hipStreamWaitEvent(x, gathered, 0));
             {
                 StageTimer t(ctx, TENT_T_SCATTER, x);
-                HIP_TRY(launch_bounded_copy(d, false, c, chunk_bytes, arena + (c & 1) * slot_bytes, x));
+                HIP_TRY(launch_bounded_copy(d, false, c, chunk_bytes, x));
             }
             HIP_TRY(hipEventRecord(scattered, x));
         }

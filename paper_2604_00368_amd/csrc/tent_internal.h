@@ -186,9 +186,8 @@ hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, h
 hipError_t launch_rotate(const BatchDev& b, const RotateParams& rot, hipStream_t s);
 hipError_t launch_fail(const BatchDev& b, const FailParams& fp, hipStream_t s);
 hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint32_t n_chunks, uint64_t slot_bytes,
-                                  hipStream_t s);
-hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t chunk_bytes, uint8_t* arena,
-                               hipStream_t s);
+                                  uint32_t slots, uint8_t* arena, hipStream_t s);
+hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t chunk_bytes, hipStream_t s);
 hipError_t launch_mark_done_bounded(const BatchDev& b, hipStream_t s);
 hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, hipStream_t s);
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
