@@ -286,6 +286,43 @@ def main():
                                 "execute_ms": round(best, 4), "GBps": round(4 * w.payload / (best * 1e-3) / 1e9, 2)})
         T.tent_destroy(ctx_b)
 
+    # One whole cycle (reset, plan, execute) recorded into a HIP graph and replayed, outside the timed region:
+    # what is left of the step when the host's launch work is taken out.
+    graph_ms = None
+    ctx_g = T.tent_create(w.slice_bytes, arena.data_ptr(), arena.numel(), 0)        # no event timers inside a capture
+    T.tent_register_segment(ctx_g, src.data_ptr(), src.numel())
+    T.tent_register_segment(ctx_g, dst.data_ptr(), dst.numel())
+    h_g = T.tent_declare(ctx_g, w.src_ptr, w.src_ext, w.dst_ptr, w.dst_ext)
+    T.tent_plan(ctx_g, h_g, w.rails, want_info=False, stream=stream)
+    T.tent_execute(ctx_g, h_g, stream)
+    torch.cuda.synchronize(dev)
+    try:
+        side = torch.cuda.Stream(dev)
+        side.wait_stream(stream)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                cap = torch.cuda.current_stream(dev)
+                T.tent_reset(ctx_g, h_g, cap)
+                T.tent_plan(ctx_g, h_g, w.rails, want_info=False, stream=cap)
+                T.tent_execute(ctx_g, h_g, cap)
+        torch.cuda.synchronize(dev)
+        graph.replay()
+        torch.cuda.synchronize(dev)
+        n_rep = 5
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(n_rep):
+            graph.replay()
+        g1.record()
+        torch.cuda.synchronize(dev)
+        graph_ms = g0.elapsed_time(g1) / n_rep
+        assert T.tent_poll(ctx_g, h_g, stream) == 0
+        del graph
+    except RuntimeError:
+        graph_ms = None
+    T.tent_destroy(ctx_g)
+
     # Plain copy of known size (1 GiB read + 1 GiB written by one elementwise kernel), outside the
     # timed region: the practical copy ceiling of the box and the reference dispatch that scales
     # hardware byte counters when this script runs under a counter-collecting profiler.
@@ -336,6 +373,7 @@ def main():
         "dispatch": {"theta_slices": 4, "mice": int(dinfo.n_mice), "elephants": int(dinfo.n_elephant),
                      "plan_ms": round(min(disp_ms), 4), "slices_per_s": round(n_slices / (min(disp_ms) * 1e-3), 1)},
         "bounded_staging": bounded,
+        "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 4),
         "plain_copy_GBps": round(plain_copy_GBps, 2),
         "roofline": {"bound": "hbm", "kernel": "ordered_copy_kernel<%s>" % ("true" if dom == "gather" else "false"), "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),

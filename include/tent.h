@@ -19,6 +19,13 @@
  *     must be used by one host thread at a time.
  *   - `stream` arguments are hipStream_t values passed as void* (NULL = the
  *     default stream).  Calls that take a stream only enqueue work unless stated.
+ *   - HIP graphs: tent_reset, tent_plan with info = NULL and tent_execute allocate nothing, copy
+ *     nothing from or to the host and enqueue kernels only (no memset nodes), so a caller may
+ *     record them on a capturing stream and replay the graph.  The host-side bookkeeping of a
+ *     batch (planned / moved) changes when the call is made, i.e. at capture time, so a recorded
+ *     sequence should be a whole cycle: tent_reset, tent_plan, tent_execute.  Calls that read
+ *     results back (info != NULL, tent_poll, tent_get_*, tent_sim_advance, tent_update_bandwidth)
+ *     or take host arrays per call (tent_plan_dispatch with priorities) are not for capture.
  */
 #ifndef TENT_H
 #define TENT_H
