@@ -202,6 +202,46 @@ def main():
         T.tent_reset(ctx, h, stream)                   # back to PENDING: the next pass re-plans from scratch
     torch.cuda.synchronize(dev)
     elapsed_piped, tm_piped = timed_pass(step_pipelined)
+    # Third pass, reported beside the headline only: plans alternate between two plan streams, so the (mostly
+    # one-wavefront) binding chains of two later steps run side by side under the copies of an earlier one.
+    for h in batches:
+        T.tent_reset(ctx, h, stream)
+    torch.cuda.synchronize(dev)
+    plan_streams = [plan_stream, torch.cuda.Stream(dev)]
+    turn = [0]
+
+    def step_two_plan_streams(h):
+        ps = plan_streams[turn[0] & 1]
+        turn[0] += 1
+        T.tent_plan(ctx, h, w.rails, want_info=False, stream=ps)
+        ev = torch.cuda.Event()
+        ev.record(ps)
+        stream.wait_event(ev)
+        T.tent_execute(ctx, h, stream)
+
+    elapsed_deep, _ = timed_pass(step_two_plan_streams)
+    # Planning throughput when independent batches are planned side by side (each chain is one wavefront, so
+    # the chains of different batches run on different compute units): every batch on its own stream.
+    for h in batches:
+        T.tent_reset(ctx, h, stream)
+    torch.cuda.synchronize(dev)
+    many = [torch.cuda.Stream(dev) for _ in range(min(8, len(batches)))]
+    for k, h in enumerate(batches[:len(many)]):          # warm-up
+        T.tent_plan(ctx, h, w.rails, want_info=False, stream=many[k])
+    torch.cuda.synchronize(dev)
+    for h in batches:
+        T.tent_reset(ctx, h, stream)
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    for k, h in enumerate(batches):
+        T.tent_plan(ctx, h, w.rails, want_info=False, stream=many[k % len(many)])
+    torch.cuda.synchronize(dev)
+    concurrent_plan_s = time.perf_counter() - t0
+    T.tent_get_timings(ctx)
+    for h in batches:
+        T.tent_reset(ctx, h, stream)
+    torch.cuda.synchronize(dev)
+
     if args.single_stream:
         elapsed, tm = elapsed_single, tm_single
     else:
@@ -360,8 +400,11 @@ def main():
                               "two: plan of step k+1 overlaps execute of step k; every step plans and executes its own batch"},
         "ms_per_step_single_stream": round(elapsed_single * 1e3 / args.steps, 4),
         "ms_per_step_two_streams": round(elapsed_piped * 1e3 / args.steps, 4),
+        "ms_per_step_two_plan_streams": round(elapsed_deep * 1e3 / args.steps, 4),
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "slices_planned_per_s": round(n_slices / (plan_ms * 1e-3), 1) if plan_ms > 0 else None,
+        "slices_planned_per_s_concurrent": {"streams": len(many), "batches": len(batches),
+                                            "value": round(n_slices * len(batches) / concurrent_plan_s, 1)},
         "stage_ms": {k: round(v[0] / max(1, args.steps), 4) for k, v in tm.items()},
         "stage_ms_single_stream": {k: round(v[0] / max(1, args.steps), 4) for k, v in tm_single.items()},
         "execute_GBps": round(4 * w.payload / ((gather_avg + scatter_avg) * 1e-3) / 1e9, 2),
