@@ -53,6 +53,7 @@ struct tent_ctx {
 namespace {
 
 constexpr uint32_t kMaxSegments = 4096;
+constexpr size_t kMaxTimedIntervals = 1u << 16;   // per stage, between two tent_get_timings calls
 
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) return TENT_ERR_HIP; } while (0)
 
@@ -146,6 +147,7 @@ struct StageTimer {
     {
         if (!(c->cfg.flags & TENT_FLAG_PROFILE)) return;
         Timing& t = c->timing[stage];
+        if (t.used >= kMaxTimedIntervals) return;          // nobody reads the timings: stop collecting
         if (t.used == t.pool.size()) {
             hipEvent_t a = nullptr, b = nullptr;
             if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
@@ -259,6 +261,7 @@ int tent_register_segment(tent_ctx* ctx, void* dev_base, uint64_t len, uint32_t*
     if (!g.ok) return TENT_ERR_HIP;
     const uint32_t id = (uint32_t)ctx->segments.size();
     const uint64_t addr = (uint64_t)dev_base;
+    try { ctx->segments.reserve(ctx->segments.size() + 1); } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
     HIP_TRY(hipMemcpy(ctx->seg_base_dev + id, &addr, sizeof(addr), hipMemcpyHostToDevice));
     ctx->segments.push_back({static_cast<uint8_t*>(dev_base), len});
     *seg_out = id;
