@@ -33,7 +33,7 @@ HBM_PEAK_GBPS = 8000.0
 # split.hip changes they are reported as null.
 PMC_TRAFFIC = {
     "copy_sources_sha256": "f8c1b7167c4631110664103de29987d72fe682492916a0476eb06a003c3321c5",
-    "kv_migration": {"gather": 43019337927, "scatter": 43019354439},
+    "kv_migration": {"gather": 43019338055, "scatter": 43019355847},
 }
 
 
@@ -59,6 +59,9 @@ def parse():
                     choices=["tiny", "kv_migration", "rl_params", "many_small", "many_small_x6", "kv_skewed"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial-binding", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="run only the headline pass (and the plain-copy calibration): no second timed pass and "
+                         "none of the untimed legs; used for the profiler summaries under profiles/")
     ap.add_argument("--single-stream", action="store_true",
                     help="report the single-stream step time as the headline (default: plan of step k+1 "
                          "overlaps execute of step k on a second stream)")
@@ -197,171 +200,182 @@ def main():
         assert T.tent_poll(ctx, batches[-1], stream) == 0
         return dt, tm_
 
-    elapsed_single, tm_single = timed_pass(step_single)
-    for h in batches:
-        T.tent_reset(ctx, h, stream)                   # back to PENDING: the next pass re-plans from scratch
-    torch.cuda.synchronize(dev)
-    elapsed_piped, tm_piped = timed_pass(step_pipelined)
-    # Third pass, reported beside the headline only: plans alternate between two plan streams, so the (mostly
-    # one-wavefront) binding chains of two later steps run side by side under the copies of an earlier one.
-    for h in batches:
-        T.tent_reset(ctx, h, stream)
-    torch.cuda.synchronize(dev)
-    plan_streams = [plan_stream, torch.cuda.Stream(dev)]
-    turn = [0]
-
-    def step_two_plan_streams(h):
-        ps = plan_streams[turn[0] & 1]
-        turn[0] += 1
-        T.tent_plan(ctx, h, w.rails, want_info=False, stream=ps)
-        ev = torch.cuda.Event()
-        ev.record(ps)
-        stream.wait_event(ev)
-        T.tent_execute(ctx, h, stream)
-
-    elapsed_deep, _ = timed_pass(step_two_plan_streams)
-    # Planning throughput when independent batches are planned side by side (each chain is one wavefront, so
-    # the chains of different batches run on different compute units): every batch on its own stream.
-    for h in batches:
-        T.tent_reset(ctx, h, stream)
-    torch.cuda.synchronize(dev)
-    many = [torch.cuda.Stream(dev) for _ in range(min(8, len(batches)))]
-    for k, h in enumerate(batches[:len(many)]):          # warm-up
-        T.tent_plan(ctx, h, w.rails, want_info=False, stream=many[k])
-    torch.cuda.synchronize(dev)
-    for h in batches:
-        T.tent_reset(ctx, h, stream)
-    torch.cuda.synchronize(dev)
-    t0 = time.perf_counter()
-    for k, h in enumerate(batches):
-        T.tent_plan(ctx, h, w.rails, want_info=False, stream=many[k % len(many)])
-    torch.cuda.synchronize(dev)
-    concurrent_plan_s = time.perf_counter() - t0
-    T.tent_get_timings(ctx)
-    for h in batches:
-        T.tent_reset(ctx, h, stream)
-    torch.cuda.synchronize(dev)
-
-    if args.single_stream:
-        elapsed, tm = elapsed_single, tm_single
+    lean = args.headline_only
+    if lean:
+        elapsed, tm = timed_pass(step_single if args.single_stream else step_pipelined)
+        elapsed_single, tm_single = elapsed, tm
+        elapsed_piped, tm_piped = elapsed, tm
+        elapsed_deep = concurrent_plan_s = None
+        many = []
     else:
-        elapsed, tm = elapsed_piped, tm_piped
+        elapsed_single, tm_single = timed_pass(step_single)
+        for h in batches:
+            T.tent_reset(ctx, h, stream)               # back to PENDING: the next pass re-plans from scratch
+        torch.cuda.synchronize(dev)
+        elapsed_piped, tm_piped = timed_pass(step_pipelined)
+        # Third pass, reported beside the headline only: plans alternate between two plan streams, so the (mostly
+        # one-wavefront) binding chains of two later steps run side by side under the copies of an earlier one.
+        for h in batches:
+            T.tent_reset(ctx, h, stream)
+        torch.cuda.synchronize(dev)
+        plan_streams = [plan_stream, torch.cuda.Stream(dev)]
+        turn = [0]
 
-    # Telemetry feedback (Eq. 2 probe + smoothed update) over one full window, outside the timed region:
-    # every slice of one batch BOUND, latencies from the rail simulator at the nominal bandwidths.
-    h_fb = batches[-1]
-    T.tent_reset(ctx, h_fb, stream)
-    T.tent_plan(ctx, h_fb, w.rails, want_info=False, stream=stream)
-    T.tent_sim_latency(ctx, h_fb, w.rails["bw_MBps"], stream)
-    torch.cuda.synchronize(dev)
-    T.tent_get_timings(ctx)
-    fb_params = W.make_probe_params(2 * w.rails["bw_MBps"].astype(np.uint64))
-    for _ in range(5):
-        T.tent_update_bandwidth(ctx, h_fb, fb_params, w.rails, stream)
-    fb_ms, fb_n = T.tent_get_timings(ctx)["feedback"]
+        def step_two_plan_streams(h):
+            ps = plan_streams[turn[0] & 1]
+            turn[0] += 1
+            T.tent_plan(ctx, h, w.rails, want_info=False, stream=ps)
+            ev = torch.cuda.Event()
+            ev.record(ps)
+            stream.wait_event(ev)
+            T.tent_execute(ctx, h, stream)
 
-    # Recovery after a hard error (Section 4.3), outside the timed region: the fastest rail fails with the
-    # whole batch bound, its slices come back with a retry count, and the next plan (compaction into
-    # retried and fresh slices, rotation pass, cost-model pass) is timed.
+        elapsed_deep, _ = timed_pass(step_two_plan_streams)
+        # Planning throughput when independent batches are planned side by side (each chain is one wavefront, so
+        # the chains of different batches run on different compute units): every batch on its own stream.
+        for h in batches:
+            T.tent_reset(ctx, h, stream)
+        torch.cuda.synchronize(dev)
+        many = [torch.cuda.Stream(dev) for _ in range(min(8, len(batches)))]
+        for k, h in enumerate(batches[:len(many)]):      # warm-up
+            T.tent_plan(ctx, h, w.rails, want_info=False, stream=many[k])
+        torch.cuda.synchronize(dev)
+        for h in batches:
+            T.tent_reset(ctx, h, stream)
+        torch.cuda.synchronize(dev)
+        t0 = time.perf_counter()
+        for k, h in enumerate(batches):
+            T.tent_plan(ctx, h, w.rails, want_info=False, stream=many[k % len(many)])
+        torch.cuda.synchronize(dev)
+        concurrent_plan_s = time.perf_counter() - t0
+        T.tent_get_timings(ctx)
+        for h in batches:
+            T.tent_reset(ctx, h, stream)
+        torch.cuda.synchronize(dev)
+        if args.single_stream:
+            elapsed, tm = elapsed_single, tm_single
+        else:
+            elapsed, tm = elapsed_piped, tm_piped
+
+    fb_ms, fb_n, rec_ms, n_retried, fastest = 0.0, 0, [], 0, 0
     R = int(w.rails.shape[0])
-    fastest = int(np.argmax(w.rails["bw_MBps"]))
-    failed_mask = np.zeros(R, dtype=np.uint8)
-    failed_mask[fastest] = 1
-    after = w.rails.copy()
-    after["health"][fastest] = 2
-    rec_ms, n_retried = [], 0
-    if R > 1:
-        for _ in range(3):
-            T.tent_reset(ctx, h_fb, stream)
-            T.tent_plan(ctx, h_fb, w.rails, want_info=False, stream=stream)
-            n_retried = int(T.tent_sim_fail(ctx, h_fb, failed_mask, True, stream)[fastest])
-            torch.cuda.synchronize(dev)
-            T.tent_get_timings(ctx)
-            T.tent_plan(ctx, h_fb, after, want_info=False, stream=stream)
-            torch.cuda.synchronize(dev)
-            tm_rec = T.tent_get_timings(ctx)
-            rec_ms.append(tm_rec["compact"][0] + tm_rec["bind"][0])
-    T.tent_reset(ctx, h_fb, stream)
-
-    # Request-level dispatch (Algorithm 1: mice round robin / weighted spraying of elephants), outside the
-    # timed region: the whole batch, every transfer HIGH priority, theta = 4 slices.
-    disp_ms = []
-    dparams = W.make_dispatch_params(4 * w.slice_bytes)
-    for _ in range(3):
+    disp_ms, dinfo, bounded, graph_ms = [], None, [], None
+    if not lean:
+        # Telemetry feedback (Eq. 2 probe + smoothed update) over one full window, outside the timed region:
+        # every slice of one batch BOUND, latencies from the rail simulator at the nominal bandwidths.
+        h_fb = batches[-1]
         T.tent_reset(ctx, h_fb, stream)
+        T.tent_plan(ctx, h_fb, w.rails, want_info=False, stream=stream)
+        T.tent_sim_latency(ctx, h_fb, w.rails["bw_MBps"], stream)
         torch.cuda.synchronize(dev)
         T.tent_get_timings(ctx)
-        st_d, dinfo = T.tent_plan_dispatch(ctx, h_fb, w.rails, dparams, None, True, stream)
-        tm_d = T.tent_get_timings(ctx)
-        disp_ms.append(sum(tm_d[k][0] for k in ("extent_scan", "slice_scan", "expand", "bind")))
-    T.tent_reset(ctx, h_fb, stream)
+        fb_params = W.make_probe_params(2 * w.rails["bw_MBps"].astype(np.uint64))
+        for _ in range(5):
+            T.tent_update_bandwidth(ctx, h_fb, fb_params, w.rails, stream)
+        fb_ms, fb_n = T.tent_get_timings(ctx)["feedback"]
 
-    # Bounded, pipelined staging (Section 4.1), outside the timed region: the same batch through an arena of
-    # one eighth of the payload (rounded to MiB) and through a 256 MiB arena, chunk after chunk.
-    bounded = []
-    if w.payload >= (64 << 20):
-        ctx_b = T.tent_create(w.slice_bytes, arena.data_ptr(), arena.numel(),
-                              T.TENT_FLAG_PROFILE | T.TENT_FLAG_BOUNDED_STAGING)
-        T.tent_register_segment(ctx_b, src.data_ptr(), src.numel())
-        T.tent_register_segment(ctx_b, dst.data_ptr(), dst.numel())
-        h_b = T.tent_declare(ctx_b, w.src_ptr, w.src_ext, w.dst_ptr, w.dst_ext)
-        for chunk in sorted({max(1, (w.payload // 8) >> 20) << 20, 256 << 20, 128 << 20}, reverse=True):
-            for slots in (1, 2):
-                if slots * (chunk + 256 * R) > arena.numel() or chunk >= w.payload:
-                    continue
-                best = None
-                for _ in range(3):
-                    T.tent_reset(ctx_b, h_b, stream)
-                    T.tent_plan(ctx_b, h_b, w.rails, want_info=False, stream=stream)
-                    torch.cuda.synchronize(dev)
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    T.tent_execute_bounded(ctx_b, h_b, chunk, stream, slots=slots)
-                    e1.record()
-                    torch.cuda.synchronize(dev)
-                    ms = e0.elapsed_time(e1)
-                    best = ms if best is None else min(best, ms)
-                assert T.tent_poll(ctx_b, h_b, stream) == 0
-                bounded.append({"slot_MiB": chunk >> 20, "slots": slots, "chunks": -(-w.payload // chunk),
-                                "execute_ms": round(best, 4), "GBps": round(4 * w.payload / (best * 1e-3) / 1e9, 2)})
-        T.tent_destroy(ctx_b)
+        # Recovery after a hard error (Section 4.3), outside the timed region: the fastest rail fails with the
+        # whole batch bound, its slices come back with a retry count, and the next plan (compaction into
+        # retried and fresh slices, rotation pass, cost-model pass) is timed.
+        R = int(w.rails.shape[0])
+        fastest = int(np.argmax(w.rails["bw_MBps"]))
+        failed_mask = np.zeros(R, dtype=np.uint8)
+        failed_mask[fastest] = 1
+        after = w.rails.copy()
+        after["health"][fastest] = 2
+        rec_ms, n_retried = [], 0
+        if R > 1:
+            for _ in range(3):
+                T.tent_reset(ctx, h_fb, stream)
+                T.tent_plan(ctx, h_fb, w.rails, want_info=False, stream=stream)
+                n_retried = int(T.tent_sim_fail(ctx, h_fb, failed_mask, True, stream)[fastest])
+                torch.cuda.synchronize(dev)
+                T.tent_get_timings(ctx)
+                T.tent_plan(ctx, h_fb, after, want_info=False, stream=stream)
+                torch.cuda.synchronize(dev)
+                tm_rec = T.tent_get_timings(ctx)
+                rec_ms.append(tm_rec["compact"][0] + tm_rec["bind"][0])
+        T.tent_reset(ctx, h_fb, stream)
 
-    # One whole cycle (reset, plan, execute) recorded into a HIP graph and replayed, outside the timed region:
-    # what is left of the step when the host's launch work is taken out.
-    graph_ms = None
-    ctx_g = T.tent_create(w.slice_bytes, arena.data_ptr(), arena.numel(), 0)        # no event timers inside a capture
-    T.tent_register_segment(ctx_g, src.data_ptr(), src.numel())
-    T.tent_register_segment(ctx_g, dst.data_ptr(), dst.numel())
-    h_g = T.tent_declare(ctx_g, w.src_ptr, w.src_ext, w.dst_ptr, w.dst_ext)
-    T.tent_plan(ctx_g, h_g, w.rails, want_info=False, stream=stream)
-    T.tent_execute(ctx_g, h_g, stream)
-    torch.cuda.synchronize(dev)
-    try:
-        side = torch.cuda.Stream(dev)
-        side.wait_stream(stream)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                cap = torch.cuda.current_stream(dev)
-                T.tent_reset(ctx_g, h_g, cap)
-                T.tent_plan(ctx_g, h_g, w.rails, want_info=False, stream=cap)
-                T.tent_execute(ctx_g, h_g, cap)
-        torch.cuda.synchronize(dev)
-        graph.replay()
-        torch.cuda.synchronize(dev)
-        n_rep = 5
-        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        g0.record()
-        for _ in range(n_rep):
-            graph.replay()
-        g1.record()
-        torch.cuda.synchronize(dev)
-        graph_ms = g0.elapsed_time(g1) / n_rep
-        assert T.tent_poll(ctx_g, h_g, stream) == 0
-        del graph
-    except RuntimeError:
+        # Request-level dispatch (Algorithm 1: mice round robin / weighted spraying of elephants), outside the
+        # timed region: the whole batch, every transfer HIGH priority, theta = 4 slices.
+        disp_ms = []
+        dparams = W.make_dispatch_params(4 * w.slice_bytes)
+        for _ in range(3):
+            T.tent_reset(ctx, h_fb, stream)
+            torch.cuda.synchronize(dev)
+            T.tent_get_timings(ctx)
+            st_d, dinfo = T.tent_plan_dispatch(ctx, h_fb, w.rails, dparams, None, True, stream)
+            tm_d = T.tent_get_timings(ctx)
+            disp_ms.append(sum(tm_d[k][0] for k in ("extent_scan", "slice_scan", "expand", "bind")))
+        T.tent_reset(ctx, h_fb, stream)
+
+        # Bounded, pipelined staging (Section 4.1), outside the timed region: the same batch through an arena of
+        # one eighth of the payload (rounded to MiB) and through a 256 MiB arena, chunk after chunk.
+        bounded = []
+        if w.payload >= (64 << 20):
+            ctx_b = T.tent_create(w.slice_bytes, arena.data_ptr(), arena.numel(),
+                                  T.TENT_FLAG_PROFILE | T.TENT_FLAG_BOUNDED_STAGING)
+            T.tent_register_segment(ctx_b, src.data_ptr(), src.numel())
+            T.tent_register_segment(ctx_b, dst.data_ptr(), dst.numel())
+            h_b = T.tent_declare(ctx_b, w.src_ptr, w.src_ext, w.dst_ptr, w.dst_ext)
+            for chunk in sorted({max(1, (w.payload // 8) >> 20) << 20, 256 << 20, 128 << 20}, reverse=True):
+                for slots in (1, 2):
+                    if slots * (chunk + 256 * R) > arena.numel() or chunk >= w.payload:
+                        continue
+                    best = None
+                    for _ in range(3):
+                        T.tent_reset(ctx_b, h_b, stream)
+                        T.tent_plan(ctx_b, h_b, w.rails, want_info=False, stream=stream)
+                        torch.cuda.synchronize(dev)
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        T.tent_execute_bounded(ctx_b, h_b, chunk, stream, slots=slots)
+                        e1.record()
+                        torch.cuda.synchronize(dev)
+                        ms = e0.elapsed_time(e1)
+                        best = ms if best is None else min(best, ms)
+                    assert T.tent_poll(ctx_b, h_b, stream) == 0
+                    bounded.append({"slot_MiB": chunk >> 20, "slots": slots, "chunks": -(-w.payload // chunk),
+                                    "execute_ms": round(best, 4), "GBps": round(4 * w.payload / (best * 1e-3) / 1e9, 2)})
+            T.tent_destroy(ctx_b)
+
+        # One whole cycle (reset, plan, execute) recorded into a HIP graph and replayed, outside the timed region:
+        # what is left of the step when the host's launch work is taken out.
         graph_ms = None
-    T.tent_destroy(ctx_g)
+        ctx_g = T.tent_create(w.slice_bytes, arena.data_ptr(), arena.numel(), 0)        # no event timers inside a capture
+        T.tent_register_segment(ctx_g, src.data_ptr(), src.numel())
+        T.tent_register_segment(ctx_g, dst.data_ptr(), dst.numel())
+        h_g = T.tent_declare(ctx_g, w.src_ptr, w.src_ext, w.dst_ptr, w.dst_ext)
+        T.tent_plan(ctx_g, h_g, w.rails, want_info=False, stream=stream)
+        T.tent_execute(ctx_g, h_g, stream)
+        torch.cuda.synchronize(dev)
+        try:
+            side = torch.cuda.Stream(dev)
+            side.wait_stream(stream)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    cap = torch.cuda.current_stream(dev)
+                    T.tent_reset(ctx_g, h_g, cap)
+                    T.tent_plan(ctx_g, h_g, w.rails, want_info=False, stream=cap)
+                    T.tent_execute(ctx_g, h_g, cap)
+            torch.cuda.synchronize(dev)
+            graph.replay()
+            torch.cuda.synchronize(dev)
+            n_rep = 5
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record()
+            for _ in range(n_rep):
+                graph.replay()
+            g1.record()
+            torch.cuda.synchronize(dev)
+            graph_ms = g0.elapsed_time(g1) / n_rep
+            assert T.tent_poll(ctx_g, h_g, stream) == 0
+            del graph
+        except RuntimeError:
+            graph_ms = None
+        T.tent_destroy(ctx_g)
 
     # Plain copy of known size (1 GiB read + 1 GiB written by one elementwise kernel), outside the
     # timed region: the practical copy ceiling of the box and the reference dispatch that scales
@@ -400,10 +414,11 @@ def main():
                               "two: plan of step k+1 overlaps execute of step k; every step plans and executes its own batch"},
         "ms_per_step_single_stream": round(elapsed_single * 1e3 / args.steps, 4),
         "ms_per_step_two_streams": round(elapsed_piped * 1e3 / args.steps, 4),
-        "ms_per_step_two_plan_streams": round(elapsed_deep * 1e3 / args.steps, 4),
+        "ms_per_step_two_plan_streams": None if elapsed_deep is None else round(elapsed_deep * 1e3 / args.steps, 4),
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "slices_planned_per_s": round(n_slices / (plan_ms * 1e-3), 1) if plan_ms > 0 else None,
-        "slices_planned_per_s_concurrent": {"streams": len(many), "batches": len(batches),
+        "slices_planned_per_s_concurrent": None if concurrent_plan_s is None else
+                                           {"streams": len(many), "batches": len(batches),
                                             "value": round(n_slices * len(batches) / concurrent_plan_s, 1)},
         "stage_ms": {k: round(v[0] / max(1, args.steps), 4) for k, v in tm.items()},
         "stage_ms_single_stream": {k: round(v[0] / max(1, args.steps), 4) for k, v in tm_single.items()},
@@ -413,7 +428,8 @@ def main():
                      "bytes_per_slice": 17},
         "recovery": {"failed_rail": fastest, "retried_slices": n_retried, "replanned_slices": n_slices,
                      "replan_ms": round(min(rec_ms), 4) if rec_ms else None},
-        "dispatch": {"theta_slices": 4, "mice": int(dinfo.n_mice), "elephants": int(dinfo.n_elephant),
+        "dispatch": None if dinfo is None else
+                    {"theta_slices": 4, "mice": int(dinfo.n_mice), "elephants": int(dinfo.n_elephant),
                      "plan_ms": round(min(disp_ms), 4), "slices_per_s": round(n_slices / (min(disp_ms) * 1e-3), 1)},
         "bounded_staging": bounded,
         "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 4),
