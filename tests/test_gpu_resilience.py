@@ -172,3 +172,71 @@ def test_fail_argument_errors(H, oracle):
         s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
         st, info = eng.plan()
         H.assert_plan_equal(eng.table(), s, oracle.bind(s.len, w.rails), info)
+
+
+@pytest.mark.parametrize("kind", range(6))
+def test_randomized_rotation_and_dispatch_plans(H, oracle, kind):
+    # plan-only, degenerate telemetry (ties, sub-picosecond cost steps, huge latencies and queues, 1-byte slices):
+    # request-level dispatch over three windows, then rounds of failures re-planned by rotation + cost model
+    from paper_2604_00368_amd import binding as T
+    from test_gpu_parity import _runs_workload
+    rng = np.random.Generator(np.random.PCG64(5000 + kind))
+    for trial in range(15):
+        w = _runs_workload(rng, kind)
+        R = w.rails.shape[0]
+        s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+        print("random plans kind", kind, "trial", trial, "S", w.slice_bytes, "D", w.n_desc, "N", s.n, "R", R, flush=True)
+        zeros = (np.zeros(w.seg_bytes[0], np.uint8), np.zeros(w.seg_bytes[1], np.uint8))
+        with H.Engine(w, *zeros) as eng:
+            eng.declare()
+            prio = W.make_priorities(int(rng.integers(0, 1 << 30)), w.n_desc)
+            done = np.zeros(s.n, dtype=np.uint8)
+            rr = int(rng.integers(0, 7))
+            theta = int(rng.choice([1, w.slice_bytes, 3 * w.slice_bytes + 1, 50 * w.slice_bytes]))
+            gamma = int(rng.choice([0, 3, 26, 256, 5000]))
+            w0 = int(rng.integers(0, 9))
+            for window in range(w0, w0 + 3):
+                dp = W.make_dispatch_params(theta, gamma_q8=gamma, window=window, rr_start=rr)
+                st, info = T.tent_plan_dispatch(eng.ctx, eng.batch, w.rails, dp, prio, True, eng.stream)
+                r = oracle.dispatch(s, w.rails, dp, priority=prio, done=done)
+                tab = eng.table()
+                ids = np.flatnonzero(r.bound)
+                assert np.array_equal(np.flatnonzero(tab["state"] == 1), ids)
+                assert np.array_equal(tab["rail"][ids], r.binding.rail[ids])
+                assert np.array_equal(tab["stage_off"][ids], r.binding.stage_off[ids])
+                assert list(info.plan.rail_bytes)[:R] == r.binding.T.tolist()
+                assert np.array_equal(T.tent_get_modes(eng.ctx, eng.batch, w.n_desc), r.mode)
+                assert info.rr_next == r.rr_end
+                rr = r.rr_end
+                eng.execute()
+                done[ids] = 1
+        with H.Engine(w, *zeros) as eng:
+            eng.declare()
+            eng.plan()
+            b = oracle.bind(s.len, w.rails)
+            retry = np.zeros(s.n, dtype=np.uint8)
+            pending = np.arange(s.n, dtype=np.uint32)
+            rails = w.rails.copy()
+            for rnd in range(3):
+                fl = (rng.random(R) < 0.4).astype(np.uint8)
+                failed, per = oracle.fail(b, fl, retry, ids=pending)
+                assert np.array_equal(T.tent_sim_fail(eng.ctx, eng.batch, fl, True, eng.stream), per)
+                eng.execute()                                  # the survivors complete
+                pending = np.ascontiguousarray(pending[failed.astype(bool)])
+                if pending.shape[0] == 0:
+                    break
+                u = rng.random(R)
+                rails["health"] = np.where(u < 0.25, 2, np.where(u < 0.5, 1, 0)).astype(np.uint8)
+                if (rails["health"] == 2).all():
+                    rails["health"][int(rng.integers(0, R))] = int(rng.integers(0, 2))
+                if kind == 3:
+                    rails["penalty_q8"] = np.minimum(rails["penalty_q8"], 500)
+                b = oracle.plan(s.len, retry, rails, ids=pending)
+                st, info = eng.plan(rails=rails)
+                tab = eng.table()
+                assert st == b.status == 0
+                assert np.array_equal(np.flatnonzero(tab["state"] != 2), pending)
+                assert np.array_equal(tab["rail"][pending], b.rail[pending])
+                assert np.array_equal(tab["stage_off"][pending], b.stage_off[pending])
+                assert list(info.rail_bytes)[:R] == b.T.tolist()
+                assert np.array_equal(T.tent_get_retries(eng.ctx, eng.batch), retry)
