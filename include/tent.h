@@ -37,7 +37,7 @@ extern "C" {
 #endif
 
 typedef struct tent_ctx tent_ctx;     /* opaque engine instance                                   */
-typedef uint64_t tent_batch_t;        /* opaque batch handle (Section 3, "opaque batch handle")   */
+typedef uint64_t tent_batch_t;        /* what the application holds for a batch (Section 3)      */
 
 typedef enum {
     TENT_OK          =  0,

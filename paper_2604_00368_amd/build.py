@@ -10,7 +10,7 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(CSRC, "libtent.so")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fgpu-rdc=0" if False else "-fno-gpu-rdc",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
     # keep packed-fp32 instruction selection off for device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
