@@ -230,3 +230,47 @@ def test_full_size_bounded_staging(H, oracle):
         del eng
         gc.collect()
         torch.cuda.empty_cache()
+
+
+def test_maximum_slice_and_extent_sizes(H, oracle):
+    # the largest slice size the library accepts (2^31 bytes) and extents close to the 32-bit length limit:
+    # one transfer of 3 GiB + 12 KiB (two slices: 2 GiB and the rest) next to a 4 KiB one; plan and every byte
+    print("maximum sizes", flush=True)
+    GiB = 1 << 30
+    S = 1 << 31
+    big = 3 * GiB + 12288
+    ptr_s = np.array([0, 2, 3], dtype=np.uint32)
+    ptr_d = np.array([0, 3, 4], dtype=np.uint32)
+    se = W._extents(W.SRC_SEG, [4096, 8192 + big - 1 * GiB - 8192, 0], [big - 1 * GiB - 8192, 1 * GiB + 8192, 4096])
+    # destination: three extents (4 GiB - 4 KiB would not fit a u32 length, so 1.5 GiB + 1.5 GiB + 12 KiB), then 4 KiB
+    de = W._extents(W.DST_SEG, [8192, 8192 + 3 * GiB // 2, 8192 + 3 * GiB, 0], [3 * GiB // 2, 3 * GiB // 2, 12288, 4096])
+    pool = 8192 + big + 4096
+    rails = W.make_rails([50000, 400000, 25000])
+    w = W.Workload("max_sizes", 0, S, [pool, pool], ptr_s, se, ptr_d, de, rails, "u8")
+    assert w.payload == big + 4096
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    src_t = torch.randint(0, 256, (pool,), dtype=torch.uint8, device="cuda", generator=g)
+    src = src_t.cpu().numpy()
+    dst0 = np.zeros(pool, dtype=np.uint8)
+    s = oracle.split(w.src_ptr, w.src_ext, S)
+    assert s.n == 3 and s.len.tolist() == [S, big - S, 4096]
+    b = oracle.bind(s.len, w.rails)
+    dst_want = dst0.copy()
+    staging_want = np.zeros(w.staging_bytes, dtype=np.uint8)
+    oracle.execute(w, s, b, [src, dst_want], staging_want)
+    eng = H.Engine(w, src, dst0)
+    try:
+        del src_t
+        eng.declare()
+        st, info = eng.plan()
+        assert st == 0
+        H.assert_plan_equal(eng.table(), s, b, info)
+        eng.execute()
+        assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+        assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+    finally:
+        eng.close()
+        del eng
+        gc.collect()
+        torch.cuda.empty_cache()
