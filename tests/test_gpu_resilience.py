@@ -240,3 +240,35 @@ def test_randomized_rotation_and_dispatch_plans(H, oracle, kind):
                 assert np.array_equal(tab["stage_off"][pending], b.stage_off[pending])
                 assert list(info.rail_bytes)[:R] == b.T.tolist()
                 assert np.array_equal(T.tent_get_retries(eng.ctx, eng.batch), retry)
+
+
+@pytest.mark.parametrize("R", [1, 17, 33, 64])
+def test_rotation_with_many_rails(H, oracle, R):
+    # every reduction width of the binders (16 / 32 / 64 lanes) behind a rotation pass; rail R-1 stays healthy
+    from paper_2604_00368_amd import binding as T
+    rng = np.random.Generator(np.random.PCG64(40 + R))
+    w = W.small_variant("many_small")
+    w.rails = W.make_rails(rng.integers(5000, 100000, R), queued=rng.integers(0, 1 << 20, R))
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    zeros = (np.zeros(w.seg_bytes[0], np.uint8), np.zeros(w.seg_bytes[1], np.uint8))
+    with H.Engine(w, *zeros) as eng:
+        eng.declare()
+        st, _ = eng.plan()
+        b = oracle.bind(s.len, w.rails)
+        retry = np.zeros(s.n, dtype=np.uint8)
+        fl = (rng.random(R) < 0.5).astype(np.uint8)
+        fl[0] = 1
+        failed, per = oracle.fail(b, fl, retry)
+        assert np.array_equal(T.tent_sim_fail(eng.ctx, eng.batch, fl, True, eng.stream), per)
+        rails = w.rails.copy()
+        rails["health"] = np.where(fl == 1, rng.choice([1, 2], R), 0).astype(np.uint8)
+        rails["health"][R - 1] = 0 if R > 1 else 1
+        pending = np.arange(s.n, dtype=np.uint32)               # nothing was executed: everything is re-planned
+        b2 = oracle.plan(s.len, retry, rails, ids=pending)
+        st, info = eng.plan(rails=rails)
+        assert st == b2.status == 0 and info.n_slices == s.n
+        tab = eng.table()
+        assert np.array_equal(tab["rail"], b2.rail) and np.array_equal(tab["stage_off"], b2.stage_off)
+        assert list(info.rail_bytes)[:R] == b2.T.tolist() and list(info.stage_base)[:R] == b2.base.tolist()
+        assert list(info.rail_slices)[:R] == b2.n_slices.tolist()
+        assert int((retry > 0).sum()) == int(per.sum()) > 0
