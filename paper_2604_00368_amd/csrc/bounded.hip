@@ -99,7 +99,11 @@ __global__ void __launch_bounds__(256) bounded_copy_kernel(const uint64_t* __res
 {
     const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
     const uint64_t at = w * kCopyBlockBytes + (uint64_t)threadIdx.x * 16;
-    const uint64_t q = q_begin + (at >> tile_shift);
+    // a wavefront's 1 KiB lies inside one tile (tiles are 1 KiB or more): the tile index is uniform per
+    // wavefront, which lets the two table entries come from scalar loads
+    const uint64_t q_lane = q_begin + (at >> tile_shift);
+    const uint64_t q = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(q_lane >> 32)) << 32) |
+                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)q_lane);
     if (q >= q_end) return;
     const uint64_t near_tile = staged[q];
     const uint64_t far_tile = paged[q];
@@ -107,7 +111,7 @@ __global__ void __launch_bounds__(256) bounded_copy_kernel(const uint64_t* __res
     const uint64_t in_tile = at & ((1ull << tile_shift) - 1);
     const uint64_t far = far_tile + in_tile, near = near_tile + in_tile;
     typedef uint32_t vec4u __attribute__((ext_vector_type(4)));
-    typedef vec4u vec4u_any __attribute__((aligned(1)));
+    typedef __attribute__((address_space(1))) vec4u vec4u_any __attribute__((aligned(1)));   // device memory, any alignment
     // the paged side is streamed (nontemporal); the arena side uses ordinary accesses so that a slot
     // small enough for the memory-side cache can be served from it when the chunk is scattered
     if (kGather) {

@@ -23,6 +23,9 @@ typedef uint32_t vec4u __attribute__((ext_vector_type(4)));
 // 16-byte vector at any address: gfx950 global loads and stores need no alignment, and the compiler
 // emits a single dwordx4 access for this type.
 typedef vec4u vec4u_any __attribute__((aligned(1)));
+// The same vector behind a pointer that is known to be device memory: addresses taken from tables are
+// plain integers, and without the address space the compiler must emit generic (flat) accesses.
+typedef __attribute__((address_space(1))) vec4u_any vec4u_dev;
 
 // Wavefront-cooperative byte copy (64 lanes).
 __device__ __forceinline__ void copy_bytes(uint8_t* __restrict__ dst, const uint8_t* __restrict__ src, uint64_t n)
@@ -154,21 +157,37 @@ static hipError_t launch_copy_lanes(const BatchDev& b, hipStream_t s)
 // rail regions, writes are sequential) -- HBM tolerates scattered reads better than scattered
 // writes.  Only used when no tile crosses an extent boundary.  kGather only names the direction
 // (the two launches show up separately in a kernel trace); the code is the same.
-template <bool kGather>
+template <bool kGather, bool kWholeTile>
 __global__ void __launch_bounds__(256) ordered_copy_kernel(const uint64_t* __restrict__ from,
                                                            const uint64_t* __restrict__ to,
                                                            uint64_t n_tiles, uint32_t tile_shift)
 {
     const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    if (kWholeTile) {
+        // 4 KiB tiles: the workgroup's block is one tile, its two table entries are the same for every
+        // lane and are fetched by scalar loads
+        if (w >= n_tiles) return;
+        const uint64_t src = from[w];
+        const uint64_t dst = to[w];
+        if (src == 0 || dst == 0) return;
+        const uint64_t in_tile = (uint64_t)threadIdx.x * 16;
+        vec4u v = __builtin_nontemporal_load((const vec4u_dev*)(src + in_tile));
+        __builtin_nontemporal_store(v, (vec4u_dev*)(dst + in_tile));
+        return;
+    }
+    // smaller tiles (1 or 2 KiB): a wavefront's 1 KiB still lies inside one tile, so the tile index is
+    // uniform per wavefront and the table entries are again fetched by scalar loads
     const uint64_t at = w * kCopyBlockBytes + (uint64_t)threadIdx.x * 16;     // byte in enumeration order
-    const uint64_t q = at >> tile_shift;
+    const uint64_t q_lane = at >> tile_shift;
+    const uint64_t q = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(q_lane >> 32)) << 32) |
+                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)q_lane);
     if (q >= n_tiles) return;
     const uint64_t src = from[q];
     const uint64_t dst = to[q];
     if (src == 0 || dst == 0) return;
     const uint64_t in_tile = at & ((1ull << tile_shift) - 1);
-    vec4u v = __builtin_nontemporal_load((const vec4u_any*)(src + in_tile));
-    __builtin_nontemporal_store(v, (vec4u_any*)(dst + in_tile));
+    vec4u v = __builtin_nontemporal_load((const vec4u_dev*)(src + in_tile));
+    __builtin_nontemporal_store(v, (vec4u_dev*)(dst + in_tile));
 }
 
 hipError_t launch_copy_ordered(const BatchDev& b, bool gather, hipStream_t s)
@@ -181,12 +200,16 @@ hipError_t launch_copy_ordered(const BatchDev& b, bool gather, hipStream_t s)
     const uint32_t gx = blocks < 65536 ? (uint32_t)blocks : 65536u;
     const uint64_t gy = (blocks + gx - 1) / gx;
     if (gy > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    if (gather)
-        hipLaunchKernelGGL(ordered_copy_kernel<true>, dim3(gx, (uint32_t)gy), dim3(256), 0, s,
-                           b.ga_src, b.ga_lin, b.n_sc_tiles, tile_shift);
+    const dim3 grid(gx, (uint32_t)gy);
+    const bool whole = b.tile_bytes == kCopyBlockBytes;
+    if (gather && whole)
+        hipLaunchKernelGGL((ordered_copy_kernel<true, true>), grid, dim3(256), 0, s, b.ga_src, b.ga_lin, b.n_sc_tiles, tile_shift);
+    else if (gather)
+        hipLaunchKernelGGL((ordered_copy_kernel<true, false>), grid, dim3(256), 0, s, b.ga_src, b.ga_lin, b.n_sc_tiles, tile_shift);
+    else if (whole)
+        hipLaunchKernelGGL((ordered_copy_kernel<false, true>), grid, dim3(256), 0, s, b.sc_lin, b.sc_dst, b.n_sc_tiles, tile_shift);
     else
-        hipLaunchKernelGGL(ordered_copy_kernel<false>, dim3(gx, (uint32_t)gy), dim3(256), 0, s,
-                           b.sc_lin, b.sc_dst, b.n_sc_tiles, tile_shift);
+        hipLaunchKernelGGL((ordered_copy_kernel<false, false>), grid, dim3(256), 0, s, b.sc_lin, b.sc_dst, b.n_sc_tiles, tile_shift);
     return hipGetLastError();
 }
 
