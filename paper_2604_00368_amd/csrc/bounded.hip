@@ -92,13 +92,13 @@ __global__ void __launch_bounds__(256) bounded_resolve_kernel(BatchDev b, uint64
 
 // Copy the tiles [q_begin, q_end) of one chunk between their paged side and the arena.
 template <bool kGather>
-__global__ void __launch_bounds__(256) bounded_copy_kernel(const uint64_t* __restrict__ paged,
+__global__ void __launch_bounds__(kOrderedLanes) bounded_copy_kernel(const uint64_t* __restrict__ paged,
                                                            const uint64_t* __restrict__ staged,
                                                            const uint64_t* __restrict__ overflow,
                                                            uint64_t q_begin, uint64_t q_end, uint32_t tile_shift)
 {
     const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
-    const uint64_t at = w * kCopyBlockBytes + (uint64_t)threadIdx.x * 16;
+    const uint64_t at = w * (kOrderedLanes * 16) + (uint64_t)threadIdx.x * 16;
     // a wavefront's 1 KiB lies inside one tile (tiles are 1 KiB or more): the tile index is uniform per
     // wavefront, which lets the two table entries come from scalar loads
     const uint64_t q_lane = q_begin + (at >> tile_shift);
@@ -166,12 +166,12 @@ hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, u
     const uint64_t q_end = q_begin + chunk_tiles < b.n_sc_tiles ? q_begin + chunk_tiles : b.n_sc_tiles;
     const uint64_t bytes = (q_end - q_begin) << tile_shift;
     dim3 grid;
-    if (!grid_for((bytes + kCopyBlockBytes - 1) / kCopyBlockBytes, &grid)) return hipErrorInvalidValue;
+    if (!grid_for((bytes + kOrderedLanes * 16 - 1) / (kOrderedLanes * 16), &grid)) return hipErrorInvalidValue;
     if (gather)
-        hipLaunchKernelGGL(bounded_copy_kernel<true>, grid, dim3(256), 0, s, b.ga_src, b.ga_lin,
+        hipLaunchKernelGGL(bounded_copy_kernel<true>, grid, dim3(kOrderedLanes), 0, s, b.ga_src, b.ga_lin,
                            &b.plan->bounded_overflow, q_begin, q_end, tile_shift);
     else
-        hipLaunchKernelGGL(bounded_copy_kernel<false>, grid, dim3(256), 0, s, b.ga_dst, b.ga_lin,
+        hipLaunchKernelGGL(bounded_copy_kernel<false>, grid, dim3(kOrderedLanes), 0, s, b.ga_dst, b.ga_lin,
                            &b.plan->bounded_overflow, q_begin, q_end, tile_shift);
     return hipGetLastError();
 }

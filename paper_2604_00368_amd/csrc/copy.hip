@@ -150,34 +150,22 @@ static hipError_t launch_copy_lanes(const BatchDev& b, hipStream_t s)
     return hipGetLastError();
 }
 
-// Table-driven copy: workgroup w moves the 4 KiB block w of an enumeration of the payload in tiles;
+// Table-driven copy: workgroup w moves block w (kOrderedLanes x 16 bytes) of an enumeration of the payload in tiles;
 // `from` and `to` hold the two addresses of every tile (0 = tile not to be moved).  Gather walks the
 // source bytes in declaration order (reads hop between pages, every rail region is written front to
 // back); scatter walks the destination bytes in ascending device address (reads hop between the
 // rail regions, writes are sequential) -- HBM tolerates scattered reads better than scattered
 // writes.  Only used when no tile crosses an extent boundary.  kGather only names the direction
 // (the two launches show up separately in a kernel trace); the code is the same.
-template <bool kGather, bool kWholeTile>
-__global__ void __launch_bounds__(256) ordered_copy_kernel(const uint64_t* __restrict__ from,
-                                                           const uint64_t* __restrict__ to,
-                                                           uint64_t n_tiles, uint32_t tile_shift)
+template <bool kGather>
+__global__ void __launch_bounds__(kOrderedLanes) ordered_copy_kernel(const uint64_t* __restrict__ from,
+                                                                     const uint64_t* __restrict__ to,
+                                                                     uint64_t n_tiles, uint32_t tile_shift)
 {
     const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
-    if (kWholeTile) {
-        // 4 KiB tiles: the workgroup's block is one tile, its two table entries are the same for every
-        // lane and are fetched by scalar loads
-        if (w >= n_tiles) return;
-        const uint64_t src = from[w];
-        const uint64_t dst = to[w];
-        if (src == 0 || dst == 0) return;
-        const uint64_t in_tile = (uint64_t)threadIdx.x * 16;
-        vec4u v = __builtin_nontemporal_load((const vec4u_dev*)(src + in_tile));
-        __builtin_nontemporal_store(v, (vec4u_dev*)(dst + in_tile));
-        return;
-    }
-    // smaller tiles (1 or 2 KiB): a wavefront's 1 KiB still lies inside one tile, so the tile index is
-    // uniform per wavefront and the table entries are again fetched by scalar loads
-    const uint64_t at = w * kCopyBlockBytes + (uint64_t)threadIdx.x * 16;     // byte in enumeration order
+    const uint64_t at = w * (kOrderedLanes * 16) + (uint64_t)threadIdx.x * 16;   // byte in enumeration order
+    // a wavefront's 1 KiB lies inside one tile (tiles are 1 KiB or more), so the tile index is uniform
+    // per wavefront and the two table entries are fetched by scalar loads
     const uint64_t q_lane = at >> tile_shift;
     const uint64_t q = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(q_lane >> 32)) << 32) |
                        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)q_lane);
@@ -195,21 +183,19 @@ hipError_t launch_copy_ordered(const BatchDev& b, bool gather, hipStream_t s)
     uint32_t tile_shift = 0;
     while ((1u << tile_shift) < b.tile_bytes) ++tile_shift;
     const uint64_t bytes = b.n_sc_tiles * (uint64_t)b.tile_bytes;
-    const uint64_t blocks = (bytes + kCopyBlockBytes - 1) / kCopyBlockBytes;
+    const uint64_t block_bytes = kOrderedLanes * 16;
+    const uint64_t blocks = (bytes + block_bytes - 1) / block_bytes;
     if (blocks == 0) return hipSuccess;
     const uint32_t gx = blocks < 65536 ? (uint32_t)blocks : 65536u;
     const uint64_t gy = (blocks + gx - 1) / gx;
     if (gy > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid(gx, (uint32_t)gy);
-    const bool whole = b.tile_bytes == kCopyBlockBytes;
-    if (gather && whole)
-        hipLaunchKernelGGL((ordered_copy_kernel<true, true>), grid, dim3(256), 0, s, b.ga_src, b.ga_lin, b.n_sc_tiles, tile_shift);
-    else if (gather)
-        hipLaunchKernelGGL((ordered_copy_kernel<true, false>), grid, dim3(256), 0, s, b.ga_src, b.ga_lin, b.n_sc_tiles, tile_shift);
-    else if (whole)
-        hipLaunchKernelGGL((ordered_copy_kernel<false, true>), grid, dim3(256), 0, s, b.sc_lin, b.sc_dst, b.n_sc_tiles, tile_shift);
+    if (gather)
+        hipLaunchKernelGGL(ordered_copy_kernel<true>, grid, dim3(kOrderedLanes), 0, s, b.ga_src, b.ga_lin, b.n_sc_tiles,
+                           tile_shift);
     else
-        hipLaunchKernelGGL((ordered_copy_kernel<false, false>), grid, dim3(256), 0, s, b.sc_lin, b.sc_dst, b.n_sc_tiles, tile_shift);
+        hipLaunchKernelGGL(ordered_copy_kernel<false>, grid, dim3(kOrderedLanes), 0, s, b.sc_lin, b.sc_dst, b.n_sc_tiles,
+                           tile_shift);
     return hipGetLastError();
 }
 

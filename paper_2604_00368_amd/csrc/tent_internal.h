@@ -169,6 +169,8 @@ struct BatchDev {
 
 enum : uint32_t { kScanBlock = 256, kScanItems = 8, kScanTile = kScanBlock * kScanItems };
 enum : uint32_t { kCopyBlockBytes = 4096 };          // bytes one copy workgroup moves (256 lanes x 16 B)
+enum : uint32_t { kOrderedLanes = 256 };             // lanes of a table-driven copy workgroup (4 KiB each): 128 and 256
+                                                     // measure the same on MI355X, 64 / 512 / 1024 are slower
 constexpr uint64_t kTileSlow = 1ull << 63;
 enum : uint32_t { kMaxChunks = 4096 };               // most chunks one bounded execute may use
 enum : uint32_t { kRotChunk = 1024 };                // retried slices one rotation workgroup handles
