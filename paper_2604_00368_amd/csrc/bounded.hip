@@ -99,11 +99,7 @@ __global__ void __launch_bounds__(kOrderedLanes) bounded_copy_kernel(const uint6
 {
     const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
     const uint64_t at = w * (kOrderedLanes * 16) + (uint64_t)threadIdx.x * 16;
-    // a wavefront's 1 KiB lies inside one tile (tiles are 1 KiB or more): the tile index is uniform per
-    // wavefront, which lets the two table entries come from scalar loads
-    const uint64_t q_lane = q_begin + (at >> tile_shift);
-    const uint64_t q = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(q_lane >> 32)) << 32) |
-                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)q_lane);
+    const uint64_t q = q_begin + (at >> tile_shift);
     if (q >= q_end) return;
     const uint64_t near_tile = staged[q];
     const uint64_t far_tile = paged[q];

@@ -164,11 +164,10 @@ __global__ void __launch_bounds__(kOrderedLanes) ordered_copy_kernel(const uint6
 {
     const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
     const uint64_t at = w * (kOrderedLanes * 16) + (uint64_t)threadIdx.x * 16;   // byte in enumeration order
-    // a wavefront's 1 KiB lies inside one tile (tiles are 1 KiB or more), so the tile index is uniform
-    // per wavefront and the two table entries are fetched by scalar loads
-    const uint64_t q_lane = at >> tile_shift;
-    const uint64_t q = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(q_lane >> 32)) << 32) |
-                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)q_lane);
+    // The tile index is the same for all lanes of a wavefront, but the table entries are fetched with
+    // ordinary per-lane loads (one cache line per wavefront): scalar loads measured 1 % faster on the
+    // KV-migration workload and 2-4 % slower on contiguous tensors and on 2 KiB tiles.
+    const uint64_t q = at >> tile_shift;
     if (q >= n_tiles) return;
     const uint64_t src = from[q];
     const uint64_t dst = to[q];
