@@ -298,6 +298,29 @@ def many_small(seed: int = 5, n_req: int = 4096, layers: int = 1, pages_lo: int 
 
 
 # --------------------------------------------------------------------------
+# Slice-size sweep: fixed payload, contiguous or paged layout (shapes of the
+# paper's block-size sweeps, Section 5.2)
+# --------------------------------------------------------------------------
+def sweep(slice_bytes: int, paged: bool, payload: int = 4 << 30, n_desc: int = 64, page_bytes: int = 32 * KiB,
+          seed: int = 6) -> Workload:
+    """n_desc equal transfers; contiguous = one extent each, paged = shuffled pages on both sides."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    per = payload // n_desc
+    rails = make_rails([50000] * 8 + [400000])
+    if not paged:
+        off = (np.arange(n_desc, dtype=np.uint64) * np.uint64(per))
+        ptr = np.arange(n_desc + 1, dtype=np.uint32)
+        order = rng.permutation(n_desc)
+        doff = np.zeros(n_desc, dtype=np.uint64)
+        doff[order] = off
+        return Workload("sweep_contiguous", seed, slice_bytes, [payload, payload], ptr, _extents(SRC_SEG, off, per),
+                        ptr.copy(), _extents(DST_SEG, doff, per), rails, "u8")
+    pages = np.full(n_desc, per // page_bytes, dtype=np.int64)
+    ptr, se, de, pool, _ = _paged_kv(rng, n_desc, pages, 1, page_bytes)
+    return Workload("sweep_paged", seed, slice_bytes, [pool, pool], ptr, se, ptr.copy(), de, rails, "u8")
+
+
+# --------------------------------------------------------------------------
 # Arbitrary-geometry descriptors for property tests (odd lengths, 1-byte
 # extents, independent source and destination block structure)
 # --------------------------------------------------------------------------
