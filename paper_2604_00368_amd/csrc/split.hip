@@ -220,7 +220,34 @@ __global__ void __launch_bounds__(256) finalize_tiles_kernel(BatchDev b)
     }
 }
 
-hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s)
+// When only a small part of the batch moves (re-planning epochs), the copy launches should not pay for
+// every tile of the batch: the tiles that do move are compacted into two index lists, one per
+// enumeration, by one scan that carries both counters (gather list low half, scatter list high half).
+struct ActiveTiles {
+    const uint64_t* ga;
+    const uint64_t* sc;
+    __device__ uint64_t operator()(uint64_t q) const
+    {
+        return (ga[q] != 0 ? 1ull : 0ull) | (sc[q] != 0 ? (1ull << 32) : 0ull);
+    }
+};
+
+__global__ void __launch_bounds__(256) tile_compact_kernel(BatchDev b)
+{
+    const uint64_t n = b.n_sc_tiles;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < n; q += stride) {
+        const uint64_t at = b.tile_scan[q];
+        if (b.ga_lin[q] != 0) b.ga_act[at & 0xFFFFFFFFu] = (uint32_t)q;
+        if (b.sc_lin[q] != 0) b.sc_act[at >> 32] = (uint32_t)q;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        b.plan->n_ga_act = b.tile_scan[n] & 0xFFFFFFFFu;
+        b.plan->n_sc_act = b.tile_scan[n] >> 32;
+    }
+}
+
+hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, bool compact, hipStream_t s)
 {
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
@@ -229,6 +256,11 @@ hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s)
         blocks = (b.n_sc_tiles + 255) / 256;
         if (blocks > 65536) blocks = 65536;
         hipLaunchKernelGGL(finalize_tiles_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+        if (compact) {
+            hipError_t e = exclusive_scan(ActiveTiles{b.ga_lin, b.sc_lin}, b.n_sc_tiles, b.tile_scan, b.tile_partials, s);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(tile_compact_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+        }
     }
     return hipGetLastError();
 }

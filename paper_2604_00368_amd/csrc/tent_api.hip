@@ -19,6 +19,7 @@ struct Batch {
     bool planned = false;        // a plan has been enqueued since declare / reset
     bool has_done = false;       // execute ran since declare / reset: DONE slices may exist
     bool has_retry = false;      // a rail failed since declare / reset: slices with a retry count may exist
+    uint64_t bound_hint = 0;     // upper bound on the number of BOUND slices, as far as the host knows
     uint32_t generation = 0;
     uint64_t payload = 0;
     uint64_t max_req_slices = 0; // most slices any one transfer has
@@ -366,6 +367,10 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
             if (rc == TENT_OK) rc = dev_alloc(b, &d.ch_hi, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
             if (rc == TENT_OK) rc = dev_alloc(b, &d.ch_base, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
         }
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.tile_scan, d.n_sc_tiles + 1);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.tile_partials, scan_partials_capacity(d.n_sc_tiles));
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_act, d.n_sc_tiles);
+        if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_act, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_dst, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_lin, d.n_sc_tiles);
         if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_slice, d.n_sc_tiles);
@@ -483,6 +488,7 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
         else        HIP_TRY(launch_bind_runs(d, rp, mode, s));
     }
     b->planned = true;
+    b->bound_hint = b->dev.n_slices;
     b->last_rails = rp;
     for (uint32_t r = 0; r < n_rails; ++r) b->last_lat_ns[r] = rails[r].lat_ns;
 
@@ -575,6 +581,7 @@ int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state*
         HIP_TRY(launch_dispatch(d, rp, dp, s));
     }
     b->planned = true;
+    b->bound_hint = b->dev.n_slices;
     b->last_rails = rp;
     for (uint32_t r = 0; r < n_rails; ++r) b->last_lat_ns[r] = rails[r].lat_ns;
 
@@ -631,6 +638,7 @@ int tent_sim_advance(tent_ctx* ctx, tent_batch_t batch, const uint64_t* budget_b
     HIP_TRY(launch_retire(b->dev, bp, s));
     HIP_TRY(hipMemcpyAsync(ctx->host_plan, b->dev.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    b->bound_hint = ctx->host_plan->n_done;
     if (n_done) *n_done = ctx->host_plan->n_done;
     return TENT_OK;
 }
@@ -761,19 +769,26 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    HIP_TRY(launch_finalize(b->dev, static_cast<uint8_t*>(ctx->cfg.staging_arena), s));
+    // When the host knows that only a small part of the batch is BOUND (after the rail simulator), the
+    // copies run over compacted tile lists and their launches are sized by that part.
+    const uint64_t max_tiles = b->bound_hint * b->dev.tiles_per_slice;
+    const bool compact = b->dev.n_sc_tiles != 0 && b->dev.n_sc_tiles < (1ull << 32) && max_tiles * 2 <= b->dev.n_sc_tiles;
+    HIP_TRY(launch_finalize(b->dev, static_cast<uint8_t*>(ctx->cfg.staging_arena), compact, s));
     {
         StageTimer t(ctx, TENT_T_GATHER, s);
-        if (b->dev.n_sc_tiles) HIP_TRY(launch_copy_ordered(b->dev, true, s));
-        else                   HIP_TRY(launch_copy(b->dev, true, s));
+        if (compact)                HIP_TRY(launch_copy_compact(b->dev, true, max_tiles, s));
+        else if (b->dev.n_sc_tiles) HIP_TRY(launch_copy_ordered(b->dev, true, s));
+        else                        HIP_TRY(launch_copy(b->dev, true, s));
     }
     {
         StageTimer t(ctx, TENT_T_SCATTER, s);
-        if (b->dev.n_sc_tiles) HIP_TRY(launch_copy_ordered(b->dev, false, s));
-        else                   HIP_TRY(launch_copy(b->dev, false, s));
+        if (compact)                HIP_TRY(launch_copy_compact(b->dev, false, max_tiles, s));
+        else if (b->dev.n_sc_tiles) HIP_TRY(launch_copy_ordered(b->dev, false, s));
+        else                        HIP_TRY(launch_copy(b->dev, false, s));
     }
     HIP_TRY(launch_mark_done(b->dev, s));
     b->has_done = true;
+    b->bound_hint = 0;
     return TENT_OK;
 }
 
@@ -851,6 +866,7 @@ int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes
     }
     HIP_TRY(launch_mark_done_bounded(d, s));
     b->has_done = true;
+    b->bound_hint = 0;
     return TENT_OK;
 }
 

@@ -82,6 +82,7 @@ struct PlanState {
     uint64_t n_mice, n_elephant, n_deferred;   // tent_plan_dispatch: requests per mode
     uint64_t rr_next;                     // round-robin counter after the call
     uint64_t bounded_overflow;            // tent_execute_bounded: chunks whose regions do not fit the arena
+    uint64_t n_ga_act, n_sc_act;          // tent_execute with few BOUND slices: entries of the compacted tile lists
 };
 
 // What a copy workgroup needs to know about its slice, in one 16-byte scalar load.
@@ -145,6 +146,10 @@ struct BatchDev {
     uint64_t* ch_lo;               // [kMaxChunks * TENT_MAX_RAILS] bounded staging: first staging offset per chunk and rail
     uint64_t* ch_hi;               // same shape: end of the interval
     uint64_t* ch_base;             // same shape: region base inside the arena
+    uint64_t* tile_scan;           // [n_sc_tiles+1] scan workspace of the per-execute tile compaction
+    uint64_t* tile_partials;       // its per-block partial sums
+    uint32_t* ga_act;              // [n_sc_tiles] declaration-order tiles that move in this execute, compacted
+    uint32_t* sc_act;              // [n_sc_tiles] destination-order tiles that move in this execute, compacted
     uint64_t* sc_dst;              // [n_sc_tiles] scatter: destination address of the tile
     uint64_t* sc_lin;              // [n_sc_tiles] scatter: staging address, 0 = not to be moved
     uint32_t* sc_slice;
@@ -193,9 +198,10 @@ hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, u
 hipError_t launch_mark_done_bounded(const BatchDev& b, hipStream_t s);
 hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, hipStream_t s);
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
-hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, hipStream_t s);
+hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, bool compact, hipStream_t s);
 hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s);
 hipError_t launch_copy_ordered(const BatchDev& b, bool gather, hipStream_t s);
+hipError_t launch_copy_compact(const BatchDev& b, bool gather, uint64_t max_tiles, hipStream_t s);
 hipError_t launch_mark_done(const BatchDev& b, hipStream_t s);
 hipError_t launch_retire(const BatchDev& b, const BudgetParams& bp, hipStream_t s);
 hipError_t launch_count_remaining(const BatchDev& b, hipStream_t s);
