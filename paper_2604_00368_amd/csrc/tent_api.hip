@@ -497,6 +497,7 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
         HIP_TRY(hipStreamSynchronize(s));
         const PlanState& ps = *ctx->host_plan;
         std::memset(info, 0, sizeof(*info));
+        b->bound_hint = ps.n_bound;
         info->n_slices = ps.n_bound;
         info->n_pending_before = ps.n_pending;
         for (uint32_t r = 0; r < TENT_MAX_RAILS; ++r) {
@@ -590,6 +591,7 @@ int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state*
         HIP_TRY(hipStreamSynchronize(s));
         const PlanState& ps = *ctx->host_plan;
         std::memset(info, 0, sizeof(*info));
+        b->bound_hint = ps.n_bound;
         info->plan.n_slices = ps.n_bound;
         info->plan.n_pending_before = ps.n_pending;
         for (uint32_t r = 0; r < n_rails; ++r) {
