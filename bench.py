@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0
 # to one version of the copy kernels and of the kernels that build their tables: when copy.hip or
 # split.hip changes they are reported as null.
 PMC_TRAFFIC = {
-    "copy_sources_sha256": "59c1fa202cdc7b469459303ed87ee8e9dbd129cdacf81aa550c3e9cd00fcb2c4",
-    "kv_migration": {"gather": 43019338055, "scatter": 43019354183},
+    "copy_sources_sha256": "8c7bb7360a6933c37003852bbad41141a7aaf4cc9ef0e41487c101ffc54a41b5",
+    "kv_migration": {"gather": 43019350087, "scatter": 43019346503},
 }
 
 
