@@ -232,7 +232,7 @@ struct ActiveTiles {
     }
 };
 
-__global__ void __launch_bounds__(256) tile_compact_kernel(BatchDev b)
+__global__ void __launch_bounds__(256) tile_compact_kernel(BatchDev b, uint64_t max_tiles)
 {
     const uint64_t n = b.n_sc_tiles;
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
@@ -242,12 +242,16 @@ __global__ void __launch_bounds__(256) tile_compact_kernel(BatchDev b)
         if (b.sc_lin[q] != 0) b.sc_act[at >> 32] = (uint32_t)q;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        b.plan->n_ga_act = b.tile_scan[n] & 0xFFFFFFFFu;
-        b.plan->n_sc_act = b.tile_scan[n] >> 32;
+        const uint64_t n_ga = b.tile_scan[n] & 0xFFFFFFFFu, n_sc = b.tile_scan[n] >> 32;
+        b.plan->n_ga_act = n_ga;
+        b.plan->n_sc_act = n_sc;
+        // the copy launches are sized by the host's bound on the BOUND slices; should more tiles move than
+        // that, the copies would be incomplete, so nothing may be marked DONE
+        b.plan->compact_overflow = (n_ga > max_tiles || n_sc > max_tiles) ? 1 : 0;
     }
 }
 
-hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, bool compact, hipStream_t s)
+hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, bool compact, uint64_t max_tiles, hipStream_t s)
 {
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
@@ -259,7 +263,7 @@ hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, bool compact, hipS
         if (compact) {
             hipError_t e = exclusive_scan(ActiveTiles{b.ga_lin, b.sc_lin}, b.n_sc_tiles, b.tile_scan, b.tile_partials, s);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(tile_compact_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+            hipLaunchKernelGGL(tile_compact_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, max_tiles);
         }
     }
     return hipGetLastError();
@@ -305,18 +309,19 @@ hipError_t launch_compact(const BatchDev& b, hipStream_t s)
 }
 
 // ---- slice state bookkeeping ------------------------------------------------------------------
-__global__ void __launch_bounds__(256) mark_done_kernel(BatchDev b)
+__global__ void __launch_bounds__(256) mark_done_kernel(BatchDev b, int compact)
 {
+    if (compact && b.plan->compact_overflow != 0) return;       // incomplete copies: the slices stay BOUND
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < b.n_slices; i += stride)
         if (b.s_state[i] == TENT_SLICE_BOUND) b.s_state[i] = TENT_SLICE_DONE;
 }
 
-hipError_t launch_mark_done(const BatchDev& b, hipStream_t s)
+hipError_t launch_mark_done(const BatchDev& b, bool compact, hipStream_t s)
 {
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(mark_done_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    hipLaunchKernelGGL(mark_done_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, compact ? 1 : 0);
     return hipGetLastError();
 }
 

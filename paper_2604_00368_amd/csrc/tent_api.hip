@@ -775,7 +775,7 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     // copies run over compacted tile lists and their launches are sized by that part.
     const uint64_t max_tiles = b->bound_hint * b->dev.tiles_per_slice;
     const bool compact = b->dev.n_sc_tiles != 0 && b->dev.n_sc_tiles < (1ull << 32) && max_tiles * 2 <= b->dev.n_sc_tiles;
-    HIP_TRY(launch_finalize(b->dev, static_cast<uint8_t*>(ctx->cfg.staging_arena), compact, s));
+    HIP_TRY(launch_finalize(b->dev, static_cast<uint8_t*>(ctx->cfg.staging_arena), compact, max_tiles, s));
     {
         StageTimer t(ctx, TENT_T_GATHER, s);
         if (compact)                HIP_TRY(launch_copy_compact(b->dev, true, max_tiles, s));
@@ -788,7 +788,7 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
         else if (b->dev.n_sc_tiles) HIP_TRY(launch_copy_ordered(b->dev, false, s));
         else                        HIP_TRY(launch_copy(b->dev, false, s));
     }
-    HIP_TRY(launch_mark_done(b->dev, s));
+    HIP_TRY(launch_mark_done(b->dev, compact, s));
     b->has_done = true;
     b->bound_hint = 0;
     return TENT_OK;

@@ -83,6 +83,7 @@ struct PlanState {
     uint64_t rr_next;                     // round-robin counter after the call
     uint64_t bounded_overflow;            // tent_execute_bounded: chunks whose regions do not fit the arena
     uint64_t n_ga_act, n_sc_act;          // tent_execute with few BOUND slices: entries of the compacted tile lists
+    uint64_t compact_overflow;            // nonzero: more tiles move than the launch was sized for (nothing is marked DONE)
 };
 
 // What a copy workgroup needs to know about its slice, in one 16-byte scalar load.
@@ -198,11 +199,11 @@ hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, u
 hipError_t launch_mark_done_bounded(const BatchDev& b, hipStream_t s);
 hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, hipStream_t s);
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
-hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, bool compact, hipStream_t s);
+hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, bool compact, uint64_t max_tiles, hipStream_t s);
 hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s);
 hipError_t launch_copy_ordered(const BatchDev& b, bool gather, hipStream_t s);
 hipError_t launch_copy_compact(const BatchDev& b, bool gather, uint64_t max_tiles, hipStream_t s);
-hipError_t launch_mark_done(const BatchDev& b, hipStream_t s);
+hipError_t launch_mark_done(const BatchDev& b, bool compact, hipStream_t s);
 hipError_t launch_retire(const BatchDev& b, const BudgetParams& bp, hipStream_t s);
 hipError_t launch_count_remaining(const BatchDev& b, hipStream_t s);
 hipError_t launch_reset(const BatchDev& b, hipStream_t s);
