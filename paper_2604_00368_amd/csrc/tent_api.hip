@@ -79,18 +79,35 @@ Batch* find_batch(tent_ctx* ctx, tent_batch_t h)
     return (b->alive && b->generation == gen) ? b : nullptr;
 }
 
-template <class T>
-int dev_alloc(Batch& b, T** out, uint64_t count)
-{
-    void* p = nullptr;
-    if (hipMalloc(&p, std::max<uint64_t>(count, 1) * sizeof(T)) != hipSuccess) {
-        (void)hipGetLastError();
-        return TENT_ERR_NOMEM;
+// Every per-batch table is carved from ONE device allocation: a declaration asks for about fifty
+// arrays, and fifty allocator calls cost more than everything else a declaration does.  The requests
+// are collected first, then one hipMalloc serves them at 256-byte aligned offsets.
+struct Carver {
+    struct Want { void** slot; uint64_t bytes; };
+    std::vector<Want> wants;
+    template <class T>
+    void want(T** out, uint64_t count)
+    {
+        wants.push_back({reinterpret_cast<void**>(out), std::max<uint64_t>(count, 1) * sizeof(T)});
     }
-    b.allocs.push_back(p);
-    *out = static_cast<T*>(p);
-    return TENT_OK;
-}
+    int commit(Batch& b)
+    {
+        uint64_t total = 0;
+        for (const Want& w : wants) total += (w.bytes + 255) & ~255ull;
+        void* base = nullptr;
+        if (hipMalloc(&base, total) != hipSuccess) {
+            (void)hipGetLastError();
+            return TENT_ERR_NOMEM;
+        }
+        b.allocs.push_back(base);
+        uint64_t at = 0;
+        for (const Want& w : wants) {
+            *w.slot = static_cast<char*>(base) + at;
+            at += (w.bytes + 255) & ~255ull;
+        }
+        return TENT_OK;
+    }
+};
 
 void free_batch(Batch& b)
 {
@@ -322,68 +339,74 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     uint32_t *sp = nullptr, *dp = nullptr;
     tent_extent *se = nullptr, *de = nullptr;
     const uint64_t scan_n = std::max<uint64_t>(std::max(ns, nd), std::max<uint64_t>(n_slices, n_desc));
-    rc = dev_alloc(b, &sp, (uint64_t)n_desc + 1);
-    if (rc == TENT_OK) rc = dev_alloc(b, &dp, (uint64_t)n_desc + 1);
-    if (rc == TENT_OK) rc = dev_alloc(b, &se, ns);
-    if (rc == TENT_OK) rc = dev_alloc(b, &de, nd);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.src_pre, ns + 1);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.dst_pre, nd + 1);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.first, (uint64_t)n_desc + 1);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_desc, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_off, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_len, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_src_e0, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_dst_e0, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_rail, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_stage_off, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_state, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_tau, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_rec, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.s_retry, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.priority, (uint64_t)n_desc);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.req_mode, (uint64_t)n_desc);
     BatchDev* self_dev = nullptr;
-    if (rc == TENT_OK) rc = dev_alloc(b, &self_dev, 1);
-    if (d.n_sc_tiles == 0) {                              // per-slice tile tables only for untiled geometry
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.src_tile, n_tiles);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.dst_tile, n_tiles);
-    }
-    d.run_capacity = 2u * n_desc;
-    d.run_stride = ctx->max_rails;
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.run_start, (uint64_t)d.run_capacity + 1);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.run_T, (uint64_t)d.run_capacity * d.run_stride);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.run_K, (uint64_t)d.run_capacity * d.run_stride);
     uint32_t* order_dev = nullptr;
-    if (rc == TENT_OK) rc = dev_alloc(b, &order_dev, nd);
-    if (d.n_sc_tiles) {
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.ord_pre, nd + 1);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_src, d.n_sc_tiles);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_lin, d.n_sc_tiles);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_slice, d.n_sc_tiles);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_x, d.n_sc_tiles);
-        if (ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING) {
-            if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_dst, d.n_sc_tiles);
-            if (rc == TENT_OK) rc = dev_alloc(b, &d.ch_lo, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
-            if (rc == TENT_OK) rc = dev_alloc(b, &d.ch_hi, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
-            if (rc == TENT_OK) rc = dev_alloc(b, &d.ch_base, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
+    Carver cv;
+    try {
+        cv.want(&sp, (uint64_t)n_desc + 1);
+        cv.want(&dp, (uint64_t)n_desc + 1);
+        cv.want(&se, ns);
+        cv.want(&de, nd);
+        cv.want(&d.src_pre, ns + 1);
+        cv.want(&d.dst_pre, nd + 1);
+        cv.want(&d.first, (uint64_t)n_desc + 1);
+        cv.want(&d.s_desc, n_slices);
+        cv.want(&d.s_off, n_slices);
+        cv.want(&d.s_len, n_slices);
+        cv.want(&d.s_src_e0, n_slices);
+        cv.want(&d.s_dst_e0, n_slices);
+        cv.want(&d.s_rail, n_slices);
+        cv.want(&d.s_stage_off, n_slices);
+        cv.want(&d.s_state, n_slices);
+        cv.want(&d.s_tau, n_slices);
+        cv.want(&d.s_rec, n_slices);
+        cv.want(&d.s_retry, n_slices);
+        cv.want(&d.priority, (uint64_t)n_desc);
+        cv.want(&d.req_mode, (uint64_t)n_desc);
+        cv.want(&self_dev, 1);
+        if (d.n_sc_tiles == 0) {                              // per-slice tile tables only for untiled geometry
+            cv.want(&d.src_tile, n_tiles);
+            cv.want(&d.dst_tile, n_tiles);
         }
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.tile_scan, d.n_sc_tiles + 1);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.tile_partials, scan_partials_capacity(d.n_sc_tiles));
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.ga_act, d.n_sc_tiles);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_act, d.n_sc_tiles);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_dst, d.n_sc_tiles);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_lin, d.n_sc_tiles);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_slice, d.n_sc_tiles);
-        if (rc == TENT_OK) rc = dev_alloc(b, &d.sc_x, d.n_sc_tiles);
+        d.run_capacity = 2u * n_desc;
+        d.run_stride = ctx->max_rails;
+        cv.want(&d.run_start, (uint64_t)d.run_capacity + 1);
+        cv.want(&d.run_T, (uint64_t)d.run_capacity * d.run_stride);
+        cv.want(&d.run_K, (uint64_t)d.run_capacity * d.run_stride);
+        cv.want(&order_dev, nd);
+        if (d.n_sc_tiles) {
+            cv.want(&d.ord_pre, nd + 1);
+            cv.want(&d.ga_src, d.n_sc_tiles);
+            cv.want(&d.ga_lin, d.n_sc_tiles);
+            cv.want(&d.ga_slice, d.n_sc_tiles);
+            cv.want(&d.ga_x, d.n_sc_tiles);
+            if (ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING) {
+                cv.want(&d.ga_dst, d.n_sc_tiles);
+                cv.want(&d.ch_lo, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
+                cv.want(&d.ch_hi, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
+                cv.want(&d.ch_base, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
+            }
+            cv.want(&d.tile_scan, d.n_sc_tiles + 1);
+            cv.want(&d.tile_partials, scan_partials_capacity(d.n_sc_tiles));
+            cv.want(&d.ga_act, d.n_sc_tiles);
+            cv.want(&d.sc_act, d.n_sc_tiles);
+            cv.want(&d.sc_dst, d.n_sc_tiles);
+            cv.want(&d.sc_lin, d.n_sc_tiles);
+            cv.want(&d.sc_slice, d.n_sc_tiles);
+            cv.want(&d.sc_x, d.n_sc_tiles);
+        }
+        cv.want(&d.pending, n_slices);
+        cv.want(&d.retry_ids, n_slices);
+        const uint64_t rot_chunks = (n_slices + kRotChunk - 1) / kRotChunk;
+        cv.want(&d.rot_bytes, rot_chunks * TENT_MAX_RAILS);
+        cv.want(&d.rot_cnt, rot_chunks * TENT_MAX_RAILS);
+        cv.want(&d.scan_tmp, scan_n + 1);
+        cv.want(&d.scan_partials, scan_partials_capacity(scan_n));
+        cv.want(&d.plan, 1);
+        rc = cv.commit(b);
+    } catch (const std::bad_alloc&) {
+        rc = TENT_ERR_NOMEM;
     }
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.pending, n_slices);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.retry_ids, n_slices);
-    const uint64_t rot_chunks = (n_slices + kRotChunk - 1) / kRotChunk;
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.rot_bytes, rot_chunks * TENT_MAX_RAILS);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.rot_cnt, rot_chunks * TENT_MAX_RAILS);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_tmp, scan_n + 1);
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.scan_partials, scan_partials_capacity(scan_n));
-    if (rc == TENT_OK) rc = dev_alloc(b, &d.plan, 1);
     if (rc != TENT_OK) { free_batch(b); return rc; }
     d.src_ptr = sp; d.dst_ptr = dp; d.src_ext = se; d.dst_ext = de;
     d.dst_order = order_dev;
