@@ -305,6 +305,7 @@ def main():
             wr = W.replanning()
             assert np.array_equal(wr.src_ext, w.src_ext) and np.array_equal(wr.dst_ext, w.dst_ext)
             seqs = []
+            replan_stream = torch.cuda.Stream(dev)
             for _ in range(2):
                 T.tent_reset(ctx, h_fb, stream)
                 torch.cuda.synchronize(dev)
@@ -312,8 +313,11 @@ def main():
                 t0 = time.perf_counter()
                 passes = 0
                 for ep in list(wr.epochs) + [wr.drain]:
-                    st_r, _ = T.tent_plan(ctx, h_fb, ep.rails, want_info=False, stream=stream)
-                    T.tent_sim_advance(ctx, h_fb, ep.budget, stream)
+                    # plan and rail simulator on the second stream: the library orders the re-plan after
+                    # the previous execute's bookkeeping, beside its copies; the simulator's read-back
+                    # waits for the second stream only
+                    st_r, _ = T.tent_plan(ctx, h_fb, ep.rails, want_info=False, stream=replan_stream)
+                    T.tent_sim_advance(ctx, h_fb, ep.budget, replan_stream)
                     T.tent_execute(ctx, h_fb, stream)
                     passes += 1
                 left = T.tent_poll(ctx, h_fb, stream)

@@ -19,6 +19,14 @@
  *     must be used by one host thread at a time.
  *   - `stream` arguments are hipStream_t values passed as void* (NULL = the
  *     default stream).  Calls that take a stream only enqueue work unless stated.
+ *   - Calls on one batch are ordered by the caller: on one stream, or across streams by events
+ *     of the caller's.  One ordering the library provides by itself: tent_plan and
+ *     tent_plan_dispatch on another stream than the batch's last tent_execute wait (on the
+ *     device) for that execute's bookkeeping only -- staging addresses resolved, slices marked
+ *     DONE -- and may then run beside its copies, which read none of what a re-plan writes.
+ *     That is what overlaps the re-planning of the unfinished slices with the data movement of
+ *     the finished ones.  The next tent_execute must still come after that plan (the
+ *     host-side wait of tent_sim_advance, or an event).
  *   - HIP graphs: tent_reset, tent_plan with info = NULL and tent_execute allocate nothing, copy
  *     nothing from or to the host and enqueue kernels only (no memset nodes), so a caller may
  *     record them on a capturing stream and replay the graph.  The host-side bookkeeping of a
@@ -342,7 +350,9 @@ int tent_get_latencies(tent_ctx *ctx, tent_batch_t batch, uint64_t *host_out, ui
  * its rail's staging region, then scatter from staging to the destination
  * extents at the slice's absolute offset (Section 4.1 staging hop; Section 4.4
  * direct-to-offset writes), and mark it DONE.  Enqueues on `stream` and
- * returns; the caller synchronises the stream.  TENT_ERR_STATE if the batch was
+ * returns; the caller synchronises the stream.  The DONE marks are enqueued
+ * ahead of the copies (the copies are driven by address tables, not by slice
+ * state), so on `stream` itself the order is not observable.  TENT_ERR_STATE if the batch was
  * never planned.  A batch with no BOUND slice is a no-op.
  */
 int tent_execute(tent_ctx *ctx, tent_batch_t batch, void *stream);

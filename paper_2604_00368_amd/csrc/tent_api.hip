@@ -25,6 +25,11 @@ struct Batch {
     uint64_t max_req_slices = 0; // most slices any one transfer has
     RailParams last_rails{};     // telemetry of the last plan (for the rail simulator)
     uint32_t last_lat_ns[TENT_MAX_RAILS] = {};
+    // The last execute's bookkeeping (staging addresses, tile lists, DONE marks) ends at prep_event on
+    // exec_stream; its copies, which follow, read none of what a re-plan writes.
+    hipEvent_t prep_event = nullptr;
+    hipStream_t exec_stream = nullptr;
+    bool prep_recorded = false;
     BatchDev dev{};
     std::vector<void*> allocs;
 };
@@ -113,6 +118,9 @@ void free_batch(Batch& b)
 {
     for (void* p : b.allocs) (void)hipFree(p);
     b.allocs.clear();
+    if (b.prep_event) (void)hipEventDestroy(b.prep_event);
+    b.prep_event = nullptr;
+    b.prep_recorded = false;
     b.alive = false;
     b.dev = BatchDev{};
 }
@@ -183,6 +191,33 @@ struct StageTimer {
     }
     ~StageTimer() { if (stop) (void)hipEventRecord(stop, s); }
 };
+
+// A re-plan enqueued on another stream than the last execute's may overlap that execute's copies: it
+// only has to come after the execute's bookkeeping.
+hipError_t order_after_execute_bookkeeping(const Batch& b, hipStream_t s)
+{
+    if (!b.prep_recorded || s == b.exec_stream) return hipSuccess;
+    return hipStreamWaitEvent(s, b.prep_event, 0);
+}
+
+// Marks the end of an execute's bookkeeping on its stream.  Nothing is recorded into a stream that is
+// being captured into a graph; a graph holds its launches in stream order anyway.
+hipError_t record_execute_bookkeeping(Batch& b, hipStream_t s)
+{
+    b.prep_recorded = false;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) != hipSuccess) { (void)hipGetLastError(); return hipSuccess; }
+    if (cap != hipStreamCaptureStatusNone) return hipSuccess;
+    if (!b.prep_event) {
+        hipError_t e = hipEventCreateWithFlags(&b.prep_event, hipEventDisableTiming);
+        if (e != hipSuccess) { b.prep_event = nullptr; return e; }
+    }
+    hipError_t e = hipEventRecord(b.prep_event, s);
+    if (e != hipSuccess) return e;
+    b.exec_stream = s;
+    b.prep_recorded = true;
+    return hipSuccess;
+}
 
 // Telemetry -> integer coefficients (Eq. 1 with the topology penalty folded in).
 int convert_rails(const tent_rail_state* rails, uint32_t n_rails, uint64_t pending_bytes, RailParams* rp)
@@ -459,6 +494,7 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BatchDev& d = b->dev;
+    HIP_TRY(order_after_execute_bookkeeping(*b, s));
 
     // Retry rotation (Section 4.3, "Link-Level Resilience"): candidates are the HEALTHY rails, else the
     // DEGRADED rails without topology penalty, else every DEGRADED rail, in ascending index.
@@ -582,6 +618,7 @@ int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state*
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BatchDev& d = b->dev;
+    HIP_TRY(order_after_execute_bookkeeping(*b, s));
     dp.all_high = priority ? 0u : 1u;
     if (priority) HIP_TRY(hipMemcpyAsync(d.priority, priority, d.n_desc, hipMemcpyHostToDevice, s));
     if (!b->planned) {
@@ -799,6 +836,11 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     const uint64_t max_tiles = b->bound_hint * b->dev.tiles_per_slice;
     const bool compact = b->dev.n_sc_tiles != 0 && b->dev.n_sc_tiles < (1ull << 32) && max_tiles * 2 <= b->dev.n_sc_tiles;
     HIP_TRY(launch_finalize(b->dev, static_cast<uint8_t*>(ctx->cfg.staging_arena), compact, max_tiles, s));
+    // The copies below are driven by the tables just written and read no slice state, so the slices
+    // are marked DONE ahead of them: in stream order nothing changes, and the next re-plan, if it
+    // is enqueued on another stream, can run beside the copies.
+    HIP_TRY(launch_mark_done(b->dev, compact, s));
+    HIP_TRY(record_execute_bookkeeping(*b, s));
     {
         StageTimer t(ctx, TENT_T_GATHER, s);
         if (compact)                HIP_TRY(launch_copy_compact(b->dev, true, max_tiles, s));
@@ -811,7 +853,6 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
         else if (b->dev.n_sc_tiles) HIP_TRY(launch_copy_ordered(b->dev, false, s));
         else                        HIP_TRY(launch_copy(b->dev, false, s));
     }
-    HIP_TRY(launch_mark_done(b->dev, compact, s));
     b->has_done = true;
     b->bound_hint = 0;
     return TENT_OK;

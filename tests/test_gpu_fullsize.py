@@ -145,6 +145,40 @@ def test_full_size_replanning(H, oracle):
         torch.cuda.empty_cache()
 
 
+def test_full_size_replanning_plan_beside_copies(H, oracle):
+    """Config 4 the way the benchmark runs it: plans and the rail simulator on a second stream, executes on
+    the first, no host wait between an execute and the next plan."""
+    from paper_2604_00368_amd import binding as T
+    print("full-size replanning, plans beside copies", flush=True)
+    w = W.replanning()
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    records, left = oracle.run_epochs(w, s)
+    assert left.shape[0] == 0
+    eng = H.Engine(w)
+    try:
+        eng.declare()
+        side = torch.cuda.Stream(eng.dev)
+        side.wait_stream(eng.stream)
+        for e, (rec, ep) in enumerate(zip(records, list(w.epochs) + [w.drain])):
+            st, info = T.tent_plan(eng.ctx, eng.batch, ep.rails, True, side)
+            assert st == 0 and info.n_slices == rec["pending"].shape[0]
+            if rec["T"] is not None:
+                R = ep.rails.shape[0]
+                assert list(info.rail_bytes)[:R] == rec["T"].tolist()
+            n_done = T.tent_sim_advance(eng.ctx, eng.batch, ep.budget, side)
+            assert n_done == rec["done_ids"].shape[0]
+            T.tent_execute(eng.ctx, eng.batch, eng.stream)
+            print("  epoch", e, "done", n_done, flush=True)
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        torch.cuda.synchronize(eng.dev)
+        device_definition_check(w, eng.src, eng.dst)
+    finally:
+        eng.close()
+        del eng
+        gc.collect()
+        torch.cuda.empty_cache()
+
+
 def test_full_size_closed_loop(H, oracle):
     # config 4 with the telemetry loop closed (plan, rails, latencies, probes and estimates per epoch)
     import test_gpu_parity as P

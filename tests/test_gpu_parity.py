@@ -169,6 +169,48 @@ def test_replanning_epochs_bit_exact(H, oracle):
     run_epochs_and_compare(H, oracle, W.small_variant("replanning"), flags=T.TENT_FLAG_SERIAL_BINDING)
 
 
+def run_epochs_plan_beside_copies(H, oracle, w, flags=0):
+    """The same epochs with plans and the rail simulator on a second stream and executes on the first, and no
+    wait of the host's between an execute and the next plan: the library itself orders a re-plan after the
+    execute's bookkeeping, beside its copies."""
+    import torch
+    from paper_2604_00368_amd import binding as T
+    src = W.fill_numpy(w, 0)
+    dst0 = W.fill_numpy(w, 1)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    dst_want = dst0.copy()
+    staging_want = np.zeros(w.staging_bytes, dtype=np.uint8)
+    records, left = oracle.run_epochs(w, s, [src, dst_want], staging_want)
+    assert left.shape[0] == 0
+    with H.Engine(w, src, dst0, flags=flags) as eng:
+        eng.declare()
+        side = torch.cuda.Stream(eng.dev)
+        side.wait_stream(eng.stream)                      # the pools were filled on the first stream
+        for e, (rec, ep) in enumerate(zip(records, list(w.epochs) + [w.drain])):
+            st, info = T.tent_plan(eng.ctx, eng.batch, ep.rails, True, side)
+            assert st == rec["status"] == 0
+            assert info.n_slices == rec["pending"].shape[0] == info.n_pending_before
+            if rec["T"] is not None:
+                R = ep.rails.shape[0]
+                assert list(info.rail_bytes)[:R] == rec["T"].tolist()
+                assert list(info.stage_base)[:R] == rec["base"].tolist()
+            n_done = T.tent_sim_advance(eng.ctx, eng.batch, ep.budget, side)   # waits for the second stream only
+            assert n_done == rec["done_ids"].shape[0]
+            T.tent_execute(eng.ctx, eng.batch, eng.stream)
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        torch.cuda.synchronize(eng.dev)
+        tab = eng.table()
+        assert (tab["state"] == 2).all()
+        assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+        assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+
+
+def test_replanning_epochs_plan_beside_copies(H, oracle):
+    from paper_2604_00368_amd import binding as T
+    run_epochs_plan_beside_copies(H, oracle, W.small_variant("replanning"))
+    run_epochs_plan_beside_copies(H, oracle, W.small_variant("replanning"), flags=T.TENT_FLAG_SERIAL_BINDING)
+
+
 def test_replanning_many_small_shape(H, oracle):
     # re-planning over a workload whose slices straddle pages and whose pending runs are short
     w = W.many_small(n_req=48, layers=2)
