@@ -305,7 +305,7 @@ def main():
             wr = W.replanning()
             assert np.array_equal(wr.src_ext, w.src_ext) and np.array_equal(wr.dst_ext, w.dst_ext)
             seqs = []
-            replan_stream = torch.cuda.Stream(dev)
+            replan_stream = plan_stream                       # streams share 4 hardware queues: no further stream here
             for _ in range(2):
                 T.tent_reset(ctx, h_fb, stream)
                 torch.cuda.synchronize(dev)

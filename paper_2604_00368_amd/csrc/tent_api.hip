@@ -931,6 +931,7 @@ int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes
         if (n_chunks >= 2) HIP_TRY(hipStreamWaitEvent(s, ctx->sync_events[2 * (n_chunks - 2) + 1], 0));
     }
     HIP_TRY(launch_mark_done_bounded(d, s));
+    b->prep_recorded = false;                                 // the bounded execute offers no overlap with a re-plan
     b->has_done = true;
     b->bound_hint = 0;
     return TENT_OK;
