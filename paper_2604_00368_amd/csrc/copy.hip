@@ -198,21 +198,18 @@ hipError_t launch_copy_ordered(const BatchDev& b, bool gather, hipStream_t s)
     return hipGetLastError();
 }
 
-// The same copy over a compacted list of tiles (one workgroup per listed tile, tile_bytes / 16 lanes):
-// used when few slices of the batch move, so that the launch is sized by what moves.  The grid is
-// an upper bound known to the host; workgroups beyond the device-side count leave at once.
+// The same copy over a list of tiles (one workgroup per listed tile, tile_bytes / 16 lanes): used when
+// few slices of the batch move, so that the launch is sized by what moves.  The grid is an upper
+// bound known to the host; workgroups beyond the device-side count leave at once.
 template <bool kGather>
 __global__ void __launch_bounds__(256) compact_copy_kernel(const uint64_t* __restrict__ from,
                                                            const uint64_t* __restrict__ to,
-                                                           const uint32_t* __restrict__ act,
                                                            const uint64_t* __restrict__ n_act)
 {
     const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
     if (w >= *n_act) return;
-    const uint32_t q = act[w];
-    const uint64_t src = from[q];
-    const uint64_t dst = to[q];
-    if (src == 0 || dst == 0) return;
+    const uint64_t src = from[w];
+    const uint64_t dst = to[w];
     const uint64_t in_tile = (uint64_t)threadIdx.x * 16;
     vec4u v = __builtin_nontemporal_load((const vec4u_dev*)(src + in_tile));
     __builtin_nontemporal_store(v, (vec4u_dev*)(dst + in_tile));
@@ -220,16 +217,16 @@ __global__ void __launch_bounds__(256) compact_copy_kernel(const uint64_t* __res
 
 hipError_t launch_copy_compact(const BatchDev& b, bool gather, uint64_t max_tiles, hipStream_t s)
 {
-    if (max_tiles > b.n_sc_tiles) max_tiles = b.n_sc_tiles;
+    if (max_tiles > b.act_capacity) max_tiles = b.act_capacity;
     if (max_tiles == 0) return hipSuccess;
     const uint32_t gx = max_tiles < 65536 ? (uint32_t)max_tiles : 65536u;
     const uint64_t gy = (max_tiles + gx - 1) / gx;
     if (gy > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 grid(gx, (uint32_t)gy), block(b.tile_bytes / 16);
     if (gather)
-        hipLaunchKernelGGL(compact_copy_kernel<true>, grid, block, 0, s, b.ga_src, b.ga_lin, b.ga_act, &b.plan->n_ga_act);
+        hipLaunchKernelGGL(compact_copy_kernel<true>, grid, block, 0, s, b.act_src, b.act_lin, &b.plan->n_act);
     else
-        hipLaunchKernelGGL(compact_copy_kernel<false>, grid, block, 0, s, b.sc_lin, b.sc_dst, b.sc_act, &b.plan->n_sc_act);
+        hipLaunchKernelGGL(compact_copy_kernel<false>, grid, block, 0, s, b.act_lin, b.act_dst, &b.plan->n_act);
     return hipGetLastError();
 }
 

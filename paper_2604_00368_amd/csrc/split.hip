@@ -221,33 +221,47 @@ __global__ void __launch_bounds__(256) finalize_tiles_kernel(BatchDev b)
 }
 
 // When only a small part of the batch moves (re-planning epochs), the copy launches should not pay for
-// every tile of the batch: the tiles that do move are compacted into two index lists, one per
-// enumeration, by one scan that carries both counters (gather list low half, scatter list high half).
-struct ActiveTiles {
-    const uint64_t* ga;
-    const uint64_t* sc;
-    __device__ uint64_t operator()(uint64_t q) const
-    {
-        return (ga[q] != 0 ? 1ull : 0ull) | (sc[q] != 0 ? (1ull << 32) : 0ull);
-    }
+// every tile of the batch.  The tiles of the BOUND slices are listed instead: a scan over the slices
+// gives each BOUND slice the position of its first tile in the list, and one wavefront per BOUND slice
+// resolves the three addresses of each of its tiles (source, staging, destination) from the slice
+// table and the extent lists.  The work is proportional to what moves, not to the batch.
+struct BoundTiles {
+    const SliceRec* rec;
+    uint32_t tile_shift;
+    __device__ uint64_t operator()(uint64_t i) const { return rec[i].len >> tile_shift; }   // 0 unless BOUND
 };
 
-__global__ void __launch_bounds__(256) tile_compact_kernel(BatchDev b, uint64_t max_tiles)
+__global__ void __launch_bounds__(256) tile_list_kernel(BatchDev b, uint32_t tile_shift, uint64_t max_tiles)
 {
-    const uint64_t n = b.n_sc_tiles;
-    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < n; q += stride) {
-        const uint64_t at = b.tile_scan[q];
-        if (b.ga_lin[q] != 0) b.ga_act[at & 0xFFFFFFFFu] = (uint32_t)q;
-        if (b.sc_lin[q] != 0) b.sc_act[at >> 32] = (uint32_t)q;
-    }
+    const uint64_t i = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);      // one wavefront per slice
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        const uint64_t n_ga = b.tile_scan[n] & 0xFFFFFFFFu, n_sc = b.tile_scan[n] >> 32;
-        b.plan->n_ga_act = n_ga;
-        b.plan->n_sc_act = n_sc;
+        const uint64_t n_act = b.tile_scan[b.n_slices];
+        b.plan->n_act = n_act < b.act_capacity ? n_act : b.act_capacity;
         // the copy launches are sized by the host's bound on the BOUND slices; should more tiles move than
-        // that, the copies would be incomplete, so nothing may be marked DONE
-        b.plan->compact_overflow = (n_ga > max_tiles || n_sc > max_tiles) ? 1 : 0;
+        // that (or than the list holds), the copies would be incomplete, so nothing may be marked DONE
+        b.plan->compact_overflow = (n_act > max_tiles || n_act > b.act_capacity) ? 1 : 0;
+    }
+    if (i >= b.n_slices) return;
+    const SliceRec r = b.s_rec[i];
+    const uint32_t n_t = r.len >> tile_shift;
+    if (n_t == 0) return;
+    const uint64_t at = b.tile_scan[i];
+    const uint32_t j = b.s_desc[i];
+    const uint64_t off = b.s_off[i];
+    const uint32_t s_hi = b.src_ptr[j + 1], d_hi = b.dst_ptr[j + 1];
+    const uint64_t s_pos0 = b.src_pre[b.src_ptr[j]] + off, d_pos0 = b.dst_pre[b.dst_ptr[j]] + off;
+    const uint32_t s_e0 = b.s_src_e0[i], d_e0 = b.s_dst_e0[i];
+    for (uint32_t t = threadIdx.x & 63; t < n_t; t += 64) {
+        const uint64_t p = at + t;
+        if (p >= b.act_capacity) break;
+        const uint64_t x = (uint64_t)t << tile_shift;
+        const uint64_t se = last_not_above(b.src_pre, s_e0, s_hi, s_pos0 + x);
+        const tent_extent sx = b.src_ext[se];
+        const uint64_t de = last_not_above(b.dst_pre, d_e0, d_hi, d_pos0 + x);
+        const tent_extent dx = b.dst_ext[de];
+        b.act_src[p] = b.seg_base[sx.seg] + sx.off + (s_pos0 + x - b.src_pre[se]);
+        b.act_lin[p] = r.lin + x;
+        b.act_dst[p] = b.seg_base[dx.seg] + dx.off + (d_pos0 + x - b.dst_pre[de]);
     }
 }
 
@@ -256,15 +270,18 @@ hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, bool compact, uint
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(finalize_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, arena);
-    if (b.n_sc_tiles) {
+    if (b.n_sc_tiles && compact) {
+        uint32_t tile_shift = 0;
+        while ((1u << tile_shift) < b.tile_bytes) ++tile_shift;
+        hipError_t e = exclusive_scan(BoundTiles{b.s_rec, tile_shift}, b.n_slices, b.tile_scan, b.tile_partials, s);
+        if (e != hipSuccess) return e;
+        const uint64_t lists = (b.n_slices + 3) / 4;
+        if (lists > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(tile_list_kernel, dim3((uint32_t)lists), dim3(256), 0, s, b, tile_shift, max_tiles);
+    } else if (b.n_sc_tiles) {
         blocks = (b.n_sc_tiles + 255) / 256;
         if (blocks > 65536) blocks = 65536;
         hipLaunchKernelGGL(finalize_tiles_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
-        if (compact) {
-            hipError_t e = exclusive_scan(ActiveTiles{b.ga_lin, b.sc_lin}, b.n_sc_tiles, b.tile_scan, b.tile_partials, s);
-            if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(tile_compact_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, max_tiles);
-        }
     }
     return hipGetLastError();
 }

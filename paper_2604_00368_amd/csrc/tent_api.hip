@@ -421,10 +421,13 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
                 cv.want(&d.ch_hi, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
                 cv.want(&d.ch_base, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
             }
-            cv.want(&d.tile_scan, d.n_sc_tiles + 1);
-            cv.want(&d.tile_partials, scan_partials_capacity(d.n_sc_tiles));
-            cv.want(&d.ga_act, d.n_sc_tiles);
-            cv.want(&d.sc_act, d.n_sc_tiles);
+            // an execute goes over a list of tiles only when at most half of the batch's tiles can move
+            d.act_capacity = d.n_sc_tiles / 2 + 1;
+            cv.want(&d.tile_scan, n_slices + 1);
+            cv.want(&d.tile_partials, scan_partials_capacity(n_slices));
+            cv.want(&d.act_src, d.act_capacity);
+            cv.want(&d.act_lin, d.act_capacity);
+            cv.want(&d.act_dst, d.act_capacity);
             cv.want(&d.sc_dst, d.n_sc_tiles);
             cv.want(&d.sc_lin, d.n_sc_tiles);
             cv.want(&d.sc_slice, d.n_sc_tiles);
@@ -832,9 +835,9 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     // When the host knows that only a small part of the batch is BOUND (after the rail simulator), the
-    // copies run over compacted tile lists and their launches are sized by that part.
+    // copies run over a list of the tiles of the BOUND slices and their launches are sized by that part.
     const uint64_t max_tiles = b->bound_hint * b->dev.tiles_per_slice;
-    const bool compact = b->dev.n_sc_tiles != 0 && b->dev.n_sc_tiles < (1ull << 32) && max_tiles * 2 <= b->dev.n_sc_tiles;
+    const bool compact = b->dev.n_sc_tiles != 0 && max_tiles * 2 <= b->dev.n_sc_tiles;
     HIP_TRY(launch_finalize(b->dev, static_cast<uint8_t*>(ctx->cfg.staging_arena), compact, max_tiles, s));
     // The copies below are driven by the tables just written and read no slice state, so the slices
     // are marked DONE ahead of them: in stream order nothing changes, and the next re-plan, if it

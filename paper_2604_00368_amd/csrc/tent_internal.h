@@ -82,7 +82,7 @@ struct PlanState {
     uint64_t n_mice, n_elephant, n_deferred;   // tent_plan_dispatch: requests per mode
     uint64_t rr_next;                     // round-robin counter after the call
     uint64_t bounded_overflow;            // tent_execute_bounded: chunks whose regions do not fit the arena
-    uint64_t n_ga_act, n_sc_act;          // tent_execute with few BOUND slices: entries of the compacted tile lists
+    uint64_t n_act;                       // tent_execute with few BOUND slices: entries of the list of tiles that move
     uint64_t compact_overflow;            // nonzero: more tiles move than the launch was sized for (nothing is marked DONE)
 };
 
@@ -147,10 +147,12 @@ struct BatchDev {
     uint64_t* ch_lo;               // [kMaxChunks * TENT_MAX_RAILS] bounded staging: first staging offset per chunk and rail
     uint64_t* ch_hi;               // same shape: end of the interval
     uint64_t* ch_base;             // same shape: region base inside the arena
-    uint64_t* tile_scan;           // [n_sc_tiles+1] scan workspace of the per-execute tile compaction
+    uint64_t* tile_scan;           // [n_slices+1] scan workspace of the per-execute tile list: tiles of the BOUND slices before slice i
     uint64_t* tile_partials;       // its per-block partial sums
-    uint32_t* ga_act;              // [n_sc_tiles] declaration-order tiles that move in this execute, compacted
-    uint32_t* sc_act;              // [n_sc_tiles] destination-order tiles that move in this execute, compacted
+    uint64_t* act_src;             // [act_capacity] per listed tile (BOUND slices in ascending index, tiles in order): source address,
+    uint64_t* act_lin;             //                staging address,
+    uint64_t* act_dst;             //                destination address
+    uint64_t  act_capacity;
     uint64_t* sc_dst;              // [n_sc_tiles] scatter: destination address of the tile
     uint64_t* sc_lin;              // [n_sc_tiles] scatter: staging address, 0 = not to be moved
     uint32_t* sc_slice;
