@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0
 # to one version of the copy kernels and of the kernels that build their tables: when copy.hip or
 # split.hip changes they are reported as null.
 PMC_TRAFFIC = {
-    "copy_sources_sha256": "b947677ba1b994b7f662e8f95159f50bf4c2279cd3bf552d57ce38c40ba5d31d",
-    "kv_migration": {"gather": 43019350855, "scatter": 43019346759},
+    "copy_sources_sha256": "b28fb830705592104d9060341445215e177215e2229344586e1bd46295b49c45",
+    "kv_migration": {"gather": 43019354439, "scatter": 43019351623},
 }
 
 

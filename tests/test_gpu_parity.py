@@ -211,6 +211,28 @@ def test_replanning_epochs_plan_beside_copies(H, oracle):
     run_epochs_plan_beside_copies(H, oracle, W.small_variant("replanning"), flags=T.TENT_FLAG_SERIAL_BINDING)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_partial_executes_random_tiled_geometry(H, oracle, seed):
+    # lengths in multiples of 1-4 KiB, source and destination cut differently, a few epochs with random budgets:
+    # partial executes go over the list of the BOUND slices' tiles, on one stream and with plans on a second
+    rng = np.random.Generator(np.random.PCG64(9000 + seed))
+    align = int(rng.choice([1024, 2048, 4096]))
+    w = W.ragged(7000 + seed, n_desc=int(rng.integers(3, 60)), max_len=int(rng.integers(20, 400)) * 1024,
+                 max_ext=int(rng.integers(1, 24)) * 1024, slice_bytes=align * int(rng.integers(1, 40)),
+                 n_rails=int(rng.integers(1, 12)), align=align)
+    R = w.rails.shape[0]
+    t_us = max(1, -(-w.payload // int(float(rng.choice([2, 4, 8])) * int(w.rails["bw_MBps"].astype(np.uint64).sum()))))
+    epochs = []
+    for e in range(int(rng.integers(2, 7))):
+        bw = np.maximum(1, np.rint(w.rails["bw_MBps"] * np.exp(0.5 * rng.standard_normal(R)))).astype(np.uint64)
+        rails = W.make_rails(bw, queued=rng.integers(0, 64 * 1024, size=R), health=w.rails["health"].copy())
+        epochs.append(W.Epoch(rails, bw * np.uint64(t_us)))
+    w.epochs = epochs
+    w.drain = W.Epoch(epochs[-1].rails.copy(), np.full(R, np.iinfo(np.uint64).max, dtype=np.uint64))
+    run_epochs_and_compare(H, oracle, w)
+    run_epochs_plan_beside_copies(H, oracle, w)
+
+
 def test_replanning_many_small_shape(H, oracle):
     # re-planning over a workload whose slices straddle pages and whose pending runs are short
     w = W.many_small(n_req=48, layers=2)
