@@ -20,6 +20,7 @@
 //                    k + sum_{d' < d} count_d'(f) + sum_{d' > d} count_d'(f - 1),  f = f_d(k),
 //                    which gives the slice it belongs to; staging offset = T_d at run start + k l.
 #include "scan.h"
+#include "tile_tables.h"
 #include "wave.h"
 
 namespace tent {
@@ -138,8 +139,9 @@ __device__ __forceinline__ uint32_t slots_upto_fast(const Rail& r, uint64_t A, u
 }
 
 // kWide = 16, 32 or 64: lanes that can hold a rail; with 16 every reduction stays inside one DPP row.
+// Runs in the first wavefront of a workgroup (lane = threadIdx.x < 64).
 template <int kWide>
-__global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams rp, int mode)
+__device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& rp, int mode)
 {
     const bool use_pending = (mode & kBindUsePending) != 0;
     const int lane = threadIdx.x;
@@ -385,6 +387,25 @@ __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams r
     if (lane == 0) ps->n_bound = ps->n_pending + n_before;
 }
 
+template <int kWide>
+__global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams rp, int mode)
+{
+    bind_chain<kWide>(b, rp, mode);
+}
+
+// The chain is one wavefront; the tile tables of the copy kernels depend on the slice table only, not
+// on the binding.  On a first plan both go into one launch: workgroup 0 walks the chain, the others
+// build the tables, so the tables cost no time of their own.
+template <int kWide>
+__global__ void __launch_bounds__(256) bind_chain_tables_kernel(BatchDev b, RailParams rp, int mode)
+{
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < 64) bind_chain<kWide>(b, rp, mode);
+        return;
+    }
+    build_tile_tables(b, blockIdx.x - 1, gridDim.x - 1);
+}
+
 // ---- step 3: emit -----------------------------------------------------------------------------
 // One lane per position q of the pending sequence; inside its run the lane enumerates slot
 // t = q - run_start as (rail d, index k) in rail-major order and computes the slot's rank.
@@ -462,9 +483,16 @@ hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, h
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(run_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, up);
-    if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, mode);
-    else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, mode);
-    else                       hipLaunchKernelGGL(bind_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, mode);
+    if (mode & kBindBuildTables) {
+        const dim3 grid(1 + tile_table_blocks(b)), block(256);
+        if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_tables_kernel<16>, grid, block, 0, s, b, rp, mode);
+        else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_tables_kernel<32>, grid, block, 0, s, b, rp, mode);
+        else                       hipLaunchKernelGGL(bind_chain_tables_kernel<64>, grid, block, 0, s, b, rp, mode);
+    } else {
+        if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, mode);
+        else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, mode);
+        else                       hipLaunchKernelGGL(bind_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, mode);
+    }
     hipLaunchKernelGGL(bind_emit_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, rp, up);
     return hipGetLastError();
 }

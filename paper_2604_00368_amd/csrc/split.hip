@@ -4,6 +4,7 @@
 // transfer of len bytes becomes ceil(len / S) slices; slice k covers [k*S, min((k+1)*S, len))
 // and keeps that absolute offset so it can be written straight to its destination.
 #include "scan.h"
+#include "tile_tables.h"
 
 namespace tent {
 
@@ -39,16 +40,6 @@ hipError_t launch_slice_scan(const BatchDev& b, hipStream_t s)
 }
 
 // ---- S3: slice table expansion ---------------------------------------------------------------
-// Largest index i in [lo, hi) with a[i] <= key (a is nondecreasing and a[lo] <= key).
-__device__ __forceinline__ uint64_t last_not_above(const uint64_t* a, uint64_t lo, uint64_t hi, uint64_t key)
-{
-    while (hi - lo > 1) {
-        uint64_t mid = lo + ((hi - lo) >> 1);
-        if (a[mid] <= key) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 __global__ void __launch_bounds__(256) expand_kernel(BatchDev b)
 {
     const uint64_t n = b.first[b.n_desc];
@@ -81,114 +72,27 @@ hipError_t launch_expand(const BatchDev& b, hipStream_t s)
 }
 
 // ---- S3b: tile tables ------------------------------------------------------------------------
-// One thread per (slice, tile): locate the extent that holds the tile's first byte and store the
-// tile's device address, so that the copy kernels reach their bytes with one table load.
-__global__ void __launch_bounds__(256) tile_table_kernel(BatchDev b)
-{
-    const uint64_t n = b.n_slices * (uint64_t)b.tiles_per_slice;
-    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < n; q += stride) {
-        const uint64_t i = q / b.tiles_per_slice;
-        const uint64_t x = (q - i * b.tiles_per_slice) * b.tile_bytes;      // byte offset inside the slice
-        const uint32_t len = b.s_len[i];
-        if (x >= len) { b.src_tile[q] = kTileSlow; b.dst_tile[q] = kTileSlow; continue; }
-        const uint64_t n_tile = len - x < b.tile_bytes ? len - x : b.tile_bytes;
-        const uint32_t j = b.s_desc[i];
-        {
-            const uint32_t hi = b.src_ptr[j + 1];
-            const uint64_t pos = b.src_pre[b.src_ptr[j]] + b.s_off[i] + x;
-            const uint32_t e = (uint32_t)last_not_above(b.src_pre, b.s_src_e0[i], hi, pos);
-            const tent_extent ex = b.src_ext[e];
-            const uint64_t addr = b.seg_base[ex.seg] + ex.off + (pos - b.src_pre[e]);
-            const bool slow = pos + n_tile > b.src_pre[e + 1];
-            b.src_tile[q] = addr | (slow ? kTileSlow : 0);
-        }
-        {
-            const uint32_t hi = b.dst_ptr[j + 1];
-            const uint64_t pos = b.dst_pre[b.dst_ptr[j]] + b.s_off[i] + x;
-            const uint32_t e = (uint32_t)last_not_above(b.dst_pre, b.s_dst_e0[i], hi, pos);
-            const tent_extent ex = b.dst_ext[e];
-            const uint64_t addr = b.seg_base[ex.seg] + ex.off + (pos - b.dst_pre[e]);
-            const bool slow = pos + n_tile > b.dst_pre[e + 1];
-            b.dst_tile[q] = addr | (slow ? kTileSlow : 0);
-        }
-    }
-}
-
-// Destination-ordered tiles: tile q covers bytes [q*tile, (q+1)*tile) of the destination extents
-// laid end to end in ascending device address.  For each tile: its destination address, the slice
-// that owns it and its offset inside that slice (independent of the binding).
+// The builders are in tile_tables.h.  The destination-ordered table needs the exclusive prefix of
+// the destination extent lengths in ascending address order first.
 struct OrderedLen {
     const tent_extent* ext;
     const uint32_t* order;
     __device__ uint64_t operator()(uint64_t r) const { return ext[order[r]].len; }
 };
 
-__global__ void __launch_bounds__(256) scatter_table_kernel(BatchDev b)
-{
-    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < b.n_sc_tiles; q += stride) {
-        const uint64_t at = q * b.tile_bytes;
-        const uint64_t r = last_not_above(b.ord_pre, 0, b.n_dst_ext, at);
-        const uint32_t e = b.dst_order[r];
-        const uint64_t within = at - b.ord_pre[r];
-        const tent_extent ex = b.dst_ext[e];
-        // owning transfer: last j with dst_ptr[j] <= e
-        uint32_t lo = 0, hi = b.n_desc;
-        while (hi - lo > 1) {
-            const uint32_t mid = lo + ((hi - lo) >> 1);
-            if (b.dst_ptr[mid] <= e) lo = mid; else hi = mid;
-        }
-        const uint64_t off = b.dst_pre[e] + within - b.dst_pre[b.dst_ptr[lo]];   // offset inside the transfer
-        const uint64_t k = off / b.slice_bytes;
-        b.sc_dst[q] = b.seg_base[ex.seg] + ex.off + within;
-        b.sc_slice[q] = (uint32_t)(b.first[lo] + k);
-        b.sc_x[q] = (uint32_t)(off - k * b.slice_bytes);
-    }
-}
+__global__ void __launch_bounds__(256) tile_tables_kernel(BatchDev b) { build_tile_tables(b, blockIdx.x, gridDim.x); }
 
-// Source-ordered tiles: tile q covers bytes [q*tile, (q+1)*tile) of the source extents laid end to
-// end in declaration order, i.e. of the transfers' logical bytes one after the other.
-__global__ void __launch_bounds__(256) gather_table_kernel(BatchDev b)
+hipError_t launch_tile_tables_prepare(const BatchDev& b, hipStream_t s)
 {
-    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; q < b.n_sc_tiles; q += stride) {
-        const uint64_t at = q * b.tile_bytes;
-        const uint64_t e = last_not_above(b.src_pre, 0, b.n_src_ext, at);
-        const tent_extent ex = b.src_ext[e];
-        uint32_t lo = 0, hi = b.n_desc;                   // owning transfer: last j with src_ptr[j] <= e
-        while (hi - lo > 1) {
-            const uint32_t mid = lo + ((hi - lo) >> 1);
-            if (b.src_ptr[mid] <= e) lo = mid; else hi = mid;
-        }
-        const uint64_t off = at - b.src_pre[b.src_ptr[lo]];
-        const uint64_t k = off / b.slice_bytes;
-        b.ga_src[q] = b.seg_base[ex.seg] + ex.off + (at - b.src_pre[e]);
-        b.ga_slice[q] = (uint32_t)(b.first[lo] + k);
-        b.ga_x[q] = (uint32_t)(off - k * b.slice_bytes);
-        if (b.ga_dst) {                                   // same tile on the destination side
-            const uint64_t dpos = b.dst_pre[b.dst_ptr[lo]] + off;
-            const uint64_t de = last_not_above(b.dst_pre, b.dst_ptr[lo], b.dst_ptr[lo + 1], dpos);
-            const tent_extent dx = b.dst_ext[de];
-            b.ga_dst[q] = b.seg_base[dx.seg] + dx.off + (dpos - b.dst_pre[de]);
-        }
-    }
+    if (b.n_sc_tiles == 0) return hipSuccess;
+    return exclusive_scan(OrderedLen{b.dst_ext, b.dst_order}, b.n_dst_ext, b.ord_pre, b.scan_partials, s);
 }
 
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s)
 {
-    if (b.n_sc_tiles == 0) {
-        uint64_t blocks = (b.n_slices * (uint64_t)b.tiles_per_slice + 255) / 256;
-        if (blocks > 65536) blocks = 65536;
-        hipLaunchKernelGGL(tile_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
-        return hipGetLastError();
-    }
-    hipError_t e = exclusive_scan(OrderedLen{b.dst_ext, b.dst_order}, b.n_dst_ext, b.ord_pre, b.scan_partials, s);
+    hipError_t e = launch_tile_tables_prepare(b, s);
     if (e != hipSuccess) return e;
-    uint64_t blocks = (b.n_sc_tiles + 255) / 256;
-    if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(gather_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
-    hipLaunchKernelGGL(scatter_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
+    hipLaunchKernelGGL(tile_tables_kernel, dim3(tile_table_blocks(b)), dim3(256), 0, s, b);
     return hipGetLastError();
 }
 

@@ -514,6 +514,11 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     }
 
     const bool replan = b->has_done || b->has_retry;
+    // the run-parallel chain divides by c1, so a rail whose cost does not grow with bytes
+    // (c1 = 0) sends the plan down the slice-by-slice kernel
+    bool serial = (ctx->cfg.flags & TENT_FLAG_SERIAL_BINDING) != 0;
+    for (uint32_t r = 0; r < n_rails; ++r)
+        if (((rp.admitted >> r) & 1) && rp.c1[r] == 0) serial = true;
     if (!replan) {
         {
             StageTimer t(ctx, TENT_T_EXTENT_SCAN, s);
@@ -525,9 +530,12 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
             HIP_TRY(launch_slice_scan(d, s));
         }
         {
+            // the tile tables of the copy kernels are built beside the binding chain, in its launch
+            // (the slice-by-slice binder has no such launch: there they are built here)
             StageTimer t(ctx, TENT_T_EXPAND, s);
             HIP_TRY(launch_expand(d, s));
-            HIP_TRY(launch_tile_tables(d, s));
+            if (serial) HIP_TRY(launch_tile_tables(d, s));
+            else        HIP_TRY(launch_tile_tables_prepare(d, s));
         }
     } else {
         StageTimer t(ctx, TENT_T_COMPACT, s);
@@ -541,13 +549,8 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     }
     {
         StageTimer t(ctx, TENT_T_BIND, s);
-        // the run-parallel chain divides by c1, so a rail whose cost does not grow with bytes
-        // (c1 = 0) sends the plan down the slice-by-slice kernel
-        bool serial = (ctx->cfg.flags & TENT_FLAG_SERIAL_BINDING) != 0;
-        for (uint32_t r = 0; r < n_rails; ++r)
-            if (((rp.admitted >> r) & 1) && rp.c1[r] == 0) serial = true;
         if (serial) HIP_TRY(launch_bind_serial(d, rp, mode, s));
-        else        HIP_TRY(launch_bind_runs(d, rp, mode, s));
+        else        HIP_TRY(launch_bind_runs(d, rp, mode | (replan ? 0 : kBindBuildTables), s));
     }
     b->planned = true;
     b->bound_hint = b->dev.n_slices;

@@ -183,7 +183,7 @@ constexpr uint64_t kTileSlow = 1ull << 63;
 enum : uint32_t { kMaxChunks = 4096 };               // most chunks one bounded execute may use
 enum : uint32_t { kRotChunk = 1024 };                // retried slices one rotation workgroup handles
 // `mode` argument of the bind kernels
-enum : int { kBindUsePending = 1, kBindAfterRotation = 2 };
+enum : int { kBindUsePending = 1, kBindAfterRotation = 2, kBindBuildTables = 4 };
 
 // ---- launch wrappers (each enqueues on `s` and returns the launch status) -------------------
 hipError_t launch_extent_scan(const tent_extent* ext, uint64_t n_ext, uint64_t* pre, uint64_t* partials,
@@ -201,6 +201,7 @@ hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, u
 hipError_t launch_mark_done_bounded(const BatchDev& b, hipStream_t s);
 hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, hipStream_t s);
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
+hipError_t launch_tile_tables_prepare(const BatchDev& b, hipStream_t s);   // what the builders need when they run inside the chain launch
 hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, bool compact, uint64_t max_tiles, hipStream_t s);
 hipError_t launch_copy(const BatchDev& b, bool gather, hipStream_t s);
 hipError_t launch_copy_ordered(const BatchDev& b, bool gather, hipStream_t s);
