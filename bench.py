@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0
 # to one version of the copy kernels and of the kernels that build their tables: when copy.hip or
 # split.hip changes they are reported as null.
 PMC_TRAFFIC = {
-    "copy_sources_sha256": "b28fb830705592104d9060341445215e177215e2229344586e1bd46295b49c45",
-    "kv_migration": {"gather": 43019354439, "scatter": 43019351623},
+    "copy_sources_sha256": "00b987d3399f1c3defa62c12b4a772f1da6ab152a436e23a558731ce7d8ce23e",
+    "kv_migration": {"gather": 43019354439, "scatter": 43019352263},
 }
 
 
