@@ -29,10 +29,10 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per copy launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
 # plain-copy calibration dispatch of the same run; summaries under profiles/).  The figures belong
-# to one version of the copy kernels and of the kernels that build their tables: when copy.hip or
-# split.hip changes they are reported as null.
+# to one version of the copy kernels and of the kernels that build their tables: when copy.hip,
+# split.hip or tile_tables.h changes they are reported as null.
 PMC_TRAFFIC = {
-    "copy_sources_sha256": "00b987d3399f1c3defa62c12b4a772f1da6ab152a436e23a558731ce7d8ce23e",
+    "copy_sources_sha256": "e59f845b6e5797b833f366e73b7e479d9fbc010675158542302e1ffc145fcf17",
     "kv_migration": {"gather": 43019354439, "scatter": 43019352263},
 }
 
@@ -41,8 +41,8 @@ def measured_traffic(workload, kernel):
     import hashlib
     csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_00368_amd", "csrc")
     try:
-        digest = hashlib.sha256(open(os.path.join(csrc, "copy.hip"), "rb").read() +
-                                open(os.path.join(csrc, "split.hip"), "rb").read()).hexdigest()
+        digest = hashlib.sha256(b"".join(open(os.path.join(csrc, f), "rb").read()
+                                         for f in ("copy.hip", "split.hip", "tile_tables.h"))).hexdigest()
     except OSError:
         return None
     if digest != PMC_TRAFFIC["copy_sources_sha256"]:
