@@ -17,6 +17,7 @@
 // floating-point estimate of the cut level, repaired with exact integer comparisons), and a second,
 // fully parallel kernel gives every slot its rank in the merge in closed form (R integer divisions).
 #include "scan.h"
+#include "tile_tables.h"
 #include "wave.h"
 
 namespace tent {
@@ -27,8 +28,9 @@ constexpr uint64_t kNoKey = ~0ull;
 // ---- the chain over requests -------------------------------------------------------------------
 // kWide = 16, 32 or 64: smallest of these that covers the rails; lanes beyond the rails only tag along
 // (uniform decisions are read from lane 0's row).
+// Runs in the first wavefront of a workgroup (lane = threadIdx.x < 64).
 template <int kWide>
-__global__ void __launch_bounds__(64) dispatch_chain_kernel(BatchDev b, RailParams rp, DispatchParams dp)
+__device__ __forceinline__ void dispatch_chain(const BatchDev& b, const RailParams& rp, const DispatchParams& dp)
 {
     const int lane = threadIdx.x;
     const uint64_t S = b.slice_bytes;
@@ -161,6 +163,24 @@ __global__ void __launch_bounds__(64) dispatch_chain_kernel(BatchDev b, RailPara
     }
 }
 
+template <int kWide>
+__global__ void __launch_bounds__(64) dispatch_chain_kernel(BatchDev b, RailParams rp, DispatchParams dp)
+{
+    dispatch_chain<kWide>(b, rp, dp);
+}
+
+// First plan of a batch: the tile tables of the copy kernels are built by the other workgroups of the
+// chain's launch (they depend on the slice table only).
+template <int kWide>
+__global__ void __launch_bounds__(256) dispatch_chain_tables_kernel(BatchDev b, RailParams rp, DispatchParams dp)
+{
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < 64) dispatch_chain<kWide>(b, rp, dp);
+        return;
+    }
+    build_tile_tables(b, blockIdx.x - 1, gridDim.x - 1);
+}
+
 // ---- emit: one lane per pending position ---------------------------------------------------------
 // Position q of the pending list belongs to request j; inside the request the lane takes slot
 // number t = q - (first pending position of j) in rail-major order, i.e. slot k of rail d, computes
@@ -228,16 +248,24 @@ __global__ void __launch_bounds__(256) pending_list_kernel(BatchDev b)
 
 }  // namespace
 
-hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, hipStream_t s)
+hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, bool build_tables,
+                           hipStream_t s)
 {
     hipError_t e = exclusive_scan(NotDone{b.s_state}, b.n_slices, b.scan_tmp, b.scan_partials, s);
     if (e != hipSuccess) return e;
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(pending_list_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b);
-    if (rp.n_rails <= 16)      hipLaunchKernelGGL(dispatch_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, dp);
-    else if (rp.n_rails <= 32) hipLaunchKernelGGL(dispatch_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, dp);
-    else                       hipLaunchKernelGGL(dispatch_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, dp);
+    if (build_tables) {
+        const dim3 grid(1 + tile_table_blocks(b)), block(256);
+        if (rp.n_rails <= 16)      hipLaunchKernelGGL(dispatch_chain_tables_kernel<16>, grid, block, 0, s, b, rp, dp);
+        else if (rp.n_rails <= 32) hipLaunchKernelGGL(dispatch_chain_tables_kernel<32>, grid, block, 0, s, b, rp, dp);
+        else                       hipLaunchKernelGGL(dispatch_chain_tables_kernel<64>, grid, block, 0, s, b, rp, dp);
+    } else {
+        if (rp.n_rails <= 16)      hipLaunchKernelGGL(dispatch_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, dp);
+        else if (rp.n_rails <= 32) hipLaunchKernelGGL(dispatch_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, dp);
+        else                       hipLaunchKernelGGL(dispatch_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, dp);
+    }
     hipLaunchKernelGGL(dispatch_emit_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, rp, dp);
     return hipGetLastError();
 }

@@ -627,7 +627,8 @@ int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state*
     HIP_TRY(order_after_execute_bookkeeping(*b, s));
     dp.all_high = priority ? 0u : 1u;
     if (priority) HIP_TRY(hipMemcpyAsync(d.priority, priority, d.n_desc, hipMemcpyHostToDevice, s));
-    if (!b->planned) {
+    const bool first_plan = !b->planned;
+    if (first_plan) {
         {
             StageTimer t(ctx, TENT_T_EXTENT_SCAN, s);
             HIP_TRY(launch_extent_scan(d.src_ext, d.n_src_ext, d.src_pre, d.scan_partials, s));
@@ -640,12 +641,12 @@ int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state*
         {
             StageTimer t(ctx, TENT_T_EXPAND, s);
             HIP_TRY(launch_expand(d, s));
-            HIP_TRY(launch_tile_tables(d, s));
+            HIP_TRY(launch_tile_tables_prepare(d, s));      // the tables themselves: beside the chain, in its launch
         }
     }
     {
         StageTimer t(ctx, TENT_T_BIND, s);
-        HIP_TRY(launch_dispatch(d, rp, dp, s));
+        HIP_TRY(launch_dispatch(d, rp, dp, first_plan, s));
     }
     b->planned = true;
     b->bound_hint = b->dev.n_slices;

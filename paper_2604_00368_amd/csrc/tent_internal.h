@@ -199,7 +199,8 @@ hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint3
                                   uint32_t slots, uint8_t* arena, hipStream_t s);
 hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t chunk_bytes, hipStream_t s);
 hipError_t launch_mark_done_bounded(const BatchDev& b, hipStream_t s);
-hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, hipStream_t s);
+hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, bool build_tables,
+                           hipStream_t s);
 hipError_t launch_tile_tables(const BatchDev& b, hipStream_t s);
 hipError_t launch_tile_tables_prepare(const BatchDev& b, hipStream_t s);   // what the builders need when they run inside the chain launch
 hipError_t launch_finalize(const BatchDev& b, uint8_t* arena, bool compact, uint64_t max_tiles, hipStream_t s);
