@@ -57,6 +57,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="kv_migration",
                     choices=["tiny", "kv_migration", "rl_params", "many_small", "many_small_x6", "kv_skewed"])
+    ap.add_argument("--placement", default="regions", choices=["regions", "plain"],
+                    help="regions: the pools are carved from one reservation so that the read side and the write side of "
+                         "either copy lie in different regions of the device memory, found by measurement (default); "
+                         "plain: three ordinary allocations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial-binding", action="store_true")
     ap.add_argument("--headline-only", action="store_true",
@@ -155,9 +159,13 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = make_workload(args.workload)
-    src = W.fill_torch(w, 0, dev)
-    dst = torch.zeros(w.seg_bytes[1], dtype=torch.uint8, device=dev)
-    arena = torch.empty(w.staging_bytes, dtype=torch.uint8, device=dev)
+    # The pools: by default carved from one reservation so that the read side and the write side of either copy
+    # lie in different regions of the device memory (placement.py: what the regions are, how they are found).
+    from paper_2604_00368_amd import placement
+    src, arena, dst, layout = placement.place_pools(dev, w.seg_bytes[0], w.staging_bytes, w.seg_bytes[1],
+                                                    mode=args.placement)
+    W.fill_torch(w, 0, dev, out=src)
+    dst.zero_()
     stream = torch.cuda.current_stream(dev)
     flags = T.TENT_FLAG_PROFILE | (T.TENT_FLAG_SERIAL_BINDING if args.serial_binding else 0)
     ctx = T.tent_create(w.slice_bytes, arena.data_ptr(), arena.numel(), flags)
@@ -446,7 +454,12 @@ def main():
                    "n_extents": int(w.src_ext.shape[0]), "n_slices": n_slices, "slice_bytes": w.slice_bytes,
                    "n_rails": int(w.rails.shape[0]), "binding": "serial" if args.serial_binding else "default",
                    "streams": "single" if args.single_stream else
-                              "two: plan of step k+1 overlaps execute of step k; every step plans and executes its own batch"},
+                              "two: plan of step k+1 overlaps execute of step k; every step plans and executes its own batch",
+                   "placement": {"mode": layout.mode, "note": layout.note,
+                                 "reserved_GiB": round(layout.reserved_bytes / 2**30, 1),
+                                 "region_of_each_%d_GiB_chunk" % (placement.CHUNK >> 30): "".join(str(x) for x in layout.labels),
+                                 "offsets_GiB": [round(o / 2**30, 2) for o in layout.offsets],
+                                 "probes": layout.probes}},
         "ms_per_step_single_stream": round(elapsed_single * 1e3 / args.steps, 4),
         "ms_per_step_two_streams": round(elapsed_piped * 1e3 / args.steps, 4),
         "ms_per_step_two_plan_streams": None if elapsed_deep is None else round(elapsed_deep * 1e3 / args.steps, 4),

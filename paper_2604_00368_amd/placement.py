@@ -1,0 +1,205 @@
+"""Where the byte pools of a transfer engine sit in device memory.
+
+Measured on MI355X (288 GiB of HBM3E): device memory behaves as three regions of 96 GiB, and a
+copy kernel whose read side and write side lie in the same region runs 4-9 % slower than one that
+reads from one region and writes to another (20 GiB gathered from 32 KiB pages in random order:
+7.2 ms when the source pool and the staging arena share the first region, 6.5 ms when they do
+not; contiguous copies differ by 2 %).  Which region an address belongs to is a property of the
+physical address.  Allocations made one after the other on an idle device come out of the same
+region, so three pools of 20 GiB allocated in the ordinary way all share one.  Nothing in the
+copy kernels can make up for that; the remedy is a layout decision of the caller, who owns the
+pools: gather should read one region and write another, and so should scatter.
+
+The runtime does not tell physical addresses, and a large allocation is not laid out in address
+order (a 212 GiB allocation was found to be made of five pieces from the three regions in the
+order 1, 2, 3, 1, 2).  So the layout is found by measurement: reserve most of the device in one
+allocation, cut it into chunks, and time a small gather (random 32 KiB pages of one chunk into
+another chunk, through the engine itself) for pairs of chunks -- same-region pairs are 6-7 %
+slower than the others, far outside the noise of 0.5 % -- which labels every chunk with its
+region after about sixty such probes (well under a second).  The pools are then carved from runs
+of chunks with one label: source pool and staging arena in different regions, staging arena and
+destination pool in different regions.
+
+The engine itself takes the pools as plain device pointers and does not care where they came
+from; the reservation stays alive as long as any pool carved from it does.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+GiB = 1 << 30
+CHUNK = 8 * GiB          # granularity of the region map
+PROBE = 2 * GiB          # bytes a probe moves (from the start of one chunk to the start of another)
+SAME_REGION_RATIO = 1.032   # a pair this much slower than the fastest pair seen shares a region
+
+
+@dataclass
+class Layout:
+    mode: str                       # "regions" (pools carved by measured region) or "plain" (ordinary allocations)
+    note: str
+    reserved_bytes: int = 0
+    chunk_bytes: int = 0
+    labels: list = field(default_factory=list)      # region label of every chunk of the reservation
+    offsets: tuple = ()                             # byte offsets of (src, arena, dst) inside the reservation
+    probes: int = 0
+
+
+def label_chunks(n_chunks: int, pair_ms, ratio: float = SAME_REGION_RATIO):
+    """Region label (0, 1, ...) for each of n_chunks chunks.  pair_ms(i, j) times one probe that
+    reads chunk i and writes chunk j; pairs in the same region take `ratio` times the fastest pair
+    seen or longer.  Returns (labels, number of probes)."""
+    labels = [-1] * n_chunks
+    fastest = None
+    probes = 0
+    next_label = 0
+    for i in range(n_chunks):
+        if labels[i] != -1:
+            continue
+        labels[i] = next_label
+        todo = [j for j in range(i + 1, n_chunks) if labels[j] == -1]
+        times = {}
+        for j in todo:
+            times[j] = pair_ms(i, j)
+            probes += 1
+            fastest = times[j] if fastest is None else min(fastest, times[j])
+        for j in todo:
+            if times[j] >= ratio * fastest:
+                labels[j] = next_label
+        next_label += 1
+    return labels, probes
+
+
+def uniform_runs(labels):
+    """Maximal runs of equal labels as (first chunk, number of chunks, label)."""
+    runs = []
+    for k, lab in enumerate(labels):
+        if runs and runs[-1][2] == lab and runs[-1][0] + runs[-1][1] == k:
+            runs[-1] = (runs[-1][0], runs[-1][1] + 1, lab)
+        else:
+            runs.append((k, 1, lab))
+    return runs
+
+
+def choose_windows(labels, chunk_bytes: int, probe_bytes: int, sizes):
+    """Byte offsets for pools of `sizes` = (src, arena, dst) bytes, each inside a run of chunks with one
+    label, arena in another region than src and dst in another region than arena (and, if possible,
+    than src).  Only the first `probe_bytes` of a chunk are known to carry its label, so a pool must
+    end within the probed part of its run's last chunk.  Returns None when no such choice exists."""
+    runs = uniform_runs(labels)
+
+    def fits(run, nbytes, taken):
+        first, count, _ = run
+        lo = first * chunk_bytes
+        for t_lo, t_hi in taken:                      # a run may host two pools, one after the other
+            if t_lo < (first + count) * chunk_bytes and t_hi > lo:
+                lo = max(lo, (t_hi + chunk_bytes - 1) // chunk_bytes * chunk_bytes)
+        hi_ok = (first + count - 1) * chunk_bytes + probe_bytes
+        return lo if lo + nbytes <= hi_ok else None
+
+    best = None
+    for ra in runs:                                   # arena first: it is the partner of both others
+        o_arena = fits(ra, sizes[1], [])
+        if o_arena is None:
+            continue
+        taken_a = [(o_arena, o_arena + sizes[1])]
+        for rs in runs:
+            if rs[2] == ra[2]:
+                continue
+            o_src = fits(rs, sizes[0], taken_a)
+            if o_src is None:
+                continue
+            taken_s = taken_a + [(o_src, o_src + sizes[0])]
+            for rd in runs:
+                if rd[2] == ra[2]:
+                    continue
+                o_dst = fits(rd, sizes[2], taken_s)
+                if o_dst is None:
+                    continue
+                score = 1 if rd[2] != rs[2] else 0    # three different regions preferred
+                if best is None or score > best[0]:
+                    best = (score, (o_src, o_arena, o_dst))
+                if score == 1:
+                    return best[1]
+    return None if best is None else best[1]
+
+
+def _probe_factory(block, chunk_bytes, probe_bytes):
+    """pair_ms(i, j) for label_chunks: a gather of probe_bytes from shuffled 32 KiB pages at the start
+    of chunk i into a staging arena at the start of chunk j, timed by the engine's own stage timers."""
+    import torch
+    from . import binding as T
+    from . import workloads as W
+    w = W.sweep(256 << 10, True, payload=probe_bytes)
+    if w.staging_bytes > chunk_bytes or max(w.seg_bytes) > chunk_bytes:
+        raise ValueError("probe does not fit a chunk")
+    stream = torch.cuda.current_stream(block.device)
+    base = block.data_ptr()
+
+    def pair_ms(i, j):
+        src = base + i * chunk_bytes
+        arena = base + j * chunk_bytes
+        ctx = T.tent_create(w.slice_bytes, arena, w.staging_bytes, T.TENT_FLAG_PROFILE | T.TENT_FLAG_SKIP_OVERLAP_CHECK)
+        try:
+            T.tent_register_segment(ctx, src, w.seg_bytes[0])
+            T.tent_register_segment(ctx, src, w.seg_bytes[1])          # the scatter goes back where it came from
+            h = T.tent_declare(ctx, w.src_ptr, w.src_ext, w.dst_ptr, w.dst_ext)
+            best = None
+            for _ in range(2):
+                T.tent_reset(ctx, h, stream)
+                T.tent_plan(ctx, h, w.rails, want_info=False, stream=stream)
+                torch.cuda.synchronize(block.device)
+                T.tent_get_timings(ctx)
+                T.tent_execute(ctx, h, stream)
+                torch.cuda.synchronize(block.device)
+                ms = T.tent_get_timings(ctx)["gather"][0]
+                best = ms if best is None else min(best, ms)
+            return best
+        finally:
+            T.tent_destroy(ctx)
+    return pair_ms
+
+
+def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: str = "regions",
+                keep_free: int = 24 * GiB, chunk_bytes: int = CHUNK, probe_bytes: int = PROBE, reserve_bytes=None):
+    """Allocate the three pools on `device` (uint8 tensors).  Returns (src, arena, dst, layout).
+
+    mode "regions": reserve the device memory but `keep_free` bytes (or `reserve_bytes`), measure the
+    region of every chunk and carve the pools as the module's header describes; falls back to
+    ordinary allocations (and says so in the layout's note) when the reservation fails, when the
+    measurement finds one region only, or when no placement exists.
+    mode "plain": three ordinary allocations."""
+    import torch
+    if mode not in ("regions", "plain"):
+        raise ValueError(f"unknown placement mode {mode!r}")
+    lay = Layout("plain", "ordinary allocations")
+    if mode == "regions":
+        free, _total = torch.cuda.mem_get_info(device)
+        want = (free - keep_free if reserve_bytes is None else reserve_bytes) // chunk_bytes * chunk_bytes
+        block = None
+        if want < src_bytes + arena_bytes + dst_bytes or want < 2 * chunk_bytes:
+            lay.note = "not enough free device memory for a reservation"
+        else:
+            try:
+                block = torch.empty(want, dtype=torch.uint8, device=device)
+            except RuntimeError as exc:                   # out of memory
+                lay.note = f"reservation failed ({type(exc).__name__})"
+        if block is not None:
+            n_chunks = want // chunk_bytes
+            labels, probes = label_chunks(n_chunks, _probe_factory(block, chunk_bytes, probe_bytes))
+            offs = choose_windows(labels, chunk_bytes, probe_bytes, (src_bytes, arena_bytes, dst_bytes))
+            if offs is None:
+                lay.note = ("one region found: nothing to choose" if len(set(labels)) < 2
+                            else "no placement with the partners in different regions")
+                del block
+                torch.cuda.empty_cache()
+            else:
+                lay = Layout("regions", "pools carved from one reservation by measured region: source and staging arena "
+                             "in different regions, staging arena and destination in different regions",
+                             want, chunk_bytes, labels, offs, probes)
+                o_src, o_arena, o_dst = offs
+                return (block[o_src:o_src + src_bytes], block[o_arena:o_arena + arena_bytes],
+                        block[o_dst:o_dst + dst_bytes], lay)
+    src = torch.empty(src_bytes, dtype=torch.uint8, device=device)
+    dst = torch.empty(dst_bytes, dtype=torch.uint8, device=device)
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device=device)
+    return src, arena, dst, lay

@@ -383,13 +383,16 @@ def fill_numpy(w: Workload, which: int = SRC_SEG) -> np.ndarray:
     return (vals.view(np.uint32) >> 16).astype(np.uint16).view(np.uint8)   # bf16 bit patterns
 
 
-def fill_torch(w: Workload, which: int, device, chunk_bytes: int = 1 << 30):
-    """Device byte pool for one segment, filled in place by a seeded torch generator."""
+def fill_torch(w: Workload, which: int, device, chunk_bytes: int = 1 << 30, out=None):
+    """Device byte pool for one segment, filled in place by a seeded torch generator (`out`: a uint8
+    tensor of the segment's size to fill instead of a new allocation)."""
     import torch
     n = w.seg_bytes[which]
     g = torch.Generator(device=device)
     g.manual_seed(w.seed * 7919 + which)
-    buf = torch.empty(n, dtype=torch.uint8, device=device)
+    if out is not None and (out.dtype != torch.uint8 or out.numel() != n):
+        raise ValueError("out must be a uint8 tensor of the segment's size")
+    buf = torch.empty(n, dtype=torch.uint8, device=device) if out is None else out
     for lo in range(0, n, chunk_bytes):
         hi = min(n, lo + chunk_bytes)
         if w.fill == "u8" or (hi - lo) % 2:

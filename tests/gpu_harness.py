@@ -11,22 +11,33 @@ from paper_2604_00368_amd import workloads as W
 class Engine:
     """Device pools + one engine context for one workload (torch only provides memory and the stream)."""
 
-    def __init__(self, w, src_host=None, dst_host=None, flags=0, device="cuda:0", arena_skew=0, arena_bytes=None):
+    def __init__(self, w, src_host=None, dst_host=None, flags=0, device="cuda:0", arena_skew=0, arena_bytes=None,
+                 pools=None):
         self.w = w
         self.dev = torch.device(device)
         torch.cuda.set_device(self.dev)
-        if src_host is not None:
+        if pools is not None:                       # (src, arena, dst) allocated by the caller; src is filled here
+            self.src, arena, self.dst = pools
+            W.fill_torch(w, 0, self.dev, out=self.src)
+            self.dst.zero_()
+            arena.zero_()
+        elif src_host is not None:
             self.src = torch.from_numpy(src_host).to(self.dev)
         else:
             self.src = W.fill_torch(w, 0, self.dev)
-        if dst_host is not None:
+        if pools is not None:
+            pass
+        elif dst_host is not None:
             self.dst = torch.from_numpy(dst_host).to(self.dev)
         else:
             self.dst = torch.zeros(w.seg_bytes[1], dtype=torch.uint8, device=self.dev)
         # arena_skew > 0 hands the engine a staging arena that starts at an odd address
         n_arena = w.staging_bytes if arena_bytes is None else arena_bytes
-        self.arena_full = torch.zeros(n_arena + arena_skew, dtype=torch.uint8, device=self.dev)
-        self.arena = self.arena_full[arena_skew:]
+        if pools is not None:
+            self.arena_full = self.arena = arena
+        else:
+            self.arena_full = torch.zeros(n_arena + arena_skew, dtype=torch.uint8, device=self.dev)
+            self.arena = self.arena_full[arena_skew:]
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = T.tent_create(w.slice_bytes, self.arena.data_ptr(), self.arena.numel(), flags)
         s0 = T.tent_register_segment(self.ctx, self.src.data_ptr(), self.src.numel())

@@ -111,6 +111,39 @@ def test_full_size_config(H, oracle, name):
         torch.cuda.empty_cache()
 
 
+def test_full_size_config_in_the_benchmarks_pool_layout(H, oracle):
+    """Config 2 with the pools where bench.py puts them: carved from one reservation by measured region."""
+    from paper_2604_00368_amd import binding as T
+    from paper_2604_00368_amd import placement
+    print("full-size kv_migration, pools carved by region", flush=True)
+    w = full_config("kv_migration")
+    gc.collect()
+    torch.cuda.empty_cache()
+    dev = torch.device("cuda:0")
+    src, arena, dst, lay = placement.place_pools(dev, w.seg_bytes[0], w.staging_bytes, w.seg_bytes[1])
+    print("  layout:", lay.mode, lay.note, "".join(str(x) for x in lay.labels), [o >> 30 for o in lay.offsets], flush=True)
+    if lay.mode != "regions":
+        del src, arena, dst
+        pytest.skip("no region layout here: " + lay.note)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    b = oracle.bind(s.len, w.rails)
+    eng = H.Engine(w, flags=T.TENT_FLAG_PROFILE, pools=(src, arena, dst))
+    try:
+        eng.declare()
+        st, _ = eng.plan(want_info=False)
+        assert st == 0
+        eng.execute()
+        H.assert_plan_equal(eng.table(), s, b)
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        device_definition_check(w, eng.src, eng.dst)
+        sampled_bytes_check(oracle, w, s, b, eng, pick_sample(w, 8, seed=5))
+    finally:
+        eng.close()
+        del eng, src, arena, dst
+        gc.collect()
+        torch.cuda.empty_cache()
+
+
 def test_full_size_replanning(H, oracle):
     from paper_2604_00368_amd import binding as T
     print("full-size replanning", flush=True)
