@@ -27,7 +27,7 @@ EXPORTS = ["tent_create", "tent_destroy", "tent_register_segment", "tent_declare
            "tent_sim_advance", "tent_sim_latency", "tent_update_bandwidth", "tent_get_latencies", "tent_execute", "tent_poll", "tent_reset", "tent_slice_count",
            "tent_get_plan", "tent_get_timings", "tent_release", "tent_strerror",
            "tent_sim_fail", "tent_get_retries", "tent_monitor_init", "tent_monitor_update",
-           "tent_plan_dispatch", "tent_get_modes", "tent_execute_bounded"]
+           "tent_plan_dispatch", "tent_get_modes", "tent_execute_bounded", "tent_probe_copy"]
 
 
 class tent_config(C.Structure):
@@ -96,6 +96,8 @@ def lib():
         L.tent_get_plan.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
         L.tent_get_timings.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_uint32)]
         L.tent_release.argtypes = [C.c_void_p, C.c_uint64]
+        L.tent_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p,
+                                      C.POINTER(C.c_float)]
         L.tent_plan_dispatch.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
                                          C.POINTER(tent_dispatch_info), C.c_void_p]
         L.tent_get_modes.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
@@ -286,6 +288,15 @@ def tent_get_timings(ctx) -> dict:
     cnt = (C.c_uint32 * len(TENT_T_NAMES))()
     _check(lib().tent_get_timings(ctx, ms, cnt), "tent_get_timings")
     return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(TENT_T_NAMES)}
+
+
+def tent_probe_copy(read_window: int, write_window: int, nbytes: int, page_bytes: int = 32768, repeats: int = 2,
+                    stream=None) -> float:
+    """Shortest of `repeats` timed probe copies (ms) from one device window to another."""
+    ms = C.c_float(0)
+    _check(lib().tent_probe_copy(C.c_void_p(read_window), C.c_void_p(write_window), nbytes, page_bytes, repeats,
+                                 _stream(stream), C.byref(ms)), "tent_probe_copy")
+    return float(ms.value)
 
 
 def tent_release(ctx, batch: int):

@@ -13,8 +13,8 @@ pools: gather should read one region and write another, and so should scatter.
 The runtime does not tell physical addresses, and a large allocation is not laid out in address
 order (a 212 GiB allocation was found to be made of five pieces from the three regions in the
 order 1, 2, 3, 1, 2).  So the layout is found by measurement: reserve most of the device in one
-allocation, cut it into chunks, and time a small gather (random 32 KiB pages of one chunk into
-another chunk, through the engine itself) for pairs of chunks -- same-region pairs are 6-7 %
+allocation, cut it into chunks, and time a small probe copy (32 KiB pages of one chunk in a
+scattered order into another chunk: tent_probe_copy) for pairs of chunks -- same-region pairs are 6-7 %
 slower than the others, far outside the noise of 0.5 % -- which labels every chunk with its
 region after about sixty such probes (well under a second).  The pools are then carved from runs
 of chunks with one label: source pool and staging arena in different regions, staging arena and
@@ -124,38 +124,17 @@ def choose_windows(labels, chunk_bytes: int, probe_bytes: int, sizes):
 
 
 def _probe_factory(block, chunk_bytes, probe_bytes):
-    """pair_ms(i, j) for label_chunks: a gather of probe_bytes from shuffled 32 KiB pages at the start
-    of chunk i into a staging arena at the start of chunk j, timed by the engine's own stage timers."""
+    """pair_ms(i, j) for label_chunks: the library's timed probe copy (32 KiB pages of the start of chunk i
+    in a scattered order, written front to back to the start of chunk j)."""
     import torch
     from . import binding as T
-    from . import workloads as W
-    w = W.sweep(256 << 10, True, payload=probe_bytes)
-    if w.staging_bytes > chunk_bytes or max(w.seg_bytes) > chunk_bytes:
-        raise ValueError("probe does not fit a chunk")
+    if probe_bytes > chunk_bytes or probe_bytes & (probe_bytes - 1):
+        raise ValueError("the probe must be a power of two and fit a chunk")
     stream = torch.cuda.current_stream(block.device)
     base = block.data_ptr()
 
     def pair_ms(i, j):
-        src = base + i * chunk_bytes
-        arena = base + j * chunk_bytes
-        ctx = T.tent_create(w.slice_bytes, arena, w.staging_bytes, T.TENT_FLAG_PROFILE | T.TENT_FLAG_SKIP_OVERLAP_CHECK)
-        try:
-            T.tent_register_segment(ctx, src, w.seg_bytes[0])
-            T.tent_register_segment(ctx, src, w.seg_bytes[1])          # the scatter goes back where it came from
-            h = T.tent_declare(ctx, w.src_ptr, w.src_ext, w.dst_ptr, w.dst_ext)
-            best = None
-            for _ in range(2):
-                T.tent_reset(ctx, h, stream)
-                T.tent_plan(ctx, h, w.rails, want_info=False, stream=stream)
-                torch.cuda.synchronize(block.device)
-                T.tent_get_timings(ctx)
-                T.tent_execute(ctx, h, stream)
-                torch.cuda.synchronize(block.device)
-                ms = T.tent_get_timings(ctx)["gather"][0]
-                best = ms if best is None else min(best, ms)
-            return best
-        finally:
-            T.tent_destroy(ctx)
+        return T.tent_probe_copy(base + i * chunk_bytes, base + j * chunk_bytes, probe_bytes, 32768, 2, stream)
     return pair_ms
 
 

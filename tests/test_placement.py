@@ -92,3 +92,31 @@ def test_carved_pools_run_the_engine(oracle):
         assert np.array_equal(eng.arena.cpu().numpy(), stg_want)
     s2, a2, d2, lay2 = P.place_pools(dev, 1 << 20, 1 << 20, 1 << 20, mode="plain")
     assert lay2.mode == "plain" and s2.numel() == a2.numel() == d2.numel() == 1 << 20
+
+
+@pytest.mark.gpu
+def test_probe_copy_moves_every_page_once():
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2604_00368_amd import binding as T
+    dev = torch.device("cuda:0")
+    page, n_pages = 32768, 256
+    g = torch.Generator(device=dev)
+    g.manual_seed(12)
+    a = torch.randint(0, 256, (page * n_pages,), dtype=torch.uint8, device=dev, generator=g)
+    b = torch.zeros_like(a)
+    ms = T.tent_probe_copy(a.data_ptr(), b.data_ptr(), a.numel(), page, 2, torch.cuda.current_stream(dev))
+    assert ms > 0
+    torch.cuda.synchronize(dev)
+    av, bv = a.view(n_pages, page), b.view(n_pages, page)
+    mult = (0x9E3779B97F4A7C15 | 1) % n_pages                  # the page permutation is k -> k * odd mod 2^m
+    perm = (torch.arange(n_pages, device=dev) * mult) % n_pages
+    assert sorted(perm.tolist()) == list(range(n_pages))
+    assert torch.equal(bv, av[perm])
+    # argument checks
+    for bad in [dict(nbytes=page * 3), dict(page_bytes=5000), dict(page_bytes=2048), dict(repeats=0)]:
+        kw = dict(nbytes=a.numel(), page_bytes=page, repeats=1)
+        kw.update(bad)
+        with pytest.raises(T.TentError):
+            T.tent_probe_copy(a.data_ptr(), b.data_ptr(), kw["nbytes"], kw["page_bytes"], kw["repeats"])
