@@ -108,7 +108,7 @@ def cpu_baseline(name):
     t_plan = t_exec = 0.0
     n_slices = 0
     t_begin = time.perf_counter()
-    while reps < 1 or (time.perf_counter() - t_begin < 10.0 and reps < 20):
+    while reps < 1 or (time.perf_counter() - t_begin < 10.0 and reps < 80):
         t0 = time.perf_counter()
         s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
         b = oracle.bind(s.len, w.rails)
