@@ -71,11 +71,14 @@ __global__ void __launch_bounds__(256) declare_is_dst_kernel(uint64_t n_dst, uin
 }
 
 __global__ void __launch_bounds__(256) declare_order_kernel(uint64_t n_dst, uint64_t n, const uint32_t* vals,
-                                                            const uint32_t* pos, uint32_t* order)
+                                                            const uint32_t* pos, uint32_t* order, uint32_t* rank)
 {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t p = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n; p += stride)
-        if (vals[p] < n_dst) order[pos[p]] = vals[p];
+        if (vals[p] < n_dst) {
+            order[pos[p]] = vals[p];
+            if (rank) rank[vals[p]] = pos[p];              // the inverse: position of every extent in address order
+        }
 }
 
 __global__ void declare_clear_kernel(uint32_t* overlap) { *overlap = 0; }
@@ -88,12 +91,13 @@ uint32_t grid_for(uint64_t n)
 
 }  // namespace
 
-// Fills order_out[n_dst] with destination extent indices in ascending address and, when `check`
-// is set, *overlap_out (host) with 1 if a destination extent overlaps another destination or any
-// source extent.  Synchronous; temporary device memory is allocated and freed inside.
+// Fills order_out[n_dst] with destination extent indices in ascending address, rank_out[n_dst] (if
+// not null) with the inverse (position of every extent in that order) and, when `check` is set,
+// *overlap_out (host) with 1 if a destination extent overlaps another destination or any source
+// extent.  Synchronous; temporary device memory is allocated and freed inside.
 hipError_t device_order_destinations(const tent_extent* dst_ext, uint64_t n_dst, const tent_extent* src_ext,
                                      uint64_t n_src, const uint64_t* seg_base, bool check, uint32_t* order_out,
-                                     uint32_t* overlap_out, hipStream_t s)
+                                     uint32_t* rank_out, uint32_t* overlap_out, hipStream_t s)
 {
     const uint64_t n = n_dst + (check ? n_src : 0);
     *overlap_out = 0;
@@ -149,7 +153,7 @@ hipError_t device_order_destinations(const tent_extent* dst_ext, uint64_t n_dst,
         bytes = lib_bytes;
         e = rocprim::exclusive_scan(lib_tmp, bytes, flag, pos, 0u, n, rocprim::plus<uint32_t>(), s);
         if (e == hipSuccess)
-            hipLaunchKernelGGL(declare_order_kernel, dim3(g), dim3(256), 0, s, n_dst, n, vals, pos, order_out);
+            hipLaunchKernelGGL(declare_order_kernel, dim3(g), dim3(256), 0, s, n_dst, n, vals, pos, order_out, rank_out);
     }
     if (e == hipSuccess) e = hipGetLastError();
     if (e == hipSuccess) e = hipMemcpyAsync(overlap_out, overlap, sizeof(uint32_t), hipMemcpyDeviceToHost, s);

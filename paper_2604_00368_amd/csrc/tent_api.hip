@@ -376,6 +376,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     const uint64_t scan_n = std::max<uint64_t>(std::max(ns, nd), std::max<uint64_t>(n_slices, n_desc));
     BatchDev* self_dev = nullptr;
     uint32_t* order_dev = nullptr;
+    uint32_t* rank_dev = nullptr;
     Carver cv;
     try {
         cv.want(&sp, (uint64_t)n_desc + 1);
@@ -409,6 +410,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
         cv.want(&d.run_T, (uint64_t)d.run_capacity * d.run_stride);
         cv.want(&d.run_K, (uint64_t)d.run_capacity * d.run_stride);
         cv.want(&order_dev, nd);
+        cv.want(&rank_dev, nd);
         if (d.n_sc_tiles) {
             cv.want(&d.ord_pre, nd + 1);
             cv.want(&d.ga_src, d.n_sc_tiles);
@@ -448,6 +450,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (rc != TENT_OK) { free_batch(b); return rc; }
     d.src_ptr = sp; d.dst_ptr = dp; d.src_ext = se; d.dst_ext = de;
     d.dst_order = order_dev;
+    d.dst_rank = rank_dev;
     d.self = self_dev;
 
     if (hipMemcpy(sp, src_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
@@ -466,7 +469,7 @@ int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     const bool check = !(ctx->cfg.flags & TENT_FLAG_SKIP_OVERLAP_CHECK);
     if (check || d.n_sc_tiles) {
         uint32_t overlap = 0;
-        if (device_order_destinations(de, nd, se, ns, ctx->seg_base_dev, check, order_dev, &overlap, nullptr) !=
+        if (device_order_destinations(de, nd, se, ns, ctx->seg_base_dev, check, order_dev, rank_dev, &overlap, nullptr) !=
             hipSuccess) {
             (void)hipGetLastError();
             free_batch(b);

@@ -137,6 +137,7 @@ struct BatchDev {
     // payload in tiles: source bytes in declaration order (gather: each rail region is written front
     // to back) and destination bytes in ascending device address (scatter: sequential writes).
     const uint32_t* dst_order;     // [n_dst_ext] destination extents sorted by device address
+    const uint32_t* dst_rank;      // [n_dst_ext] the inverse: position of every destination extent in that order
     uint64_t* ord_pre;             // [n_dst_ext+1] exclusive prefix of their lengths in that order
     uint64_t  n_sc_tiles;          // payload / tile_bytes
     uint64_t* ga_src;              // [n_sc_tiles] gather: source address of the tile
@@ -218,6 +219,6 @@ uint64_t scan_partials_capacity(uint64_t n);
 
 hipError_t device_order_destinations(const tent_extent* dst_ext, uint64_t n_dst, const tent_extent* src_ext,
                                      uint64_t n_src, const uint64_t* seg_base, bool check, uint32_t* order_out,
-                                     uint32_t* overlap_out, hipStream_t s);
+                                     uint32_t* rank_out, uint32_t* overlap_out, hipStream_t s);
 
 }  // namespace tent

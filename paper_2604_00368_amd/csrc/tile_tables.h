@@ -55,57 +55,45 @@ __device__ __forceinline__ void slice_tile_tables(const BatchDev& b, uint64_t vb
     }
 }
 
-// Destination-ordered tiles: tile q covers bytes [q*tile, (q+1)*tile) of the destination extents
-// laid end to end in ascending device address.  For each tile: its destination address, the slice
-// that owns it and its offset inside that slice (independent of the binding).
-__device__ __forceinline__ void scatter_tile_table(const BatchDev& b, uint64_t vb, uint64_t nb)
+// Geometry in which no tile crosses an extent boundary: two enumerations of the payload in tiles.
+//   Source-ordered:      tile q covers bytes [q*tile, (q+1)*tile) of the source extents laid end to end in
+//                        declaration order, i.e. of the transfers' logical bytes one after the other.
+//   Destination-ordered: tile q' covers bytes [q'*tile, (q'+1)*tile) of the destination extents laid end
+//                        to end in ascending device address.
+// For each tile of either enumeration: its address on the paged side, the slice that owns it and its
+// offset inside that slice (independent of the binding).  One thread per (slice, tile of the slice):
+// the slice table already holds the first source and destination extent of the slice, so each side
+// costs a search over the few extents of one slice; the tile's place in the destination order
+// follows from the rank of its extent in that order and the prefix of the extent lengths.
+__device__ __forceinline__ void ordered_tile_tables(const BatchDev& b, uint64_t vb, uint64_t nb)
 {
+    const uint32_t tps = b.tiles_per_slice;
+    const uint32_t tile = b.tile_bytes;
+    const uint64_t n = b.n_slices * (uint64_t)tps;
     const uint64_t stride = nb * blockDim.x;
-    for (uint64_t q = vb * blockDim.x + threadIdx.x; q < b.n_sc_tiles; q += stride) {
-        const uint64_t at = q * b.tile_bytes;
-        const uint64_t r = last_not_above(b.ord_pre, 0, b.n_dst_ext, at);
-        const uint32_t e = b.dst_order[r];
-        const uint64_t within = at - b.ord_pre[r];
-        const tent_extent ex = b.dst_ext[e];
-        // owning transfer: last j with dst_ptr[j] <= e
-        uint32_t lo = 0, hi = b.n_desc;
-        while (hi - lo > 1) {
-            const uint32_t mid = lo + ((hi - lo) >> 1);
-            if (b.dst_ptr[mid] <= e) lo = mid; else hi = mid;
-        }
-        const uint64_t off = b.dst_pre[e] + within - b.dst_pre[b.dst_ptr[lo]];   // offset inside the transfer
-        const uint64_t k = off / b.slice_bytes;
-        b.sc_dst[q] = b.seg_base[ex.seg] + ex.off + within;
-        b.sc_slice[q] = (uint32_t)(b.first[lo] + k);
-        b.sc_x[q] = (uint32_t)(off - k * b.slice_bytes);
-    }
-}
-
-// Source-ordered tiles: tile q covers bytes [q*tile, (q+1)*tile) of the source extents laid end to
-// end in declaration order, i.e. of the transfers' logical bytes one after the other.
-__device__ __forceinline__ void gather_tile_table(const BatchDev& b, uint64_t vb, uint64_t nb)
-{
-    const uint64_t stride = nb * blockDim.x;
-    for (uint64_t q = vb * blockDim.x + threadIdx.x; q < b.n_sc_tiles; q += stride) {
-        const uint64_t at = q * b.tile_bytes;
-        const uint64_t e = last_not_above(b.src_pre, 0, b.n_src_ext, at);
-        const tent_extent ex = b.src_ext[e];
-        uint32_t lo = 0, hi = b.n_desc;                   // owning transfer: last j with src_ptr[j] <= e
-        while (hi - lo > 1) {
-            const uint32_t mid = lo + ((hi - lo) >> 1);
-            if (b.src_ptr[mid] <= e) lo = mid; else hi = mid;
-        }
-        const uint64_t off = at - b.src_pre[b.src_ptr[lo]];
-        const uint64_t k = off / b.slice_bytes;
-        b.ga_src[q] = b.seg_base[ex.seg] + ex.off + (at - b.src_pre[e]);
-        b.ga_slice[q] = (uint32_t)(b.first[lo] + k);
-        b.ga_x[q] = (uint32_t)(off - k * b.slice_bytes);
-        if (b.ga_dst) {                                   // same tile on the destination side
-            const uint64_t dpos = b.dst_pre[b.dst_ptr[lo]] + off;
-            const uint64_t de = last_not_above(b.dst_pre, b.dst_ptr[lo], b.dst_ptr[lo + 1], dpos);
-            const tent_extent dx = b.dst_ext[de];
-            b.ga_dst[q] = b.seg_base[dx.seg] + dx.off + (dpos - b.dst_pre[de]);
-        }
+    for (uint64_t idx = vb * blockDim.x + threadIdx.x; idx < n; idx += stride) {
+        const uint64_t i = idx / tps;
+        const uint64_t x = (idx - i * tps) * tile;                 // byte offset inside the slice
+        if (x >= b.s_len[i]) continue;
+        const uint32_t j = b.s_desc[i];
+        const uint64_t off = b.s_off[i] + x;                       // byte offset inside the transfer
+        const uint64_t s_pos = b.src_pre[b.src_ptr[j]] + off;
+        const uint64_t se = last_not_above(b.src_pre, b.s_src_e0[i], b.src_ptr[j + 1], s_pos);
+        const tent_extent sx = b.src_ext[se];
+        const uint64_t q = s_pos / tile;
+        b.ga_src[q] = b.seg_base[sx.seg] + sx.off + (s_pos - b.src_pre[se]);
+        b.ga_slice[q] = (uint32_t)i;
+        b.ga_x[q] = (uint32_t)x;
+        const uint64_t d_pos = b.dst_pre[b.dst_ptr[j]] + off;
+        const uint64_t de = last_not_above(b.dst_pre, b.s_dst_e0[i], b.dst_ptr[j + 1], d_pos);
+        const tent_extent dx = b.dst_ext[de];
+        const uint64_t within = d_pos - b.dst_pre[de];
+        const uint64_t dst_addr = b.seg_base[dx.seg] + dx.off + within;
+        if (b.ga_dst) b.ga_dst[q] = dst_addr;                      // same tile on the destination side
+        const uint64_t qd = (b.ord_pre[b.dst_rank[de]] + within) / tile;
+        b.sc_dst[qd] = dst_addr;
+        b.sc_slice[qd] = (uint32_t)i;
+        b.sc_x[qd] = (uint32_t)x;
     }
 }
 
@@ -115,15 +103,14 @@ __device__ __forceinline__ void build_tile_tables(const BatchDev& b, uint64_t vb
     if (b.n_sc_tiles == 0) {
         slice_tile_tables(b, vb, nb);
     } else {
-        gather_tile_table(b, vb, nb);
-        scatter_tile_table(b, vb, nb);
+        ordered_tile_tables(b, vb, nb);
     }
 }
 
 // Workgroups of 256 lanes that the table builders are launched with.
 inline uint32_t tile_table_blocks(const BatchDev& b)
 {
-    const uint64_t n = b.n_sc_tiles ? b.n_sc_tiles : b.n_slices * (uint64_t)b.tiles_per_slice;
+    const uint64_t n = b.n_slices * (uint64_t)b.tiles_per_slice;
     const uint64_t blocks = (n + 255) / 256;
     return (uint32_t)(blocks > 65536 ? 65536 : (blocks ? blocks : 1));
 }
