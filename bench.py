@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0
 # to one version of the copy kernels and of the kernels that build their tables: when copy.hip,
 # split.hip or tile_tables.h changes they are reported as null.
 PMC_TRAFFIC = {
-    "copy_sources_sha256": "e59f845b6e5797b833f366e73b7e479d9fbc010675158542302e1ffc145fcf17",
-    "kv_migration": {"gather": 43019358407, "scatter": 43019350215},
+    "copy_sources_sha256": "4d38e225488fae66925b0ef45bc35c69cacd759f2b97e655b5390f95ba29420b",
+    "kv_migration": {"gather": 43019354951, "scatter": 43019352135},
 }
 
 
