@@ -459,7 +459,7 @@ def main():
                                  "reserved_GiB": round(layout.reserved_bytes / 2**30, 1),
                                  "region_of_each_%d_GiB_chunk" % (placement.CHUNK >> 30): "".join(str(x) for x in layout.labels),
                                  "offsets_GiB": [round(o / 2**30, 2) for o in layout.offsets],
-                                 "probes": layout.probes}},
+                                 "probes": layout.probes, "verified": layout.verified}},
         "ms_per_step_single_stream": round(elapsed_single * 1e3 / args.steps, 4),
         "ms_per_step_two_streams": round(elapsed_piped * 1e3 / args.steps, 4),
         "ms_per_step_two_plan_streams": None if elapsed_deep is None else round(elapsed_deep * 1e3 / args.steps, 4),

@@ -29,6 +29,7 @@ from dataclasses import dataclass, field
 
 GiB = 1 << 30
 CHUNK = 8 * GiB          # granularity of the region map
+ALIGN = 2 << 20          # verification probes start on 2 MiB boundaries
 PROBE = 2 * GiB          # bytes a probe moves (from the start of one chunk to the start of another)
 SAME_REGION_RATIO = 1.032   # a pair this much slower than the fastest pair seen shares a region
 
@@ -42,12 +43,13 @@ class Layout:
     labels: list = field(default_factory=list)      # region label of every chunk of the reservation
     offsets: tuple = ()                             # byte offsets of (src, arena, dst) inside the reservation
     probes: int = 0
+    verified: bool = False          # probes between the carved pools themselves (first and last bytes) say "different regions"
 
 
 def label_chunks(n_chunks: int, pair_ms, ratio: float = SAME_REGION_RATIO):
     """Region label (0, 1, ...) for each of n_chunks chunks.  pair_ms(i, j) times one probe that
     reads chunk i and writes chunk j; pairs in the same region take `ratio` times the fastest pair
-    seen or longer.  Returns (labels, number of probes)."""
+    seen or longer.  Returns (labels, number of probes, fastest pair time)."""
     labels = [-1] * n_chunks
     fastest = None
     probes = 0
@@ -66,7 +68,7 @@ def label_chunks(n_chunks: int, pair_ms, ratio: float = SAME_REGION_RATIO):
             if times[j] >= ratio * fastest:
                 labels[j] = next_label
         next_label += 1
-    return labels, probes
+    return labels, probes, fastest
 
 
 def uniform_runs(labels):
@@ -124,8 +126,9 @@ def choose_windows(labels, chunk_bytes: int, probe_bytes: int, sizes):
 
 
 def _probe_factory(block, chunk_bytes, probe_bytes):
-    """pair_ms(i, j) for label_chunks: the library's timed probe copy (32 KiB pages of the start of chunk i
-    in a scattered order, written front to back to the start of chunk j)."""
+    """(pair_ms, window_ms): pair_ms(i, j) for label_chunks is the library's timed probe copy (32 KiB pages of
+    the start of chunk i in a scattered order, written front to back to the start of chunk j); window_ms(a, b)
+    is the same probe between two byte offsets of the reservation."""
     import torch
     from . import binding as T
     if probe_bytes > chunk_bytes or probe_bytes & (probe_bytes - 1):
@@ -133,9 +136,23 @@ def _probe_factory(block, chunk_bytes, probe_bytes):
     stream = torch.cuda.current_stream(block.device)
     base = block.data_ptr()
 
+    def window_ms(read_off, write_off):
+        return T.tent_probe_copy(base + read_off, base + write_off, probe_bytes, 32768, 2, stream)
+
     def pair_ms(i, j):
-        return T.tent_probe_copy(base + i * chunk_bytes, base + j * chunk_bytes, probe_bytes, 32768, 2, stream)
-    return pair_ms
+        return window_ms(i * chunk_bytes, j * chunk_bytes)
+    return pair_ms, window_ms
+
+
+def verify_windows(offsets, sizes, probe_bytes, window_ms, fastest, ratio: float = SAME_REGION_RATIO) -> bool:
+    """Probes between the pools as carved -- source to arena and arena to destination, at the pools' first
+    bytes and at their last -- must all be as fast as pairs from different regions."""
+    (o_src, o_arena, o_dst), (n_src, n_arena, n_dst) = offsets, sizes
+    def last(o, n):
+        return o + (max(n - probe_bytes, 0) // ALIGN) * ALIGN
+    pairs = [(o_src, o_arena), (last(o_src, n_src), last(o_arena, n_arena)),
+             (o_arena, o_dst), (last(o_arena, n_arena), last(o_dst, n_dst))]
+    return all(window_ms(a, b) < ratio * fastest for a, b in pairs)
 
 
 def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: str = "regions",
@@ -164,8 +181,10 @@ def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: 
                 lay.note = f"reservation failed ({type(exc).__name__})"
         if block is not None:
             n_chunks = want // chunk_bytes
-            labels, probes = label_chunks(n_chunks, _probe_factory(block, chunk_bytes, probe_bytes))
-            offs = choose_windows(labels, chunk_bytes, probe_bytes, (src_bytes, arena_bytes, dst_bytes))
+            pair_ms, window_ms = _probe_factory(block, chunk_bytes, probe_bytes)
+            labels, probes, fastest = label_chunks(n_chunks, pair_ms)
+            sizes = (src_bytes, arena_bytes, dst_bytes)
+            offs = choose_windows(labels, chunk_bytes, probe_bytes, sizes)
             if offs is None:
                 lay.note = ("one region found: nothing to choose" if len(set(labels)) < 2
                             else "no placement with the partners in different regions")
@@ -175,6 +194,9 @@ def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: 
                 lay = Layout("regions", "pools carved from one reservation by measured region: source and staging arena "
                              "in different regions, staging arena and destination in different regions",
                              want, chunk_bytes, labels, offs, probes)
+                if min(sizes) >= probe_bytes:
+                    lay.verified = verify_windows(offs, sizes, probe_bytes, window_ms, fastest)
+                    lay.probes += 4
                 o_src, o_arena, o_dst = offs
                 return (block[o_src:o_src + src_bytes], block[o_arena:o_arena + arena_bytes],
                         block[o_dst:o_dst + dst_bytes], lay)

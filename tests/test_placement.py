@@ -19,16 +19,17 @@ def fake_probe(regions, same=0.729, cross=0.683, jitter=0.004, seed=0):
 def test_region_labels_from_pair_times():
     # a reservation made of five pieces from three regions, as found on the device: 1, 2, 3, 1, 2
     regions = [0] * 8 + [1] * 8 + [2] * 4 + [0] * 4 + [1] * 2
-    labels, probes = P.label_chunks(len(regions), fake_probe(regions))
+    labels, probes, fastest = P.label_chunks(len(regions), fake_probe(regions))
+    assert 0.679 <= fastest <= 0.687
     assert labels == regions                      # labels are numbered in order of first appearance
     assert probes == 25 + 13 + 3
     # address-ordered thirds
     regions = [0] * 12 + [1] * 12 + [2] * 8
-    labels, _ = P.label_chunks(len(regions), fake_probe(regions, seed=3))
+    labels, _, _ = P.label_chunks(len(regions), fake_probe(regions, seed=3))
     assert labels == regions
     # one region only: no pair is slower than the fastest by the ratio, so no two chunks are reported as sharing a
     # region, no run is long enough for a pool, and the caller falls back to ordinary allocations
-    labels, _ = P.label_chunks(6, fake_probe([0] * 6))
+    labels, _, _ = P.label_chunks(6, fake_probe([0] * 6))
     assert len(set(labels)) == 6
     assert P.choose_windows(labels, 8 * GiB, 2 * GiB, (20 * GiB, 20 * GiB, 20 * GiB)) is None
 
@@ -51,6 +52,12 @@ def test_windows_keep_partners_in_different_regions():
         assert spans[0][1] <= spans[1][0] and spans[1][1] <= spans[2][0]          # no overlap
         for o, n in zip(offs, sizes):                                            # ends inside the probed part of a chunk
             assert (o + n - 1) % chunk < probe or labels[(o + n - 1) // chunk] == labels[min(len(labels) - 1, (o + n - 1) // chunk + 1)]
+        # the carved pools verify against the same region map, and a pool pushed across a boundary does not
+        chunk_region = lambda off: labels[off // chunk]
+        window_ms = lambda a, b: 0.729 if chunk_region(a) == chunk_region(b) else 0.683
+        assert P.verify_windows(offs, sizes, probe, window_ms, 0.683)
+        bad = (offs[1], offs[1], offs[2])
+        assert not P.verify_windows(bad, sizes, probe, window_ms, 0.683)
     # runs too short for the pools
     assert P.choose_windows([0, 0, 1, 1, 2, 2], chunk, probe, sizes) is None
     # two regions, the second one must host nothing but the arena
