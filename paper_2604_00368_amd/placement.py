@@ -125,10 +125,11 @@ def choose_windows(labels, chunk_bytes: int, probe_bytes: int, sizes):
     return None if best is None else best[1]
 
 
-def _probe_factory(block, chunk_bytes, probe_bytes):
+def _probe_factory(block, chunk_bytes, probe_bytes, repeats):
     """(pair_ms, window_ms): pair_ms(i, j) for label_chunks is the library's timed probe copy (32 KiB pages of
     the start of chunk i in a scattered order, written front to back to the start of chunk j); window_ms(a, b)
-    is the same probe between two byte offsets of the reservation."""
+    is the same probe between two byte offsets of the reservation.  Every probe is the shortest of `repeats`
+    runs: what disturbs a timing (a profiler, another process) only ever makes it longer."""
     import torch
     from . import binding as T
     if probe_bytes > chunk_bytes or probe_bytes & (probe_bytes - 1):
@@ -137,7 +138,7 @@ def _probe_factory(block, chunk_bytes, probe_bytes):
     base = block.data_ptr()
 
     def window_ms(read_off, write_off):
-        return T.tent_probe_copy(base + read_off, base + write_off, probe_bytes, 32768, 2, stream)
+        return T.tent_probe_copy(base + read_off, base + write_off, probe_bytes, 32768, repeats, stream)
 
     def pair_ms(i, j):
         return window_ms(i * chunk_bytes, j * chunk_bytes)
@@ -181,10 +182,19 @@ def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: 
                 lay.note = f"reservation failed ({type(exc).__name__})"
         if block is not None:
             n_chunks = want // chunk_bytes
-            pair_ms, window_ms = _probe_factory(block, chunk_bytes, probe_bytes)
-            labels, probes, fastest = label_chunks(n_chunks, pair_ms)
             sizes = (src_bytes, arena_bytes, dst_bytes)
-            offs = choose_windows(labels, chunk_bytes, probe_bytes, sizes)
+            total_probes = 0
+            for repeats in (3, 8):                        # a second, more patient pass if the first map does not hold up
+                pair_ms, window_ms = _probe_factory(block, chunk_bytes, probe_bytes, repeats)
+                labels, probes, fastest = label_chunks(n_chunks, pair_ms)
+                total_probes += probes
+                offs = choose_windows(labels, chunk_bytes, probe_bytes, sizes)
+                verified = False
+                if offs is not None and min(sizes) >= probe_bytes:
+                    verified = verify_windows(offs, sizes, probe_bytes, window_ms, fastest)
+                    total_probes += 4
+                if offs is not None and (verified or min(sizes) < probe_bytes):
+                    break
             if offs is None:
                 lay.note = ("one region found: nothing to choose" if len(set(labels)) < 2
                             else "no placement with the partners in different regions")
@@ -193,10 +203,7 @@ def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: 
             else:
                 lay = Layout("regions", "pools carved from one reservation by measured region: source and staging arena "
                              "in different regions, staging arena and destination in different regions",
-                             want, chunk_bytes, labels, offs, probes)
-                if min(sizes) >= probe_bytes:
-                    lay.verified = verify_windows(offs, sizes, probe_bytes, window_ms, fastest)
-                    lay.probes += 4
+                             want, chunk_bytes, labels, offs, total_probes, verified)
                 o_src, o_arena, o_dst = offs
                 return (block[o_src:o_src + src_bytes], block[o_arena:o_arena + arena_bytes],
                         block[o_dst:o_dst + dst_bytes], lay)
