@@ -5,7 +5,7 @@
 // an address belongs to.  A caller that lays out its pools (source pool, staging arena,
 // destination pool) times this probe for pairs of candidate windows and keeps partners apart.
 // The probe has the access pattern of the gather that shows the effect best: pages of the read
-// window visited in a scattered order (a multiplicative permutation of the page index), written
+// window visited in a scattered order (a hashed permutation of the page index), written
 // front to back into the write window, 16 bytes per lane, 4 KiB per workgroup.
 #include "tent_internal.h"
 
@@ -17,15 +17,22 @@ typedef __attribute__((address_space(1))) pvec4u pvec4u_dev;
 
 __global__ void __launch_bounds__(256) region_probe_kernel(uint64_t read_base, uint64_t write_base, uint64_t n_blocks,
                                                            uint32_t blocks_per_page_shift, uint64_t page_mask,
-                                                           uint64_t multiplier)
+                                                           uint32_t half_bits, uint64_t multiplier)
 {
     const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
     if (w >= n_blocks) return;
     const uint64_t page = w >> blocks_per_page_shift;
     const uint64_t in_page = w & ((1ull << blocks_per_page_shift) - 1);
-    const uint64_t from_page = (page * multiplier) & page_mask;          // odd multiplier, power-of-two count: a bijection
+    // a bijection of the page index (odd multiplier, xor with the upper half, odd multiplier; power-of-two count)
+    // that leaves no regular stride between the pages of consecutive workgroups
+    uint64_t from_page = (page * multiplier) & page_mask;
+    from_page ^= from_page >> half_bits;
+    from_page = (from_page * (multiplier >> 7 | 1ull)) & page_mask;
     const uint64_t src = read_base + (((from_page << blocks_per_page_shift) + in_page) << 12) + (uint64_t)threadIdx.x * 16;
-    const uint64_t dst = write_base + (w << 12) + (uint64_t)threadIdx.x * 16;
+    // eight write frontiers, as a gather into the staging regions of several rails has
+    const uint64_t per_frontier = n_blocks >> 3;
+    const uint64_t wb = per_frontier ? (w & 7) * per_frontier + (w >> 3) : w;
+    const uint64_t dst = write_base + (wb << 12) + (uint64_t)threadIdx.x * 16;
     pvec4u v = __builtin_nontemporal_load((const pvec4u_dev*)src);
     __builtin_nontemporal_store(v, (pvec4u_dev*)dst);
 }
@@ -44,6 +51,9 @@ extern "C" int tent_probe_copy(const void* read_window, void* write_window, uint
     if ((n_pages & (n_pages - 1)) != 0) return TENT_ERR_INVALID;         // the permutation needs a power of two
     uint32_t shift = 0;
     while ((4096u << shift) < page_bytes) ++shift;
+    uint32_t page_bits = 0;
+    while ((1ull << page_bits) < n_pages) ++page_bits;
+    const uint32_t half_bits = page_bits > 1 ? page_bits / 2 : 1;
     const uint64_t n_blocks = bytes >> 12;
     const uint32_t gx = n_blocks < 65536 ? (uint32_t)n_blocks : 65536u;
     const uint64_t gy = (n_blocks + gx - 1) / gx;
@@ -58,7 +68,7 @@ extern "C" int tent_probe_copy(const void* read_window, void* write_window, uint
         float ms = 0.f;
         if (hipEventRecord(e0, s) != hipSuccess) { rc = TENT_ERR_HIP; break; }
         hipLaunchKernelGGL(region_probe_kernel, dim3(gx, (uint32_t)gy), dim3(256), 0, s, (uint64_t)read_window,
-                           (uint64_t)write_window, n_blocks, shift, n_pages - 1, 0x9E3779B97F4A7C15ull | 1ull);
+                           (uint64_t)write_window, n_blocks, shift, n_pages - 1, half_bits, 0x9E3779B97F4A7C15ull);
         if (hipGetLastError() != hipSuccess || hipEventRecord(e1, s) != hipSuccess ||
             hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
             (void)hipGetLastError();

@@ -46,12 +46,25 @@ class Layout:
     verified: bool = False          # probes between the carved pools themselves (first and last bytes) say "different regions"
 
 
+def split_level(times, min_spread: float = 1.02):
+    """Where a set of probe times falls into a fast and a slow group: the middle of the widest gap between
+    neighbours of the sorted times, or None when the slowest is within `min_spread` of the fastest (one group)."""
+    ts = sorted(times)
+    if len(ts) < 2 or ts[-1] < min_spread * ts[0]:
+        return None
+    k = max(range(len(ts) - 1), key=lambda n: ts[n + 1] - ts[n])
+    return 0.5 * (ts[k] + ts[k + 1])
+
+
 def label_chunks(n_chunks: int, pair_ms, ratio: float = SAME_REGION_RATIO):
-    """Region label (0, 1, ...) for each of n_chunks chunks.  pair_ms(i, j) times one probe that
-    reads chunk i and writes chunk j; pairs in the same region take `ratio` times the fastest pair
-    seen or longer.  Returns (labels, number of probes, fastest pair time)."""
+    """Region label (0, 1, ...) for each of n_chunks chunks.  pair_ms(i, j) times one probe that reads
+    chunk i and writes chunk j.  Same-region pairs are the slow group: the level between the groups is
+    taken from the first reference chunk whose probes show two groups and kept for the rest (later
+    references may see one group only); until then a pair counts as same-region when it takes `ratio`
+    times the fastest pair seen.  Returns (labels, number of probes, fastest pair time, the level or None)."""
     labels = [-1] * n_chunks
     fastest = None
+    level = None
     probes = 0
     next_label = 0
     for i in range(n_chunks):
@@ -64,11 +77,14 @@ def label_chunks(n_chunks: int, pair_ms, ratio: float = SAME_REGION_RATIO):
             times[j] = pair_ms(i, j)
             probes += 1
             fastest = times[j] if fastest is None else min(fastest, times[j])
+        if level is None:
+            level = split_level(list(times.values()))
+        cut = level if level is not None else ratio * fastest
         for j in todo:
-            if times[j] >= ratio * fastest:
+            if times[j] >= cut:
                 labels[j] = next_label
         next_label += 1
-    return labels, probes, fastest
+    return labels, probes, fastest, level
 
 
 def uniform_runs(labels):
@@ -145,15 +161,15 @@ def _probe_factory(block, chunk_bytes, probe_bytes, repeats):
     return pair_ms, window_ms
 
 
-def verify_windows(offsets, sizes, probe_bytes, window_ms, fastest, ratio: float = SAME_REGION_RATIO) -> bool:
+def verify_windows(offsets, sizes, probe_bytes, window_ms, cut) -> bool:
     """Probes between the pools as carved -- source to arena and arena to destination, at the pools' first
-    bytes and at their last -- must all be as fast as pairs from different regions."""
+    bytes and at their last -- must all be faster than `cut`, i.e. as fast as pairs from different regions."""
     (o_src, o_arena, o_dst), (n_src, n_arena, n_dst) = offsets, sizes
     def last(o, n):
         return o + (max(n - probe_bytes, 0) // ALIGN) * ALIGN
     pairs = [(o_src, o_arena), (last(o_src, n_src), last(o_arena, n_arena)),
              (o_arena, o_dst), (last(o_arena, n_arena), last(o_dst, n_dst))]
-    return all(window_ms(a, b) < ratio * fastest for a, b in pairs)
+    return all(window_ms(a, b) < cut for a, b in pairs)
 
 
 def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: str = "regions",
@@ -186,12 +202,13 @@ def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: 
             total_probes = 0
             for repeats in (3, 8):                        # a second, more patient pass if the first map does not hold up
                 pair_ms, window_ms = _probe_factory(block, chunk_bytes, probe_bytes, repeats)
-                labels, probes, fastest = label_chunks(n_chunks, pair_ms)
+                labels, probes, fastest, level = label_chunks(n_chunks, pair_ms)
                 total_probes += probes
                 offs = choose_windows(labels, chunk_bytes, probe_bytes, sizes)
                 verified = False
                 if offs is not None and min(sizes) >= probe_bytes:
-                    verified = verify_windows(offs, sizes, probe_bytes, window_ms, fastest)
+                    verified = verify_windows(offs, sizes, probe_bytes, window_ms,
+                                              level if level is not None else SAME_REGION_RATIO * fastest)
                     total_probes += 4
                 if offs is not None and (verified or min(sizes) < probe_bytes):
                     break
@@ -211,3 +228,34 @@ def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: 
     dst = torch.empty(dst_bytes, dtype=torch.uint8, device=device)
     arena = torch.empty(arena_bytes, dtype=torch.uint8, device=device)
     return src, arena, dst, lay
+
+
+def main(argv=None):
+    """python -m paper_2604_00368_amd.placement [--step GiB]: reserve the device memory, print the probe time
+    of every pair of windows `step` GiB apart (rows read, columns write) and the region map."""
+    import argparse
+    import torch
+    ap = argparse.ArgumentParser(description=main.__doc__)
+    ap.add_argument("--step", type=int, default=16, help="distance between probed windows in GiB (a multiple of 8)")
+    ap.add_argument("--keep-free", type=int, default=24, help="GiB left outside the reservation")
+    args = ap.parse_args(argv)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    free, total = torch.cuda.mem_get_info(dev)
+    want = (free - args.keep_free * GiB) // CHUNK * CHUNK
+    block = torch.empty(want, dtype=torch.uint8, device=dev)
+    print(f"device memory {total / GiB:.1f} GiB, reservation {want / GiB:.0f} GiB; probe: {PROBE >> 30} GiB, 32 KiB pages "
+          "in scattered order -> sequential writes; ms, shortest of 3")
+    pair_ms, _ = _probe_factory(block, CHUNK, PROBE, 3)
+    per = max(1, args.step * GiB // CHUNK)
+    idx = list(range(0, want // CHUNK, per))
+    print("read\\write " + " ".join(f"{k * (CHUNK >> 30):6d}" for k in idx))
+    for i in idx:
+        print(f"{i * (CHUNK >> 30):9d}  " + " ".join("    --" if i == j else f"{pair_ms(i, j):6.3f}" for j in idx), flush=True)
+    labels, probes, fastest, level = label_chunks(want // CHUNK, pair_ms)
+    print(f"region of each {CHUNK >> 30} GiB chunk: {''.join(str(x) for x in labels)}  ({probes} probes, fastest pair {fastest:.3f} ms, "
+          f"level between the groups {level if level is None else round(level, 3)} ms)")
+
+
+if __name__ == "__main__":
+    main()
