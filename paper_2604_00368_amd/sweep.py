@@ -14,23 +14,37 @@ import numpy as np
 def main():
     import torch
     from . import binding as T
+    from . import placement
     from . import workloads as W
     ap = argparse.ArgumentParser()
     ap.add_argument("--payload-gib", type=int, default=4)
     ap.add_argument("--reps", type=int, default=4)
+    ap.add_argument("--placement", default="regions", choices=["regions", "plain"],
+                    help="regions: pools carved so that either copy crosses memory regions (placement.py); plain: "
+                         "ordinary allocations")
     args = ap.parse_args()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     payload = args.payload_gib << 30
     stream = torch.cuda.current_stream(dev)
+    # one set of pools for the whole sweep, large enough for every layout (the paged pools carry some slack)
+    biggest = [W.sweep(kib * 1024, paged, payload=payload) for paged in (False, True) for kib in (4, 65536)]
+    n_src = max(w.seg_bytes[0] for w in biggest)
+    n_dst = max(w.seg_bytes[1] for w in biggest)
+    n_arena = max(w.staging_bytes for w in biggest)
+    src_pool, arena_pool, dst_pool, layout = placement.place_pools(dev, n_src, n_arena, n_dst, mode=args.placement)
+    print(f"placement: {layout.mode} ({layout.note}); region map {''.join(str(x) for x in layout.labels)}, "
+          f"offsets GiB {[round(o / 2**30, 1) for o in layout.offsets]}")
     print(f"{'layout':12s} {'slice':>8s} {'slices':>9s} {'plan ms':>9s} {'M slices/s':>11s} {'gather GB/s':>12s} "
           f"{'scatter GB/s':>13s} {'execute GB/s':>13s}")
     for paged in (False, True):
         for kib in (4, 16, 64, 256, 1024, 4096, 16384, 65536):
             w = W.sweep(kib * 1024, paged, payload=payload)
-            src = W.fill_torch(w, 0, dev)
-            dst = torch.zeros(w.seg_bytes[1], dtype=torch.uint8, device=dev)
-            arena = torch.empty(w.staging_bytes, dtype=torch.uint8, device=dev)
+            src = src_pool[:w.seg_bytes[0]]
+            dst = dst_pool[:w.seg_bytes[1]]
+            arena = arena_pool[:w.staging_bytes]
+            W.fill_torch(w, 0, dev, out=src)
+            dst.zero_()
             ctx = T.tent_create(w.slice_bytes, arena.data_ptr(), arena.numel(), T.TENT_FLAG_PROFILE)
             T.tent_register_segment(ctx, src.data_ptr(), src.numel())
             T.tent_register_segment(ctx, dst.data_ptr(), dst.numel())
@@ -53,7 +67,6 @@ def main():
                   f"{2 * w.payload / g / 1e6:12.0f} {2 * w.payload / s / 1e6:13.0f} {4 * w.payload / (g + s) / 1e6:13.0f}",
                   flush=True)
             T.tent_destroy(ctx)
-            del src, dst, arena
 
 
 if __name__ == "__main__":
