@@ -413,7 +413,9 @@ int tent_release(tent_ctx *ctx, tent_batch_t batch);
  * copy (source pool / staging arena, staging arena / destination pool) in different ones.
  * The probe copies `bytes` from `read_window` to `write_window` (both device memory, at least
  * `bytes` long, contents of the write window are overwritten): pages of `page_bytes` are read in
- * a scattered order and written front to back.  `page_bytes` is a power of two >= 4096,
+ * a scattered order and written in 4 KiB blocks to eight frontiers that advance through the
+ * write window side by side, as a gather into several rails' regions does.  Every block of
+ * the read window lands exactly once.  `page_bytes` is a power of two >= 4096,
  * `bytes / page_bytes` a power of two.  Needs no context.  The copy runs `repeats` times on
  * `stream`, the call waits for each, and `*ms_out` (host) receives the shortest duration.
  * TENT_ERR_INVALID for a null pointer or sizes that break the rules above.

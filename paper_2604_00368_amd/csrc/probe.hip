@@ -5,8 +5,8 @@
 // an address belongs to.  A caller that lays out its pools (source pool, staging arena,
 // destination pool) times this probe for pairs of candidate windows and keeps partners apart.
 // The probe has the access pattern of the gather that shows the effect best: pages of the read
-// window visited in a scattered order (a hashed permutation of the page index), written
-// front to back into the write window, 16 bytes per lane, 4 KiB per workgroup.
+// window visited in a scattered order (a hashed permutation of the page index), written to
+// eight frontiers of the write window, 16 bytes per lane, 4 KiB per workgroup.
 #include "tent_internal.h"
 
 namespace tent {
