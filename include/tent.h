@@ -191,11 +191,19 @@ int tent_register_segment(tent_ctx *ctx, void *dev_base, uint64_t len, uint32_t 
  * length.  All four arrays are host memory in CSR form (ptr arrays have
  * n_desc+1 entries, ptr[0] = 0, nondecreasing).
  * Errors: TENT_ERR_INVALID for null pointers, n_desc = 0, an empty transfer, a
- * zero-length extent, an extent outside its segment, unequal source and
- * destination lengths, or (unless TENT_FLAG_SKIP_OVERLAP_CHECK) a destination
- * extent that overlaps another destination extent or any source extent of the
- * batch; TENT_ERR_RANGE when the batch holds more than 2^32-2 slices.
- * Device tables for the batch are allocated here, not in plan or execute.
+ * zero-length extent, an extent outside its segment, or unequal source and
+ * destination lengths; TENT_ERR_RANGE when the batch holds more than 2^32-2 slices.
+ * The call returns as soon as the host arrays are copied (Section 4.1: submitting a transfer
+ * returns immediately): the upload of the descriptors, the ordering of the destination extents by
+ * address and the overlap check run on a stream of the library's own (default priority) and hold up
+ * none of the caller's streams.  Unless TENT_FLAG_SKIP_OVERLAP_CHECK is set, a destination extent
+ * that overlaps another destination extent or any source extent of the batch makes the batch
+ * invalid; that verdict comes from the device and is delivered by the first tent_plan or
+ * tent_plan_dispatch on the batch, which waits for it, returns TENT_ERR_INVALID and releases the
+ * batch.
+ * Device tables for the batch are set up here, not in plan or execute: they come from one device
+ * allocation per batch, and the allocations of released batches are kept and handed to later
+ * declarations of similar size, so a loop of declare ... release settles into allocating nothing.
  */
 int tent_declare(tent_ctx *ctx, uint32_t n_desc,
                  const uint32_t *src_ptr, const tent_extent *src_ext,
@@ -220,8 +228,11 @@ int tent_declare(tent_ctx *ctx, uint32_t n_desc,
  * NULL; when it is non-NULL the call waits for the stream and fills it, when it
  * is NULL the call only enqueues work on `stream`.
  * Returns TENT_DEFER (and binds nothing) when every rail is excluded;
- * TENT_ERR_RANGE when n_rails exceeds the context's max_rails, bw_MBps = 0, c1_d >= 2^32, (max A_d + pending bytes) *
- * max c1_d >= 2^63, or the arena is smaller than pending bytes + 256*n_rails.
+ * TENT_ERR_INVALID for a health value above 2 (and for a batch that failed its overlap check, see
+ * tent_declare); TENT_ERR_RANGE when n_rails exceeds the context's max_rails, bw_MBps = 0,
+ * c1_d >= 2^32, (max A_d + the batch's payload) * max c1_d >= 2^63, or the arena is smaller than the
+ * batch's payload + 256*n_rails; TENT_ERR_STATE for a batch whose last tent_execute failed half way
+ * (see there).
  */
 int tent_plan(tent_ctx *ctx, tent_batch_t batch, const tent_rail_state *rails, uint32_t n_rails,
               tent_plan_info *info, void *stream);
@@ -350,10 +361,15 @@ int tent_get_latencies(tent_ctx *ctx, tent_batch_t batch, uint64_t *host_out, ui
  * its rail's staging region, then scatter from staging to the destination
  * extents at the slice's absolute offset (Section 4.1 staging hop; Section 4.4
  * direct-to-offset writes), and mark it DONE.  Enqueues on `stream` and
- * returns; the caller synchronises the stream.  The DONE marks are enqueued
+ * returns; the caller synchronises the stream or polls.  The DONE marks are enqueued
  * ahead of the copies (the copies are driven by address tables, not by slice
- * state), so on `stream` itself the order is not observable.  TENT_ERR_STATE if the batch was
- * never planned.  A batch with no BOUND slice is a no-op.
+ * state), which is what lets a re-plan on another stream run beside the copies; tent_poll, on
+ * any stream, waits for the end of the copies before it counts, so completion is never reported
+ * while bytes are still moving.  TENT_ERR_STATE if the batch was never planned.  A batch with no
+ * BOUND slice is a no-op.
+ * Should a launch fail after the slices were marked (TENT_ERR_HIP), the batch is flagged: every
+ * later call on it but tent_reset (which clears the flag and returns all slices to PENDING, so
+ * the bytes are moved again) and tent_release returns TENT_ERR_STATE.
  */
 int tent_execute(tent_ctx *ctx, tent_batch_t batch, void *stream);
 
@@ -371,10 +387,12 @@ int tent_execute(tent_ctx *ctx, tent_batch_t batch, void *stream);
  * (default priority), ordered by events, and `stream` is made to wait for the last scatter, so work
  * enqueued on `stream` afterwards sees the batch complete.  Slices are marked DONE as by
  * tent_execute.  Only enqueues.
+ * Lengths and addresses may be anything: when every extent length and the slice size are multiples of
+ * 1 KiB the chunks are moved by table-driven copies, otherwise byte-exactly in ranges of 1 KiB of the
+ * payload (slower).
  * Needs a context created with TENT_FLAG_BOUNDED_STAGING (else TENT_ERR_STATE).  TENT_ERR_INVALID
- * unless chunk_bytes is a positive multiple of 1 MiB and slots is 1 or 2; TENT_ERR_RANGE when some
- * extent length or the slice size is not a multiple of 1 KiB, when the slots exceed the arena, or
- * when the payload needs more than 4096 chunks.  Should a chunk's regions not fit the arena after all
+ * unless chunk_bytes is a positive multiple of 1 MiB and slots is 1 or 2; TENT_ERR_RANGE when the
+ * slots exceed the arena or when the payload needs more than 4096 chunks.  Should a chunk's regions not fit the arena after all
  * (possible only when the BOUND slices of a rail are not a contiguous run of its staging offsets),
  * nothing is moved and the slices stay BOUND: tent_poll then still reports them.
  * With the flag set tent_execute returns TENT_ERR_RANGE when the arena cannot hold the payload.
@@ -382,7 +400,8 @@ int tent_execute(tent_ctx *ctx, tent_batch_t batch, void *stream);
 int tent_execute_bounded(tent_ctx *ctx, tent_batch_t batch, uint64_t chunk_bytes, uint32_t slots, void *stream);
 
 /* Batch-level completion (Section 4.4): *remaining (host) receives the number of
- * slices not DONE.  Waits for `stream`. */
+ * slices not DONE.  Waits for `stream`, which is first made to wait for the copies of the batch's
+ * last execute if that ran on another stream: 0 means every byte of the batch has landed. */
 int tent_poll(tent_ctx *ctx, tent_batch_t batch, uint64_t *remaining, void *stream);
 
 /* Return every slice of the batch to PENDING (the next tent_plan rebuilds the table). */
@@ -402,7 +421,9 @@ int tent_get_plan(tent_ctx *ctx, tent_batch_t batch, tent_slice *host_out, uint6
  * `ms_out` and `launches_out` are host memory with TENT_T_COUNT entries each. */
 int tent_get_timings(tent_ctx *ctx, float *ms_out, uint32_t *launches_out);
 
-/* Free the batch's device tables.  Waits for the device. */
+/* Give up the batch.  Waits (on the host) for the work that the library's calls enqueued for this
+ * batch, on whichever streams, and for nothing else; its device tables are kept for a later
+ * declaration of similar size or freed. */
 int tent_release(tent_ctx *ctx, tent_batch_t batch);
 
 /*

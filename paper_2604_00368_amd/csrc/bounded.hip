@@ -9,7 +9,13 @@
 //
 // Both copies walk the chunk's tiles in declaration order (a chunk is a contiguous range of that
 // enumeration), so a chunk's launch touches only its own table entries.
-#include "tent_internal.h"
+//
+// Geometry whose lengths are no multiple of the tile size has no such enumeration.  There the same
+// steps run over the payload in ranges of 1 KiB, one wavefront per range: the wavefront finds the
+// slice that holds the range's first byte (transfers are laid end to end, so a payload position
+// gives the transfer by a search over their first positions and the slice by a division), walks
+// the slices that intersect the range and moves each piece byte-exactly through the extent lists.
+#include "copy_generic.h"
 
 namespace tent {
 namespace {
@@ -119,6 +125,83 @@ __global__ void __launch_bounds__(kOrderedLanes) bounded_copy_kernel(const uint6
     }
 }
 
+// ---- geometry without a tile enumeration: ranges of 1 KiB of the payload -----------------------
+constexpr uint32_t kRangeBytes = 1024;
+
+// Payload position of the first byte of transfer j (the source extent prefix runs over the whole batch).
+__device__ __forceinline__ uint64_t transfer_start(const BatchDev& b, uint32_t j) { return b.src_pre[b.src_ptr[j]]; }
+
+// Slice that holds payload position p (p < payload).
+__device__ __forceinline__ uint64_t slice_at(const BatchDev& b, uint64_t p)
+{
+    uint32_t lo = 0, hi = b.n_desc;                       // last transfer that starts at or before p
+    while (hi - lo > 1) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if (transfer_start(b, mid) <= p) lo = mid; else hi = mid;
+    }
+    return b.first[lo] + (p - transfer_start(b, lo)) / b.slice_bytes;
+}
+
+// Per (chunk, rail): the interval of staging offsets that the BOUND bytes of the chunk touch.  A
+// workgroup covers four consecutive ranges, which lie in one chunk (chunks are multiples of 1 MiB).
+__global__ void __launch_bounds__(256) bounded_ranges_kernel(BatchDev b, uint64_t payload, uint64_t chunk_bytes)
+{
+    __shared__ unsigned long long lo[TENT_MAX_RAILS], hi[TENT_MAX_RAILS];
+    if (threadIdx.x < TENT_MAX_RAILS) { lo[threadIdx.x] = kNoTile; hi[threadIdx.x] = 0; }
+    __syncthreads();
+    const uint64_t first = ((uint64_t)blockIdx.y * gridDim.x + blockIdx.x) * (4ull * kRangeBytes);
+    const uint64_t p0 = first + (uint64_t)(threadIdx.x >> 6) * kRangeBytes;
+    if (p0 < payload) {
+        const uint64_t p1 = p0 + kRangeBytes < payload ? p0 + kRangeBytes : payload;
+        uint64_t i = slice_at(b, p0);
+        for (;;) {
+            const uint64_t at = transfer_start(b, b.s_desc[i]) + b.s_off[i];      // payload position of the slice
+            const uint64_t end = at + b.s_len[i];
+            if ((threadIdx.x & 63) == 0 && b.s_state[i] == TENT_SLICE_BOUND) {
+                const uint64_t from = at > p0 ? at : p0, to = end < p1 ? end : p1;
+                const uint64_t reg = b.s_stage_off[i] + (from - at);
+                const uint32_t d = b.s_rail[i];
+                atomicMin(&lo[d], (unsigned long long)reg);
+                atomicMax(&hi[d], (unsigned long long)(reg + (to - from)));
+            }
+            if (end >= p1) break;
+            ++i;
+        }
+    }
+    __syncthreads();
+    if (first < payload && threadIdx.x < TENT_MAX_RAILS && lo[threadIdx.x] != kNoTile) {
+        const uint64_t c = first / chunk_bytes;
+        atomicMin((unsigned long long*)&b.ch_lo[c * TENT_MAX_RAILS + threadIdx.x], lo[threadIdx.x]);
+        atomicMax((unsigned long long*)&b.ch_hi[c * TENT_MAX_RAILS + threadIdx.x], hi[threadIdx.x]);
+    }
+}
+
+// Move the BOUND bytes of payload positions [c_lo, c_hi) -- one chunk -- between their paged side and the
+// chunk's slot, one wavefront per range of 1 KiB.
+template <bool kGather>
+__global__ void __launch_bounds__(256) bounded_ranges_copy_kernel(BatchDev b, uint64_t c_lo, uint64_t c_hi,
+                                                                  uint8_t* slot, uint64_t row)
+{
+    const uint64_t w = ((uint64_t)blockIdx.y * gridDim.x + blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const uint64_t p0 = c_lo + w * kRangeBytes;
+    if (p0 >= c_hi || b.plan->bounded_overflow != 0) return;
+    const uint64_t p1 = p0 + kRangeBytes < c_hi ? p0 + kRangeBytes : c_hi;
+    uint64_t i = slice_at(b, p0);
+    for (;;) {
+        const uint64_t at = transfer_start(b, b.s_desc[i]) + b.s_off[i];
+        const uint64_t end = at + b.s_len[i];
+        if (b.s_state[i] == TENT_SLICE_BOUND) {
+            const uint64_t from = at > p0 ? at : p0, to = end < p1 ? end : p1;
+            const uint64_t x = from - at;                                         // offset inside the slice
+            const uint32_t d = b.s_rail[i];
+            uint8_t* staged = slot + b.ch_base[row + d] + (b.s_stage_off[i] + x - b.ch_lo[row + d]);
+            copy_range_generic<kGather>(b, i, x, x + (to - from), staged);
+        }
+        if (end >= p1) break;
+        ++i;
+    }
+}
+
 __global__ void __launch_bounds__(256) mark_done_bounded_kernel(BatchDev b)
 {
     if (b.plan->bounded_overflow != 0) return;                      // nothing moved: leave the slices BOUND
@@ -138,12 +221,18 @@ bool grid_for(uint64_t blocks, dim3* grid)
 
 }  // namespace
 
-hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint32_t n_chunks, uint64_t slot_bytes,
-                                  uint32_t slots, uint8_t* arena, hipStream_t s)
+hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t payload, uint64_t chunk_bytes, uint32_t n_chunks,
+                                  uint64_t slot_bytes, uint32_t slots, uint8_t* arena, hipStream_t s)
 {
     const uint32_t cells = n_chunks * TENT_MAX_RAILS;
     hipLaunchKernelGGL(bounded_clear_kernel, dim3((cells + 255) / 256), dim3(256), 0, s, b, n_chunks);
     dim3 grid;
+    if (b.n_sc_tiles == 0) {                                  // no tile enumeration: ranges of the payload
+        if (!grid_for((payload + 4 * kRangeBytes - 1) / (4 * kRangeBytes), &grid)) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(bounded_ranges_kernel, grid, dim3(256), 0, s, b, payload, chunk_bytes);
+        hipLaunchKernelGGL(bounded_bases_kernel, dim3(n_chunks), dim3(64), 0, s, b, slot_bytes);
+        return hipGetLastError();
+    }
     if (!grid_for((b.n_sc_tiles + 255) / 256, &grid)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(bounded_tiles_kernel, grid, dim3(256), 0, s, b, chunk_bytes / b.tile_bytes);
     hipLaunchKernelGGL(bounded_bases_kernel, dim3(n_chunks), dim3(64), 0, s, b, slot_bytes);
@@ -152,8 +241,23 @@ hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint3
     return hipGetLastError();
 }
 
-hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t chunk_bytes, hipStream_t s)
+hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t payload, uint64_t chunk_bytes,
+                               uint64_t slot_bytes, uint32_t slots, uint8_t* arena, hipStream_t s)
 {
+    if (b.n_sc_tiles == 0) {
+        const uint64_t c_lo = (uint64_t)chunk * chunk_bytes;
+        if (c_lo >= payload) return hipSuccess;
+        const uint64_t c_hi = c_lo + chunk_bytes < payload ? c_lo + chunk_bytes : payload;
+        dim3 grid;
+        if (!grid_for((c_hi - c_lo + 4 * kRangeBytes - 1) / (4 * kRangeBytes), &grid)) return hipErrorInvalidValue;
+        uint8_t* slot = arena + (chunk % slots) * slot_bytes;
+        const uint64_t row = (uint64_t)chunk * TENT_MAX_RAILS;
+        if (gather)
+            hipLaunchKernelGGL(bounded_ranges_copy_kernel<true>, grid, dim3(256), 0, s, b, c_lo, c_hi, slot, row);
+        else
+            hipLaunchKernelGGL(bounded_ranges_copy_kernel<false>, grid, dim3(256), 0, s, b, c_lo, c_hi, slot, row);
+        return hipGetLastError();
+    }
     uint32_t tile_shift = 0;
     while ((1u << tile_shift) < b.tile_bytes) ++tile_shift;
     const uint64_t chunk_tiles = chunk_bytes >> tile_shift;

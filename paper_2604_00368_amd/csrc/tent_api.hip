@@ -14,11 +14,20 @@ namespace {
 
 struct Segment { uint8_t* base; uint64_t len; };
 
+// A stream on which work of a batch was enqueued, with an event recorded after the latest such work.
+struct StreamMark {
+    hipStream_t stream = nullptr;
+    hipEvent_t event = nullptr;
+    bool used = false;
+};
+constexpr int kMarks = 4;
+
 struct Batch {
     bool alive = false;
     bool planned = false;        // a plan has been enqueued since declare / reset
     bool has_done = false;       // execute ran since declare / reset: DONE slices may exist
     bool has_retry = false;      // a rail failed since declare / reset: slices with a retry count may exist
+    bool broken = false;         // an execute failed after its slices were marked DONE: only reset or release help
     uint64_t bound_hint = 0;     // upper bound on the number of BOUND slices, as far as the host knows
     uint32_t generation = 0;
     uint64_t payload = 0;
@@ -26,12 +35,25 @@ struct Batch {
     RailParams last_rails{};     // telemetry of the last plan (for the rail simulator)
     uint32_t last_lat_ns[TENT_MAX_RAILS] = {};
     // The last execute's bookkeeping (staging addresses, tile lists, DONE marks) ends at prep_event on
-    // exec_stream; its copies, which follow, read none of what a re-plan writes.
-    hipEvent_t prep_event = nullptr;
+    // exec_stream; its copies, which follow, read none of what a re-plan writes, and end at done_event.
     hipStream_t exec_stream = nullptr;
     bool prep_recorded = false;
+    bool done_recorded = false;
+    // The declaration's device work (descriptor upload, address sort, overlap check) runs on the
+    // context's own stream and ends at decl_event; `verdict` (pinned host memory) then holds the
+    // overlap check's result.
+    bool decl_pending = false;
+    uint32_t* overlap_dev = nullptr;
+    // Device memory of the tables: one allocation.
+    void* block = nullptr;
+    uint64_t block_bytes = 0;
+    bool marks_lost = false;     // work was enqueued that no mark covers: waiting for the batch means waiting for the device
     BatchDev dev{};
-    std::vector<void*> allocs;
+
+    // Created once per slot and kept across the batches that use it.
+    hipEvent_t prep_event = nullptr, done_event = nullptr, decl_event = nullptr;
+    uint32_t* verdict = nullptr;
+    StreamMark marks[kMarks];
 };
 
 // Event pairs recorded around the launches of one stage since the last tent_get_timings.
@@ -39,6 +61,8 @@ struct Timing {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;   // every pair ever created for the stage
     size_t used = 0;                                        // pairs recorded since the last read-out
 };
+
+struct Block { void* ptr; uint64_t bytes; };
 
 }  // namespace
 
@@ -53,6 +77,17 @@ struct tent_ctx {
     PlanState* host_plan = nullptr;         // pinned read-back buffer
     hipStream_t aux_stream = nullptr;       // second stream of the pipelined bounded execute (default priority)
     std::vector<hipEvent_t> sync_events;    // ordering events of the pipelined bounded execute, reused
+    // tent_declare: its device work runs on a stream of the library's own, so that it neither waits for
+    // nor holds up the caller's streams; host arrays travel through two pinned buffers used in turn.
+    hipStream_t decl_stream = nullptr;
+    uint8_t* stage[2] = {nullptr, nullptr};
+    uint64_t stage_bytes[2] = {0, 0};
+    hipEvent_t stage_event[2] = {nullptr, nullptr};
+    bool stage_busy[2] = {false, false};
+    uint32_t stage_turn = 0;
+    void* order_ws = nullptr;               // workspace of the address sort, grown when a declaration needs more
+    uint64_t order_ws_bytes = 0;
+    std::vector<Block> spare;               // table allocations of released batches, handed to later declarations
     Timing timing[TENT_T_COUNT];
 };
 
@@ -60,7 +95,8 @@ namespace {
 
 constexpr uint32_t kMaxSegments = 4096;
 constexpr size_t kMaxTimedIntervals = 1u << 16;   // per stage, between two tent_get_timings calls
-
+constexpr size_t kSpareBlocks = 4;                // released table allocations kept for reuse
+constexpr uint64_t kStageInitial = 1ull << 20;    // pinned bytes per staging buffer at tent_create
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) return TENT_ERR_HIP; } while (0)
 
 struct DeviceGuard {
@@ -75,6 +111,119 @@ struct DeviceGuard {
     int target = -1;
 };
 
+bool capturing(hipStream_t s)
+{
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return cap != hipStreamCaptureStatusNone;
+}
+
+// Remember that work of the batch was just enqueued on `s` (nothing is recorded into a stream that is
+// being captured into a graph: such work is only known to be over when the device is idle).
+void note_stream(Batch& b, hipStream_t s)
+{
+    if (capturing(s)) { b.marks_lost = true; return; }
+    StreamMark* slot = nullptr;
+    for (StreamMark& m : b.marks) {
+        if (m.used && m.stream == s) { slot = &m; break; }
+        if (!m.used && !slot) slot = &m;
+    }
+    if (!slot || !slot->event || hipEventRecord(slot->event, s) != hipSuccess) {
+        (void)hipGetLastError();
+        b.marks_lost = true;
+        return;
+    }
+    slot->stream = s;
+    slot->used = true;
+}
+
+// Records the batch's stream use when an entry point returns, whichever way it returns.
+struct StreamNote {
+    Batch& b;
+    hipStream_t s;
+    StreamNote(Batch& batch, hipStream_t stream) : b(batch), s(stream) {}
+    ~StreamNote() { note_stream(b, s); }
+};
+
+// Host-side wait for everything that was enqueued for the batch.
+void wait_batch_idle(Batch& b)
+{
+    if (b.decl_pending) (void)hipEventSynchronize(b.decl_event);
+    for (StreamMark& m : b.marks)
+        if (m.used) (void)hipEventSynchronize(m.event);
+    if (b.marks_lost) (void)hipDeviceSynchronize();
+    (void)hipGetLastError();
+}
+
+bool init_slot(Batch& b)
+{
+    bool ok = hipEventCreateWithFlags(&b.prep_event, hipEventDisableTiming) == hipSuccess &&
+              hipEventCreateWithFlags(&b.done_event, hipEventDisableTiming) == hipSuccess &&
+              hipEventCreateWithFlags(&b.decl_event, hipEventDisableTiming) == hipSuccess &&
+              hipHostMalloc((void**)&b.verdict, 64, hipHostMallocDefault) == hipSuccess;
+    for (StreamMark& m : b.marks)
+        ok = ok && hipEventCreateWithFlags(&m.event, hipEventDisableTiming) == hipSuccess;
+    if (!ok) (void)hipGetLastError();
+    return ok;
+}
+
+void destroy_slot(Batch& b)
+{
+    if (b.prep_event) (void)hipEventDestroy(b.prep_event);
+    if (b.done_event) (void)hipEventDestroy(b.done_event);
+    if (b.decl_event) (void)hipEventDestroy(b.decl_event);
+    if (b.verdict) (void)hipHostFree(b.verdict);
+    for (StreamMark& m : b.marks)
+        if (m.event) (void)hipEventDestroy(m.event);
+    b.prep_event = b.done_event = b.decl_event = nullptr;
+    b.verdict = nullptr;
+    for (StreamMark& m : b.marks) m = StreamMark{};
+}
+
+// Start a new batch in a slot: everything but the slot's events, its pinned word and its generation starts afresh.
+void renew_slot(Batch& b)
+{
+    Batch fresh;
+    fresh.generation = b.generation + 1;
+    fresh.prep_event = b.prep_event;
+    fresh.done_event = b.done_event;
+    fresh.decl_event = b.decl_event;
+    fresh.verdict = b.verdict;
+    for (int k = 0; k < kMarks; ++k) fresh.marks[k].event = b.marks[k].event;
+    b = fresh;
+}
+
+// The batch's tables go back to the context (an allocation is kept for a later declaration of
+// similar size; what the context cannot keep is freed).  The caller has waited for the batch.
+void free_batch(tent_ctx* ctx, Batch& b)
+{
+    if (b.block) {
+        bool kept = false;
+        if (ctx->spare.size() < kSpareBlocks) {
+            try { ctx->spare.push_back({b.block, b.block_bytes}); kept = true; } catch (const std::bad_alloc&) {}
+        } else {
+            // keep the larger allocations: replace the smallest spare one if this one is larger
+            size_t least = 0;
+            for (size_t k = 1; k < ctx->spare.size(); ++k)
+                if (ctx->spare[k].bytes < ctx->spare[least].bytes) least = k;
+            if (ctx->spare[least].bytes < b.block_bytes) {
+                (void)hipFree(ctx->spare[least].ptr);
+                ctx->spare[least] = {b.block, b.block_bytes};
+                kept = true;
+            }
+        }
+        if (!kept) (void)hipFree(b.block);
+    }
+    b.block = nullptr;
+    b.block_bytes = 0;
+    b.alive = false;
+    b.decl_pending = false;
+    b.prep_recorded = b.done_recorded = false;
+    b.marks_lost = false;
+    for (StreamMark& m : b.marks) { m.used = false; m.stream = nullptr; }
+    b.dev = BatchDev{};
+}
+
 Batch* find_batch(tent_ctx* ctx, tent_batch_t h)
 {
     const uint64_t idx = (h & 0xFFFFFFFFull);
@@ -84,79 +233,131 @@ Batch* find_batch(tent_ctx* ctx, tent_batch_t h)
     return (b->alive && b->generation == gen) ? b : nullptr;
 }
 
-// Every per-batch table is carved from ONE device allocation: a declaration asks for about fifty
+// Every per-batch table is carved from ONE range of device memory: a declaration asks for about fifty
 // arrays, and fifty allocator calls cost more than everything else a declaration does.  The requests
-// are collected first, then one hipMalloc serves them at 256-byte aligned offsets.
+// are collected first and then laid out at 256-byte aligned offsets.
 struct Carver {
     struct Want { void** slot; uint64_t bytes; };
-    std::vector<Want> wants;
+    static constexpr int kMost = 80;
+    Want wants[kMost];
+    int n = 0;
+    bool overflow = false;
     template <class T>
     void want(T** out, uint64_t count)
     {
-        wants.push_back({reinterpret_cast<void**>(out), std::max<uint64_t>(count, 1) * sizeof(T)});
+        if (n == kMost) { overflow = true; return; }
+        wants[n++] = {reinterpret_cast<void**>(out), std::max<uint64_t>(count, 1) * sizeof(T)};
     }
-    int commit(Batch& b)
+    uint64_t total() const
     {
-        uint64_t total = 0;
-        for (const Want& w : wants) total += (w.bytes + 255) & ~255ull;
-        void* base = nullptr;
-        if (hipMalloc(&base, total) != hipSuccess) {
-            (void)hipGetLastError();
-            return TENT_ERR_NOMEM;
-        }
-        b.allocs.push_back(base);
+        uint64_t t = 0;
+        for (int k = 0; k < n; ++k) t += (wants[k].bytes + 255) & ~255ull;
+        return t;
+    }
+    void place(void* base) const
+    {
         uint64_t at = 0;
-        for (const Want& w : wants) {
-            *w.slot = static_cast<char*>(base) + at;
-            at += (w.bytes + 255) & ~255ull;
+        for (int k = 0; k < n; ++k) {
+            *wants[k].slot = static_cast<char*>(base) + at;
+            at += (wants[k].bytes + 255) & ~255ull;
         }
-        return TENT_OK;
     }
 };
 
-void free_batch(Batch& b)
+// Device memory for a batch's tables: a spare allocation of a released batch when one is large enough
+// (and not absurdly larger), else a new one.
+int acquire_block(tent_ctx* ctx, uint64_t need, void** out, uint64_t* out_bytes)
 {
-    for (void* p : b.allocs) (void)hipFree(p);
-    b.allocs.clear();
-    if (b.prep_event) (void)hipEventDestroy(b.prep_event);
-    b.prep_event = nullptr;
-    b.prep_recorded = false;
-    b.alive = false;
-    b.dev = BatchDev{};
+    size_t best = ctx->spare.size();
+    for (size_t k = 0; k < ctx->spare.size(); ++k) {
+        const uint64_t have = ctx->spare[k].bytes;
+        if (have >= need && have <= 4 * need + (1ull << 20) &&
+            (best == ctx->spare.size() || have < ctx->spare[best].bytes))
+            best = k;
+    }
+    if (best != ctx->spare.size()) {
+        *out = ctx->spare[best].ptr;
+        *out_bytes = ctx->spare[best].bytes;
+        ctx->spare.erase(ctx->spare.begin() + (long)best);
+        return TENT_OK;
+    }
+    void* p = nullptr;
+    if (hipMalloc(&p, need) != hipSuccess) {
+        (void)hipGetLastError();
+        return TENT_ERR_NOMEM;
+    }
+    *out = p;
+    *out_bytes = need;
+    return TENT_OK;
 }
 
-// Walk both extent lists of every transfer: structure, bounds, equal lengths.  Also returns
-// the payload and the number of slices the device splitter will produce.
-int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const tent_extent* se,
-             const uint32_t* dp, const tent_extent* de, uint64_t* payload, uint64_t* n_slices, uint64_t* len_bits,
-             uint64_t* max_req_slices)
+// Pinned buffer for the host arrays of one declaration: the two buffers are used in turn, so a
+// declaration seldom has to wait for the upload of the one before.
+uint8_t* acquire_stage(tent_ctx* ctx, uint64_t need, int* which)
 {
-    if (sp[0] != 0 || dp[0] != 0) return TENT_ERR_INVALID;
+    const int k = (int)(ctx->stage_turn & 1);
+    if (ctx->stage_busy[k]) {
+        (void)hipEventSynchronize(ctx->stage_event[k]);
+        ctx->stage_busy[k] = false;
+    }
+    if (ctx->stage_bytes[k] < need) {
+        uint8_t* p = nullptr;
+        const uint64_t want = need + need / 4;
+        if (hipHostMalloc((void**)&p, want, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        if (ctx->stage[k]) (void)hipHostFree(ctx->stage[k]);
+        ctx->stage[k] = p;
+        ctx->stage_bytes[k] = want;
+    }
+    ++ctx->stage_turn;
+    *which = k;
+    return ctx->stage[k];
+}
+
+// CSR pointer arrays: start at 0, strictly increasing (no empty transfer).
+bool pointers_ok(uint32_t n_desc, const uint32_t* p)
+{
+    if (p[0] != 0) return false;
+    for (uint32_t j = 0; j < n_desc; ++j)
+        if (p[j + 1] <= p[j]) return false;
+    return true;
+}
+
+// Walk both extent lists of every transfer: structure, bounds, equal lengths; every extent is copied
+// to `se_out` / `de_out` (if not null) on the way.  Also returns the payload and the number of slices
+// the device splitter will produce.
+int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const tent_extent* se,
+             const uint32_t* dp, const tent_extent* de, tent_extent* se_out, tent_extent* de_out,
+             uint64_t* payload, uint64_t* n_slices, uint64_t* len_bits, uint64_t* max_req_slices)
+{
     const uint64_t S = ctx->cfg.slice_bytes;
+    const size_t n_seg = ctx->segments.size();
+    const Segment* seg = ctx->segments.data();
     uint64_t total = 0, slices = 0, bits = 0, most = 0;
     for (uint32_t j = 0; j < n_desc; ++j) {
-        if (sp[j + 1] <= sp[j] || dp[j + 1] <= dp[j]) return TENT_ERR_INVALID;   // empty or non-monotone
         uint64_t ls = 0, ld = 0;
         for (uint32_t e = sp[j]; e < sp[j + 1]; ++e) {
-            const tent_extent& x = se[e];
-            if (x.len == 0 || x.seg >= ctx->segments.size()) return TENT_ERR_INVALID;
-            const uint64_t seg_len = ctx->segments[x.seg].len;
+            const tent_extent x = se[e];
+            if (x.len == 0 || x.seg >= n_seg) return TENT_ERR_INVALID;
+            const uint64_t seg_len = seg[x.seg].len;
             if (x.off > seg_len || x.len > seg_len - x.off) return TENT_ERR_INVALID;
+            if (se_out) se_out[e] = x;
             ls += x.len;
             bits |= x.len;
         }
         for (uint32_t e = dp[j]; e < dp[j + 1]; ++e) {
-            const tent_extent& x = de[e];
-            if (x.len == 0 || x.seg >= ctx->segments.size()) return TENT_ERR_INVALID;
-            const uint64_t seg_len = ctx->segments[x.seg].len;
+            const tent_extent x = de[e];
+            if (x.len == 0 || x.seg >= n_seg) return TENT_ERR_INVALID;
+            const uint64_t seg_len = seg[x.seg].len;
             if (x.off > seg_len || x.len > seg_len - x.off) return TENT_ERR_INVALID;
+            if (de_out) de_out[e] = x;
             ld += x.len;
             bits |= x.len;
         }
         if (ls != ld) return TENT_ERR_INVALID;
         total += ls;
-        slices += (ls + S - 1) / S;
-        most = std::max(most, (ls + S - 1) / S);
+        const uint64_t cnt = (ls + S - 1) / S;
+        slices += cnt;
+        most = std::max(most, cnt);
     }
     *payload = total;
     *n_slices = slices;
@@ -205,18 +406,40 @@ hipError_t order_after_execute_bookkeeping(const Batch& b, hipStream_t s)
 hipError_t record_execute_bookkeeping(Batch& b, hipStream_t s)
 {
     b.prep_recorded = false;
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(s, &cap) != hipSuccess) { (void)hipGetLastError(); return hipSuccess; }
-    if (cap != hipStreamCaptureStatusNone) return hipSuccess;
-    if (!b.prep_event) {
-        hipError_t e = hipEventCreateWithFlags(&b.prep_event, hipEventDisableTiming);
-        if (e != hipSuccess) { b.prep_event = nullptr; return e; }
-    }
+    b.done_recorded = false;
+    if (capturing(s)) return hipSuccess;
     hipError_t e = hipEventRecord(b.prep_event, s);
     if (e != hipSuccess) return e;
     b.exec_stream = s;
     b.prep_recorded = true;
     return hipSuccess;
+}
+
+// Marks the end of an execute's copies on its stream: what batch-level completion waits for.
+hipError_t record_execute_done(Batch& b, hipStream_t s)
+{
+    b.done_recorded = false;
+    if (capturing(s)) return hipSuccess;
+    hipError_t e = hipEventRecord(b.done_event, s);
+    if (e != hipSuccess) return e;
+    b.exec_stream = s;
+    b.done_recorded = true;
+    return hipSuccess;
+}
+
+// The first call that needs the batch's tables waits (on the host) for the declaration's device work
+// and learns the verdict of the overlap check.  A batch that fails it is released.
+int finish_declare(tent_ctx* ctx, Batch& b)
+{
+    if (!b.decl_pending) return TENT_OK;
+    HIP_TRY(hipEventSynchronize(b.decl_event));
+    b.decl_pending = false;
+    if (*b.verdict != 0) {
+        wait_batch_idle(b);
+        free_batch(ctx, b);
+        return TENT_ERR_INVALID;
+    }
+    return TENT_OK;
 }
 
 // Telemetry -> integer coefficients (Eq. 1 with the topology penalty folded in).
@@ -227,6 +450,7 @@ int convert_rails(const tent_rail_state* rails, uint32_t n_rails, uint64_t pendi
     uint64_t max_c1 = 0, max_A = 0;
     for (uint32_t d = 0; d < n_rails; ++d) {
         const tent_rail_state& r = rails[d];
+        if (r.health > 2) return TENT_ERR_INVALID;
         if (r.bw_MBps == 0) return TENT_ERR_RANGE;
         const uint64_t bp = (uint64_t)r.beta1_q8 * r.penalty_q8;
         // a degraded rail keeps half its weight: its predicted cost counts twice (Section 4.3)
@@ -245,6 +469,214 @@ int convert_rails(const tent_rail_state* rails, uint32_t n_rails, uint64_t pendi
     // (max A + pending bytes) * max c1 must stay below 2^63 so that no cost wraps
     const unsigned __int128 worst = ((unsigned __int128)max_A + pending_bytes) * max_c1;
     if (worst >= ((unsigned __int128)1 << 63)) return TENT_ERR_RANGE;
+    return TENT_OK;
+}
+
+int declare_impl(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const tent_extent* src_ext,
+                 const uint32_t* dst_ptr, const tent_extent* dst_ext, tent_batch_t* out)
+{
+    if (!ctx || !src_ptr || !src_ext || !dst_ptr || !dst_ext || !out || n_desc == 0) return TENT_ERR_INVALID;
+    *out = 0;
+    if (n_desc >= 0x7FFFFFFFu) return TENT_ERR_RANGE;
+    if (!pointers_ok(n_desc, src_ptr) || !pointers_ok(n_desc, dst_ptr)) return TENT_ERR_INVALID;
+    const uint64_t ns = src_ptr[n_desc], nd = dst_ptr[n_desc];
+    if (ns + nd >= 0xFFFFFFFFull) return TENT_ERR_RANGE;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+
+    // Host arrays -> pinned buffer (laid out as they will lie in the upload): both pointer arrays,
+    // both extent lists, then the device view of the batch.
+    const uint64_t ptr_bytes = ((uint64_t)n_desc + 1) * sizeof(uint32_t);
+    const uint64_t o_sp = 0, o_dp = (o_sp + ptr_bytes + 15) & ~15ull, o_se = (o_dp + ptr_bytes + 15) & ~15ull;
+    const uint64_t o_de = o_se + ns * sizeof(tent_extent), o_self = o_de + nd * sizeof(tent_extent);
+    const uint64_t stage_need = o_self + sizeof(BatchDev);
+    int which = -1;
+    uint8_t* st = acquire_stage(ctx, stage_need, &which);
+    if (!st) return TENT_ERR_NOMEM;
+
+    uint64_t payload = 0, n_slices = 0, len_bits = 0, max_req_slices = 0;
+    int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, (tent_extent*)(st + o_se),
+                      (tent_extent*)(st + o_de), &payload, &n_slices, &len_bits, &max_req_slices);
+    if (rc != TENT_OK) return rc;
+    if (n_slices >= 0xFFFFFFFEull) return TENT_ERR_RANGE;
+
+    // reuse a dead slot or append
+    size_t slot = ctx->batches.size();
+    for (size_t k = 0; k < ctx->batches.size(); ++k) if (!ctx->batches[k].alive) { slot = k; break; }
+    if (slot == ctx->batches.size()) {
+        try { ctx->batches.emplace_back(); } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
+        if (!init_slot(ctx->batches[slot])) {
+            destroy_slot(ctx->batches[slot]);
+            ctx->batches.pop_back();
+            return TENT_ERR_NOMEM;
+        }
+    }
+    Batch& b = ctx->batches[slot];
+    renew_slot(b);
+    b.payload = payload;
+    b.max_req_slices = max_req_slices;
+    BatchDev& d = b.dev;
+    d.n_desc = n_desc;
+    d.n_src_ext = ns;
+    d.n_dst_ext = nd;
+    d.n_slices = n_slices;
+    d.slice_bytes = ctx->cfg.slice_bytes;
+    d.seg_base = ctx->seg_base_dev;
+    // Tile size: the largest power of two in [1 KiB, 4 KiB] that divides the slice size and every
+    // extent length, so that no tile crosses an extent boundary; geometry that allows no such size
+    // gets 1 KiB tiles, and the tiles that do cross a boundary take the generic copy path.
+    {
+        const uint64_t bits = len_bits | d.slice_bytes | kCopyBlockBytes;
+        uint32_t tile = (uint32_t)(bits & (~bits + 1));
+        d.tile_bytes = tile < 1024 ? 1024 : tile;
+        d.tiles_per_slice = (uint32_t)((d.slice_bytes + d.tile_bytes - 1) / d.tile_bytes);
+    }
+    const uint64_t n_tiles = n_slices * d.tiles_per_slice;
+    // Destination-ordered scatter needs every boundary on a tile boundary (addresses may have any
+    // alignment); other geometry keeps the slice-ordered scatter.
+    {
+        const uint64_t bits = len_bits | d.slice_bytes;
+        d.n_sc_tiles = (bits & (d.tile_bytes - 1)) == 0 ? payload / d.tile_bytes : 0;
+    }
+
+    uint32_t *sp = nullptr, *dp = nullptr;
+    tent_extent *se = nullptr, *de = nullptr;
+    const uint64_t scan_n = std::max<uint64_t>(std::max(ns, nd), std::max<uint64_t>(n_slices, n_desc));
+    BatchDev* self_dev = nullptr;
+    uint32_t* order_dev = nullptr;
+    uint32_t* rank_dev = nullptr;
+    Carver cv;
+    cv.want(&sp, (uint64_t)n_desc + 1);
+    cv.want(&dp, (uint64_t)n_desc + 1);
+    cv.want(&se, ns);
+    cv.want(&de, nd);
+    cv.want(&d.src_pre, ns + 1);
+    cv.want(&d.dst_pre, nd + 1);
+    cv.want(&d.first, (uint64_t)n_desc + 1);
+    cv.want(&d.s_desc, n_slices);
+    cv.want(&d.s_off, n_slices);
+    cv.want(&d.s_len, n_slices);
+    cv.want(&d.s_src_e0, n_slices);
+    cv.want(&d.s_dst_e0, n_slices);
+    cv.want(&d.s_rail, n_slices);
+    cv.want(&d.s_stage_off, n_slices);
+    cv.want(&d.s_state, n_slices);
+    cv.want(&d.s_tau, n_slices);
+    cv.want(&d.s_rec, n_slices);
+    cv.want(&d.s_retry, n_slices);
+    cv.want(&d.priority, (uint64_t)n_desc);
+    cv.want(&d.req_mode, (uint64_t)n_desc);
+    cv.want(&self_dev, 1);
+    cv.want(&b.overlap_dev, 1);
+    if (d.n_sc_tiles == 0) {                              // per-slice tile tables only for untiled geometry
+        cv.want(&d.src_tile, n_tiles);
+        cv.want(&d.dst_tile, n_tiles);
+    }
+    d.run_capacity = 2u * n_desc;
+    d.run_stride = ctx->max_rails;
+    cv.want(&d.run_start, (uint64_t)d.run_capacity + 1);
+    cv.want(&d.run_T, (uint64_t)d.run_capacity * d.run_stride);
+    cv.want(&d.run_K, (uint64_t)d.run_capacity * d.run_stride);
+    cv.want(&order_dev, nd);
+    cv.want(&rank_dev, nd);
+    if (d.n_sc_tiles) {
+        cv.want(&d.ord_pre, nd + 1);
+        cv.want(&d.ga_src, d.n_sc_tiles);
+        cv.want(&d.ga_lin, d.n_sc_tiles);
+        cv.want(&d.ga_slice, d.n_sc_tiles);
+        cv.want(&d.ga_x, d.n_sc_tiles);
+        if (ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING) cv.want(&d.ga_dst, d.n_sc_tiles);
+        // an execute goes over a list of tiles only when at most half of the batch's tiles can move
+        d.act_capacity = d.n_sc_tiles / 2 + 1;
+        cv.want(&d.tile_scan, n_slices + 1);
+        cv.want(&d.tile_partials, scan_partials_capacity(n_slices));
+        cv.want(&d.act_src, d.act_capacity);
+        cv.want(&d.act_lin, d.act_capacity);
+        cv.want(&d.act_dst, d.act_capacity);
+        cv.want(&d.sc_dst, d.n_sc_tiles);
+        cv.want(&d.sc_lin, d.n_sc_tiles);
+        cv.want(&d.sc_slice, d.n_sc_tiles);
+        cv.want(&d.sc_x, d.n_sc_tiles);
+    }
+    if (ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING) {
+        cv.want(&d.ch_lo, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
+        cv.want(&d.ch_hi, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
+        cv.want(&d.ch_base, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
+    }
+    cv.want(&d.pending, n_slices);
+    cv.want(&d.retry_ids, n_slices);
+    const uint64_t rot_chunks = (n_slices + kRotChunk - 1) / kRotChunk;
+    cv.want(&d.rot_bytes, rot_chunks * TENT_MAX_RAILS);
+    cv.want(&d.rot_cnt, rot_chunks * TENT_MAX_RAILS);
+    cv.want(&d.scan_tmp, scan_n + 1);
+    cv.want(&d.scan_partials, scan_partials_capacity(scan_n));
+    cv.want(&d.plan, 1);
+    if (cv.overflow) return TENT_ERR_NOMEM;
+
+    // destination extents in address order (for the scatter) and the overlap check run on the device
+    const bool check = !(ctx->cfg.flags & TENT_FLAG_SKIP_OVERLAP_CHECK);
+    const bool order = check || d.n_sc_tiles != 0;
+    uint64_t ws_need = 0;
+    if (order && order_workspace_bytes(nd, ns, check, &ws_need) != hipSuccess) { (void)hipGetLastError(); return TENT_ERR_HIP; }
+    const uint64_t table_bytes = cv.total();
+    void* workspace = nullptr;
+    {
+        rc = acquire_block(ctx, table_bytes, &b.block, &b.block_bytes);
+        if (rc != TENT_OK) return rc;
+        if (ws_need > ctx->order_ws_bytes) {
+            // the stream that used the old workspace is the context's own: wait for it, then replace
+            (void)hipStreamSynchronize(ctx->decl_stream);
+            if (ctx->order_ws) (void)hipFree(ctx->order_ws);
+            ctx->order_ws = nullptr;
+            ctx->order_ws_bytes = 0;
+            const uint64_t want = ws_need + ws_need / 4;
+            if (hipMalloc(&ctx->order_ws, want) != hipSuccess) {
+                (void)hipGetLastError();
+                ctx->order_ws = nullptr;
+                free_batch(ctx, b);
+                return TENT_ERR_NOMEM;
+            }
+            ctx->order_ws_bytes = want;
+        }
+        workspace = ctx->order_ws;
+    }
+    cv.place(b.block);
+    d.src_ptr = sp; d.dst_ptr = dp; d.src_ext = se; d.dst_ext = de;
+    d.dst_order = order_dev;
+    d.dst_rank = rank_dev;
+    d.self = self_dev;
+
+    // Everything from here on is enqueued on the context's own stream; nothing waits for the device.
+    hipStream_t ds = ctx->decl_stream;
+    std::memcpy(st + o_sp, src_ptr, ptr_bytes);
+    std::memcpy(st + o_dp, dst_ptr, ptr_bytes);
+    std::memcpy(st + o_self, &d, sizeof(BatchDev));
+    bool ok = hipMemcpyAsync(sp, st + o_sp, ptr_bytes, hipMemcpyHostToDevice, ds) == hipSuccess &&
+              hipMemcpyAsync(dp, st + o_dp, ptr_bytes, hipMemcpyHostToDevice, ds) == hipSuccess &&
+              hipMemcpyAsync(se, st + o_se, ns * sizeof(tent_extent), hipMemcpyHostToDevice, ds) == hipSuccess &&
+              hipMemcpyAsync(de, st + o_de, nd * sizeof(tent_extent), hipMemcpyHostToDevice, ds) == hipSuccess &&
+              hipMemcpyAsync(self_dev, st + o_self, sizeof(BatchDev), hipMemcpyHostToDevice, ds) == hipSuccess &&
+              hipEventRecord(ctx->stage_event[which], ds) == hipSuccess;
+    if (ok) ctx->stage_busy[which] = true;
+    ok = ok && hipMemsetAsync(d.s_retry, 0, std::max<uint64_t>(n_slices, 1), ds) == hipSuccess &&
+         hipMemsetAsync(d.req_mode, 0, n_desc, ds) == hipSuccess &&
+         hipMemsetAsync(d.plan, 0, sizeof(PlanState), ds) == hipSuccess &&
+         hipMemsetAsync(b.overlap_dev, 0, sizeof(uint32_t), ds) == hipSuccess;
+    if (ok && order)
+        ok = device_order_destinations(de, nd, se, ns, ctx->seg_base_dev, check, order_dev, rank_dev, b.overlap_dev,
+                                       workspace, ds) == hipSuccess;
+    *b.verdict = 0;
+    ok = ok && hipMemcpyAsync(b.verdict, b.overlap_dev, sizeof(uint32_t), hipMemcpyDeviceToHost, ds) == hipSuccess &&
+         hipEventRecord(b.decl_event, ds) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        (void)hipStreamSynchronize(ds);
+        free_batch(ctx, b);
+        return TENT_ERR_HIP;
+    }
+    b.decl_pending = true;
+    b.alive = true;
+    *out = ((uint64_t)b.generation << 32) | (uint64_t)(slot + 1);
     return TENT_OK;
 }
 
@@ -279,12 +711,21 @@ int tent_create(tent_ctx** out, const tent_config* cfg)
     ctx->max_rails = cfg->max_rails ? cfg->max_rails : TENT_MAX_RAILS;
     if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return TENT_ERR_HIP; }
     ctx->seg_capacity = kMaxSegments;
-    if (hipMalloc((void**)&ctx->seg_base_dev, sizeof(uint64_t) * ctx->seg_capacity) != hipSuccess ||
-        hipHostMalloc((void**)&ctx->host_plan, sizeof(PlanState), hipHostMallocDefault) != hipSuccess) {
+    bool ok = true;
+    try { ctx->spare.reserve(kSpareBlocks); ctx->batches.reserve(16); } catch (const std::bad_alloc&) { ok = false; }
+    ok = ok && hipMalloc((void**)&ctx->seg_base_dev, sizeof(uint64_t) * ctx->seg_capacity) == hipSuccess &&
+         hipHostMalloc((void**)&ctx->host_plan, sizeof(PlanState), hipHostMallocDefault) == hipSuccess &&
+         hipStreamCreateWithFlags(&ctx->decl_stream, hipStreamNonBlocking) == hipSuccess;
+    for (int k = 0; k < 2 && ok; ++k) {
+        ok = hipHostMalloc((void**)&ctx->stage[k], kStageInitial, hipHostMallocDefault) == hipSuccess &&
+             hipEventCreateWithFlags(&ctx->stage_event[k], hipEventDisableTiming) == hipSuccess;
+        if (ok) ctx->stage_bytes[k] = kStageInitial;
+    }
+    const int rc = ok ? TENT_OK : TENT_ERR_NOMEM;
+    if (rc != TENT_OK) {
         (void)hipGetLastError();
-        if (ctx->seg_base_dev) (void)hipFree(ctx->seg_base_dev);
-        delete ctx;
-        return TENT_ERR_NOMEM;
+        (void)tent_destroy(ctx);
+        return rc;
     }
     *out = ctx;
     return TENT_OK;
@@ -295,10 +736,20 @@ int tent_destroy(tent_ctx* ctx)
     if (!ctx) return TENT_ERR_INVALID;
     DeviceGuard g(ctx->device);
     (void)hipDeviceSynchronize();
-    for (Batch& b : ctx->batches) if (b.alive) free_batch(b);
+    for (Batch& b : ctx->batches) {
+        if (b.alive) free_batch(ctx, b);
+        destroy_slot(b);
+    }
+    for (Block& blk : ctx->spare) (void)hipFree(blk.ptr);
     for (Timing& t : ctx->timing)
         for (auto& pr : t.pool) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
     for (hipEvent_t e : ctx->sync_events) (void)hipEventDestroy(e);
+    for (int k = 0; k < 2; ++k) {
+        if (ctx->stage[k]) (void)hipHostFree(ctx->stage[k]);
+        if (ctx->stage_event[k]) (void)hipEventDestroy(ctx->stage_event[k]);
+    }
+    if (ctx->order_ws) (void)hipFree(ctx->order_ws);
+    if (ctx->decl_stream) (void)hipStreamDestroy(ctx->decl_stream);
     if (ctx->aux_stream) (void)hipStreamDestroy(ctx->aux_stream);
     if (ctx->seg_base_dev) (void)hipFree(ctx->seg_base_dev);
     if (ctx->host_plan) (void)hipHostFree(ctx->host_plan);
@@ -324,162 +775,7 @@ int tent_register_segment(tent_ctx* ctx, void* dev_base, uint64_t len, uint32_t*
 int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const tent_extent* src_ext,
                  const uint32_t* dst_ptr, const tent_extent* dst_ext, tent_batch_t* out)
 {
-    if (!ctx || !src_ptr || !src_ext || !dst_ptr || !dst_ext || !out || n_desc == 0) return TENT_ERR_INVALID;
-    *out = 0;
-    uint64_t payload = 0, n_slices = 0, len_bits = 0, max_req_slices = 0;
-    int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, &payload, &n_slices, &len_bits, &max_req_slices);
-    if (rc != TENT_OK) return rc;
-    if (n_slices >= 0xFFFFFFFEull || n_desc >= 0x7FFFFFFFu) return TENT_ERR_RANGE;
-    const uint64_t ns = src_ptr[n_desc], nd = dst_ptr[n_desc];
-    if (ns + nd >= 0xFFFFFFFFull) return TENT_ERR_RANGE;
-    DeviceGuard g(ctx->device);
-    if (!g.ok) return TENT_ERR_HIP;
-
-    // reuse a dead slot or append
-    size_t slot = ctx->batches.size();
-    for (size_t k = 0; k < ctx->batches.size(); ++k) if (!ctx->batches[k].alive) { slot = k; break; }
-    if (slot == ctx->batches.size()) {
-        try { ctx->batches.emplace_back(); } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
-    }
-    Batch& b = ctx->batches[slot];
-    const uint32_t gen = b.generation + 1;
-    b = Batch{};
-    b.generation = gen;
-    b.payload = payload;
-    b.max_req_slices = max_req_slices;
-    BatchDev& d = b.dev;
-    d.n_desc = n_desc;
-    d.n_src_ext = ns;
-    d.n_dst_ext = nd;
-    d.n_slices = n_slices;
-    d.slice_bytes = ctx->cfg.slice_bytes;
-    d.seg_base = ctx->seg_base_dev;
-    // Tile size: the largest power of two in [1 KiB, 4 KiB] that divides the slice size and every
-    // extent length, so that no tile crosses an extent boundary; geometry that allows no such size
-    // gets 1 KiB tiles, and the tiles that do cross a boundary take the generic copy path.
-    {
-        const uint64_t bits = len_bits | d.slice_bytes | kCopyBlockBytes;
-        uint32_t tile = (uint32_t)(bits & (~bits + 1));
-        d.tile_bytes = tile < 1024 ? 1024 : tile;
-        d.tiles_per_slice = (uint32_t)((d.slice_bytes + d.tile_bytes - 1) / d.tile_bytes);
-    }
-    const uint64_t n_tiles = n_slices * d.tiles_per_slice;
-    // Destination-ordered scatter needs every boundary on a tile boundary (addresses may have any
-    // alignment); other geometry keeps the slice-ordered scatter.
-    {
-        const uint64_t bits = len_bits | d.slice_bytes;
-        d.n_sc_tiles = (bits & (d.tile_bytes - 1)) == 0 ? payload / d.tile_bytes : 0;
-    }
-
-    uint32_t *sp = nullptr, *dp = nullptr;
-    tent_extent *se = nullptr, *de = nullptr;
-    const uint64_t scan_n = std::max<uint64_t>(std::max(ns, nd), std::max<uint64_t>(n_slices, n_desc));
-    BatchDev* self_dev = nullptr;
-    uint32_t* order_dev = nullptr;
-    uint32_t* rank_dev = nullptr;
-    Carver cv;
-    try {
-        cv.want(&sp, (uint64_t)n_desc + 1);
-        cv.want(&dp, (uint64_t)n_desc + 1);
-        cv.want(&se, ns);
-        cv.want(&de, nd);
-        cv.want(&d.src_pre, ns + 1);
-        cv.want(&d.dst_pre, nd + 1);
-        cv.want(&d.first, (uint64_t)n_desc + 1);
-        cv.want(&d.s_desc, n_slices);
-        cv.want(&d.s_off, n_slices);
-        cv.want(&d.s_len, n_slices);
-        cv.want(&d.s_src_e0, n_slices);
-        cv.want(&d.s_dst_e0, n_slices);
-        cv.want(&d.s_rail, n_slices);
-        cv.want(&d.s_stage_off, n_slices);
-        cv.want(&d.s_state, n_slices);
-        cv.want(&d.s_tau, n_slices);
-        cv.want(&d.s_rec, n_slices);
-        cv.want(&d.s_retry, n_slices);
-        cv.want(&d.priority, (uint64_t)n_desc);
-        cv.want(&d.req_mode, (uint64_t)n_desc);
-        cv.want(&self_dev, 1);
-        if (d.n_sc_tiles == 0) {                              // per-slice tile tables only for untiled geometry
-            cv.want(&d.src_tile, n_tiles);
-            cv.want(&d.dst_tile, n_tiles);
-        }
-        d.run_capacity = 2u * n_desc;
-        d.run_stride = ctx->max_rails;
-        cv.want(&d.run_start, (uint64_t)d.run_capacity + 1);
-        cv.want(&d.run_T, (uint64_t)d.run_capacity * d.run_stride);
-        cv.want(&d.run_K, (uint64_t)d.run_capacity * d.run_stride);
-        cv.want(&order_dev, nd);
-        cv.want(&rank_dev, nd);
-        if (d.n_sc_tiles) {
-            cv.want(&d.ord_pre, nd + 1);
-            cv.want(&d.ga_src, d.n_sc_tiles);
-            cv.want(&d.ga_lin, d.n_sc_tiles);
-            cv.want(&d.ga_slice, d.n_sc_tiles);
-            cv.want(&d.ga_x, d.n_sc_tiles);
-            if (ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING) {
-                cv.want(&d.ga_dst, d.n_sc_tiles);
-                cv.want(&d.ch_lo, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
-                cv.want(&d.ch_hi, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
-                cv.want(&d.ch_base, (uint64_t)kMaxChunks * TENT_MAX_RAILS);
-            }
-            // an execute goes over a list of tiles only when at most half of the batch's tiles can move
-            d.act_capacity = d.n_sc_tiles / 2 + 1;
-            cv.want(&d.tile_scan, n_slices + 1);
-            cv.want(&d.tile_partials, scan_partials_capacity(n_slices));
-            cv.want(&d.act_src, d.act_capacity);
-            cv.want(&d.act_lin, d.act_capacity);
-            cv.want(&d.act_dst, d.act_capacity);
-            cv.want(&d.sc_dst, d.n_sc_tiles);
-            cv.want(&d.sc_lin, d.n_sc_tiles);
-            cv.want(&d.sc_slice, d.n_sc_tiles);
-            cv.want(&d.sc_x, d.n_sc_tiles);
-        }
-        cv.want(&d.pending, n_slices);
-        cv.want(&d.retry_ids, n_slices);
-        const uint64_t rot_chunks = (n_slices + kRotChunk - 1) / kRotChunk;
-        cv.want(&d.rot_bytes, rot_chunks * TENT_MAX_RAILS);
-        cv.want(&d.rot_cnt, rot_chunks * TENT_MAX_RAILS);
-        cv.want(&d.scan_tmp, scan_n + 1);
-        cv.want(&d.scan_partials, scan_partials_capacity(scan_n));
-        cv.want(&d.plan, 1);
-        rc = cv.commit(b);
-    } catch (const std::bad_alloc&) {
-        rc = TENT_ERR_NOMEM;
-    }
-    if (rc != TENT_OK) { free_batch(b); return rc; }
-    d.src_ptr = sp; d.dst_ptr = dp; d.src_ext = se; d.dst_ext = de;
-    d.dst_order = order_dev;
-    d.dst_rank = rank_dev;
-    d.self = self_dev;
-
-    if (hipMemcpy(sp, src_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(dp, dst_ptr, sizeof(uint32_t) * ((uint64_t)n_desc + 1), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(se, src_ext, sizeof(tent_extent) * ns, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(de, dst_ext, sizeof(tent_extent) * nd, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(self_dev, &d, sizeof(BatchDev), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemset(d.s_retry, 0, std::max<uint64_t>(n_slices, 1)) != hipSuccess ||
-        hipMemset(d.req_mode, 0, n_desc) != hipSuccess ||
-        hipMemset(d.plan, 0, sizeof(PlanState)) != hipSuccess) {
-        (void)hipGetLastError();
-        free_batch(b);
-        return TENT_ERR_HIP;
-    }
-    // destination extents in address order (for the scatter) and the overlap check, on the device
-    const bool check = !(ctx->cfg.flags & TENT_FLAG_SKIP_OVERLAP_CHECK);
-    if (check || d.n_sc_tiles) {
-        uint32_t overlap = 0;
-        if (device_order_destinations(de, nd, se, ns, ctx->seg_base_dev, check, order_dev, rank_dev, &overlap, nullptr) !=
-            hipSuccess) {
-            (void)hipGetLastError();
-            free_batch(b);
-            return TENT_ERR_HIP;
-        }
-        if (overlap) { free_batch(b); return TENT_ERR_INVALID; }
-    }
-    b.alive = true;
-    *out = ((uint64_t)b.generation << 32) | (uint64_t)(slot + 1);
-    return TENT_OK;
+    return declare_impl(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, out);
 }
 
 int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, uint32_t n_rails,
@@ -488,18 +784,21 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     if (!ctx || !rails) return TENT_ERR_INVALID;
     Batch* b = find_batch(ctx, batch);
     if (!b) return TENT_ERR_INVALID;
+    if (b->broken) return TENT_ERR_STATE;
     if (n_rails == 0 || n_rails > ctx->max_rails) return TENT_ERR_RANGE;
     RailParams rp;
     int rc = convert_rails(rails, n_rails, b->payload, &rp);
     if (rc != TENT_OK) return rc;
+    DeviceGuard g(ctx->device);
+    if (!g.ok) return TENT_ERR_HIP;
+    rc = finish_declare(ctx, *b);
+    if (rc != TENT_OK) return rc;
     if (rp.admitted == 0) return TENT_DEFER;
     if (!(ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING) && b->payload + 256ull * n_rails > ctx->cfg.staging_bytes)
         return TENT_ERR_RANGE;
-
-    DeviceGuard g(ctx->device);
-    if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BatchDev& d = b->dev;
+    StreamNote note(*b, s);
     HIP_TRY(order_after_execute_bookkeeping(*b, s));
 
     // Retry rotation (Section 4.3, "Link-Level Resilience"): candidates are the HEALTHY rails, else the
@@ -585,11 +884,18 @@ int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state*
     if (!ctx || !rails || !params) return TENT_ERR_INVALID;
     Batch* b = find_batch(ctx, batch);
     if (!b) return TENT_ERR_INVALID;
+    if (b->broken) return TENT_ERR_STATE;
     if (n_rails == 0 || n_rails > ctx->max_rails) return TENT_ERR_RANGE;
     if (params->gamma_q8 > 65535u) return TENT_ERR_RANGE;
     RailParams rp;
     int rc = convert_rails(rails, n_rails, b->payload, &rp);
     if (rc != TENT_OK) return rc;
+    {
+        DeviceGuard g0(ctx->device);
+        if (!g0.ok) return TENT_ERR_HIP;
+        rc = finish_declare(ctx, *b);
+        if (rc != TENT_OK) return rc;
+    }
     if (rp.admitted == 0) return TENT_DEFER;
     if (!(ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING) && b->payload + 256ull * n_rails > ctx->cfg.staging_bytes)
         return TENT_ERR_RANGE;
@@ -627,6 +933,7 @@ int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state*
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BatchDev& d = b->dev;
+    StreamNote note(*b, s);
     HIP_TRY(order_after_execute_bookkeeping(*b, s));
     dp.all_high = priority ? 0u : 1u;
     if (priority) HIP_TRY(hipMemcpyAsync(d.priority, priority, d.n_desc, hipMemcpyHostToDevice, s));
@@ -733,6 +1040,7 @@ int tent_sim_fail(tent_ctx* ctx, tent_batch_t batch, const uint8_t* rail_failed,
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    StreamNote note(*b, s);
     if (any) {
         HIP_TRY(launch_fail(b->dev, fp, s));
         b->has_retry = true;
@@ -781,6 +1089,7 @@ int tent_sim_latency(tent_ctx* ctx, tent_batch_t batch, const uint32_t* true_bw_
     if (max_q >= (1ull << 53) || b->payload >= (1ull << 53) || max_q + b->payload >= (1ull << 53)) return TENT_ERR_RANGE;
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
+    StreamNote note(*b, static_cast<hipStream_t>(stream));
     HIP_TRY(launch_sim_latency(b->dev, lp, static_cast<hipStream_t>(stream)));
     return TENT_OK;
 }
@@ -836,11 +1145,12 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     if (!ctx) return TENT_ERR_INVALID;
     Batch* b = find_batch(ctx, batch);
     if (!b) return TENT_ERR_INVALID;
-    if (!b->planned) return TENT_ERR_STATE;
+    if (!b->planned || b->broken) return TENT_ERR_STATE;
     if (b->payload + 256ull * b->last_rails.n_rails > ctx->cfg.staging_bytes) return TENT_ERR_RANGE;
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    StreamNote note(*b, s);
     // When the host knows that only a small part of the batch is BOUND (after the rail simulator), the
     // copies run over a list of the tiles of the BOUND slices and their launches are sized by that part.
     const uint64_t max_tiles = b->bound_hint * b->dev.tiles_per_slice;
@@ -848,23 +1158,35 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     HIP_TRY(launch_finalize(b->dev, static_cast<uint8_t*>(ctx->cfg.staging_arena), compact, max_tiles, s));
     // The copies below are driven by the tables just written and read no slice state, so the slices
     // are marked DONE ahead of them: in stream order nothing changes, and the next re-plan, if it
-    // is enqueued on another stream, can run beside the copies.
+    // is enqueued on another stream, can run beside the copies.  tent_poll, on whatever stream, waits
+    // for the end of the copies (done_event), so a slice is never reported complete while its bytes move.
     HIP_TRY(launch_mark_done(b->dev, compact, s));
-    HIP_TRY(record_execute_bookkeeping(*b, s));
-    {
-        StageTimer t(ctx, TENT_T_GATHER, s);
-        if (compact)                HIP_TRY(launch_copy_compact(b->dev, true, max_tiles, s));
-        else if (b->dev.n_sc_tiles) HIP_TRY(launch_copy_ordered(b->dev, true, s));
-        else                        HIP_TRY(launch_copy(b->dev, true, s));
-    }
-    {
-        StageTimer t(ctx, TENT_T_SCATTER, s);
-        if (compact)                HIP_TRY(launch_copy_compact(b->dev, false, max_tiles, s));
-        else if (b->dev.n_sc_tiles) HIP_TRY(launch_copy_ordered(b->dev, false, s));
-        else                        HIP_TRY(launch_copy(b->dev, false, s));
-    }
+    // From here on a failure would leave slices marked DONE whose bytes were never moved: the batch
+    // is then flagged, and every call but tent_reset and tent_release refuses it.
+    auto copies = [&]() -> hipError_t {
+        hipError_t e = record_execute_bookkeeping(*b, s);
+        if (e != hipSuccess) return e;
+        {
+            StageTimer t(ctx, TENT_T_GATHER, s);
+            e = compact ? launch_copy_compact(b->dev, true, max_tiles, s)
+                : b->dev.n_sc_tiles ? launch_copy_ordered(b->dev, true, s) : launch_copy(b->dev, true, s);
+        }
+        if (e != hipSuccess) return e;
+        {
+            StageTimer t(ctx, TENT_T_SCATTER, s);
+            e = compact ? launch_copy_compact(b->dev, false, max_tiles, s)
+                : b->dev.n_sc_tiles ? launch_copy_ordered(b->dev, false, s) : launch_copy(b->dev, false, s);
+        }
+        if (e != hipSuccess) return e;
+        return record_execute_done(*b, s);
+    };
     b->has_done = true;
     b->bound_hint = 0;
+    if (copies() != hipSuccess) {
+        (void)hipGetLastError();
+        b->broken = true;
+        return TENT_ERR_HIP;
+    }
     return TENT_OK;
 }
 
@@ -873,11 +1195,11 @@ int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes
     if (!ctx) return TENT_ERR_INVALID;
     Batch* b = find_batch(ctx, batch);
     if (!b) return TENT_ERR_INVALID;
-    if (!b->planned || !(ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING)) return TENT_ERR_STATE;
+    if (!b->planned || b->broken || !(ctx->cfg.flags & TENT_FLAG_BOUNDED_STAGING)) return TENT_ERR_STATE;
     const BatchDev& d = b->dev;
-    // chunks are cut on 1 MiB boundaries so that 256 consecutive tiles never straddle two chunks
+    // chunks are cut on 1 MiB boundaries so that the 256 consecutive tiles (or four consecutive 1 KiB
+    // ranges) of one workgroup never straddle two chunks
     if (chunk_bytes == 0 || (chunk_bytes & ((1ull << 20) - 1)) != 0 || slots < 1 || slots > 2) return TENT_ERR_INVALID;
-    if (d.n_sc_tiles == 0) return TENT_ERR_RANGE;             // geometry: some length is not a multiple of 1 KiB
     const uint64_t slot_bytes = chunk_bytes + 256ull * b->last_rails.n_rails;
     if (slot_bytes > ctx->cfg.staging_bytes / slots) return TENT_ERR_RANGE;
     const uint64_t n_chunks = (b->payload + chunk_bytes - 1) / chunk_bytes;
@@ -885,17 +1207,19 @@ int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    StreamNote note(*b, s);
     uint8_t* arena = static_cast<uint8_t*>(ctx->cfg.staging_arena);
-    HIP_TRY(launch_bounded_prepare(d, chunk_bytes, (uint32_t)n_chunks, slot_bytes, slots, arena, s));
+    const uint64_t payload = b->payload;
+    HIP_TRY(launch_bounded_prepare(d, payload, chunk_bytes, (uint32_t)n_chunks, slot_bytes, slots, arena, s));
     if (slots == 1) {
         for (uint32_t c = 0; c < n_chunks; ++c) {
             {
                 StageTimer t(ctx, TENT_T_GATHER, s);
-                HIP_TRY(launch_bounded_copy(d, true, c, chunk_bytes, s));
+                HIP_TRY(launch_bounded_copy(d, true, c, payload, chunk_bytes, slot_bytes, slots, arena, s));
             }
             {
                 StageTimer t(ctx, TENT_T_SCATTER, s);
-                HIP_TRY(launch_bounded_copy(d, false, c, chunk_bytes, s));
+                HIP_TRY(launch_bounded_copy(d, false, c, payload, chunk_bytes, slot_bytes, slots, arena, s));
             }
         }
     } else {
@@ -926,13 +1250,13 @@ int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes
             if (c >= 2) HIP_TRY(hipStreamWaitEvent(s, ctx->sync_events[2 * (c - 2) + 1], 0));
             {
                 StageTimer t(ctx, TENT_T_GATHER, s);
-                HIP_TRY(launch_bounded_copy(d, true, c, chunk_bytes, s));
+                HIP_TRY(launch_bounded_copy(d, true, c, payload, chunk_bytes, slot_bytes, slots, arena, s));
             }
             HIP_TRY(hipEventRecord(gathered, s));
             HIP_TRY(hipStreamWaitEvent(x, gathered, 0));
             {
                 StageTimer t(ctx, TENT_T_SCATTER, x);
-                HIP_TRY(launch_bounded_copy(d, false, c, chunk_bytes, x));
+                HIP_TRY(launch_bounded_copy(d, false, c, payload, chunk_bytes, slot_bytes, slots, arena, x));
             }
             HIP_TRY(hipEventRecord(scattered, x));
         }
@@ -944,6 +1268,7 @@ int tent_execute_bounded(tent_ctx* ctx, tent_batch_t batch, uint64_t chunk_bytes
     b->prep_recorded = false;                                 // the bounded execute offers no overlap with a re-plan
     b->has_done = true;
     b->bound_hint = 0;
+    HIP_TRY(record_execute_done(*b, s));
     return TENT_OK;
 }
 
@@ -952,10 +1277,14 @@ int tent_poll(tent_ctx* ctx, tent_batch_t batch, uint64_t* remaining, void* stre
     if (!ctx || !remaining) return TENT_ERR_INVALID;
     Batch* b = find_batch(ctx, batch);
     if (!b) return TENT_ERR_INVALID;
+    if (b->broken) return TENT_ERR_STATE;
     if (!b->planned) { *remaining = b->dev.n_slices; return TENT_OK; }
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    // slices are marked DONE ahead of their copies: completion is only reported once the last
+    // execute's copies have ended, whichever stream the caller polls on
+    if (b->done_recorded && s != b->exec_stream) HIP_TRY(hipStreamWaitEvent(s, b->done_event, 0));
     HIP_TRY(launch_count_remaining(b->dev, s));
     HIP_TRY(hipMemcpyAsync(ctx->host_plan, b->dev.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
@@ -970,10 +1299,17 @@ int tent_reset(tent_ctx* ctx, tent_batch_t batch, void* stream)
     if (!b) return TENT_ERR_INVALID;
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
-    if (b->planned) HIP_TRY(launch_reset(b->dev, static_cast<hipStream_t>(stream)));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (b->planned) {
+        StreamNote note(*b, s);
+        // the reset must not overtake the copies of an execute that runs on another stream
+        if (b->done_recorded && s != b->exec_stream && !capturing(s)) HIP_TRY(hipStreamWaitEvent(s, b->done_event, 0));
+        HIP_TRY(launch_reset(b->dev, s));
+    }
     b->planned = false;
     b->has_done = false;
     b->has_retry = false;
+    b->broken = false;
     return TENT_OK;
 }
 
@@ -1048,8 +1384,8 @@ int tent_release(tent_ctx* ctx, tent_batch_t batch)
     if (!b) return TENT_ERR_INVALID;
     DeviceGuard g(ctx->device);
     if (!g.ok) return TENT_ERR_HIP;
-    (void)hipDeviceSynchronize();
-    free_batch(*b);
+    wait_batch_idle(*b);
+    free_batch(ctx, *b);
     return TENT_OK;
 }
 

@@ -145,7 +145,7 @@ struct BatchDev {
     uint32_t* ga_slice;            // [n_sc_tiles] slice that holds the tile
     uint32_t* ga_x;                // [n_sc_tiles] byte offset of the tile inside that slice
     uint64_t* ga_dst;              // [n_sc_tiles] destination address of the tile in declaration order (bounded staging only)
-    uint64_t* ch_lo;               // [kMaxChunks * TENT_MAX_RAILS] bounded staging: first staging offset per chunk and rail
+    uint64_t* ch_lo;               // [kMaxChunks * TENT_MAX_RAILS] bounded staging (any geometry): first staging offset per chunk and rail
     uint64_t* ch_hi;               // same shape: end of the interval
     uint64_t* ch_base;             // same shape: region base inside the arena
     uint64_t* tile_scan;           // [n_slices+1] scan workspace of the per-execute tile list: tiles of the BOUND slices before slice i
@@ -196,9 +196,10 @@ hipError_t launch_bind_serial(const BatchDev& b, const RailParams& rp, int mode,
 hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, hipStream_t s);
 hipError_t launch_rotate(const BatchDev& b, const RotateParams& rot, hipStream_t s);
 hipError_t launch_fail(const BatchDev& b, const FailParams& fp, hipStream_t s);
-hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t chunk_bytes, uint32_t n_chunks, uint64_t slot_bytes,
-                                  uint32_t slots, uint8_t* arena, hipStream_t s);
-hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t chunk_bytes, hipStream_t s);
+hipError_t launch_bounded_prepare(const BatchDev& b, uint64_t payload, uint64_t chunk_bytes, uint32_t n_chunks,
+                                  uint64_t slot_bytes, uint32_t slots, uint8_t* arena, hipStream_t s);
+hipError_t launch_bounded_copy(const BatchDev& b, bool gather, uint32_t chunk, uint64_t payload, uint64_t chunk_bytes,
+                               uint64_t slot_bytes, uint32_t slots, uint8_t* arena, hipStream_t s);
 hipError_t launch_mark_done_bounded(const BatchDev& b, hipStream_t s);
 hipError_t launch_dispatch(const BatchDev& b, const RailParams& rp, const DispatchParams& dp, bool build_tables,
                            hipStream_t s);
@@ -217,8 +218,9 @@ hipError_t launch_probe(const BatchDev& b, const ProbeParams& pp, hipStream_t s)
 
 uint64_t scan_partials_capacity(uint64_t n);
 
+hipError_t order_workspace_bytes(uint64_t n_dst, uint64_t n_src, bool check, uint64_t* bytes_out);
 hipError_t device_order_destinations(const tent_extent* dst_ext, uint64_t n_dst, const tent_extent* src_ext,
                                      uint64_t n_src, const uint64_t* seg_base, bool check, uint32_t* order_out,
-                                     uint32_t* rank_out, uint32_t* overlap_out, hipStream_t s);
+                                     uint32_t* rank_out, uint32_t* overlap_dev, void* workspace, hipStream_t s);
 
 }  // namespace tent

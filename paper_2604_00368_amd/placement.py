@@ -186,19 +186,29 @@ def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: 
         raise ValueError(f"unknown placement mode {mode!r}")
     lay = Layout("plain", "ordinary allocations")
     if mode == "regions":
+        sizes = (src_bytes, arena_bytes, dst_bytes)
+        torch.cuda.empty_cache()                          # blocks the caching allocator still holds count as used
         free, _total = torch.cuda.mem_get_info(device)
-        want = (free - keep_free if reserve_bytes is None else reserve_bytes) // chunk_bytes * chunk_bytes
-        block = None
-        if want < src_bytes + arena_bytes + dst_bytes or want < 2 * chunk_bytes:
-            lay.note = "not enough free device memory for a reservation"
-        else:
+        first = (free - keep_free if reserve_bytes is None else reserve_bytes) // chunk_bytes * chunk_bytes
+        # A reservation of nearly the whole device can fail (or map one region only) in a process that has
+        # allocated and freed a lot before; smaller reservations are tried before giving up, and every
+        # attempt leaves its reason in the layout's note.
+        attempts, notes = [], []
+        for num, den in ((1, 1), (3, 4), (1, 2)):
+            want = first * num // den // chunk_bytes * chunk_bytes
+            if want not in attempts:
+                attempts.append(want)
+        for want in attempts:
+            if want < sum(sizes) or want < 2 * chunk_bytes:
+                notes.append(f"{want >> 30} GiB: too small for the pools")
+                continue
             try:
                 block = torch.empty(want, dtype=torch.uint8, device=device)
             except RuntimeError as exc:                   # out of memory
-                lay.note = f"reservation failed ({type(exc).__name__})"
-        if block is not None:
+                notes.append(f"{want >> 30} GiB: reservation failed ({type(exc).__name__})")
+                torch.cuda.empty_cache()
+                continue
             n_chunks = want // chunk_bytes
-            sizes = (src_bytes, arena_bytes, dst_bytes)
             total_probes = 0
             for repeats in (3, 8):                        # a second, more patient pass if the first map does not hold up
                 pair_ms, window_ms = _probe_factory(block, chunk_bytes, probe_bytes, repeats)
@@ -213,17 +223,21 @@ def place_pools(device, src_bytes: int, arena_bytes: int, dst_bytes: int, mode: 
                 if offs is not None and (verified or min(sizes) < probe_bytes):
                     break
             if offs is None:
-                lay.note = ("one region found: nothing to choose" if len(set(labels)) < 2
-                            else "no placement with the partners in different regions")
+                notes.append(f"{want >> 30} GiB: " + ("one region found (map " + "".join(str(x) for x in labels) + ")"
+                                                      if len(set(labels)) < 2 else
+                                                      "no placement with the partners in different regions (map "
+                                                      + "".join(str(x) for x in labels) + ")"))
                 del block
                 torch.cuda.empty_cache()
-            else:
-                lay = Layout("regions", "pools carved from one reservation by measured region: source and staging arena "
-                             "in different regions, staging arena and destination in different regions",
-                             want, chunk_bytes, labels, offs, total_probes, verified)
-                o_src, o_arena, o_dst = offs
-                return (block[o_src:o_src + src_bytes], block[o_arena:o_arena + arena_bytes],
-                        block[o_dst:o_dst + dst_bytes], lay)
+                continue
+            lay = Layout("regions", "pools carved from one reservation by measured region: source and staging arena "
+                         "in different regions, staging arena and destination in different regions"
+                         + ("" if not notes else "; earlier attempts: " + "; ".join(notes)),
+                         want, chunk_bytes, labels, offs, total_probes, verified)
+            o_src, o_arena, o_dst = offs
+            return (block[o_src:o_src + src_bytes], block[o_arena:o_arena + arena_bytes],
+                    block[o_dst:o_dst + dst_bytes], lay)
+        lay.note = "ordinary allocations, no region layout: " + "; ".join(notes)
     src = torch.empty(src_bytes, dtype=torch.uint8, device=device)
     dst = torch.empty(dst_bytes, dtype=torch.uint8, device=device)
     arena = torch.empty(arena_bytes, dtype=torch.uint8, device=device)

@@ -126,15 +126,79 @@ def test_bounded_argument_errors(H, oracle):
         T.tent_execute_bounded(eng.ctx, h, 2 * MiB, eng.stream)
         torch.cuda.synchronize()
         assert T.tent_poll(eng.ctx, h, eng.stream) == 0
-    wr = W.ragged(3)                                           # odd lengths: no tile size fits
-    with H.Engine(wr, W.fill_numpy(wr, 0), W.fill_numpy(wr, 1), flags=T.TENT_FLAG_BOUNDED_STAGING) as eng:
-        h = eng.declare()
-        eng.plan()
-        with pytest.raises(T.TentError) as ei:
-            T.tent_execute_bounded(eng.ctx, h, MiB, eng.stream)
-        assert ei.value.status == T.TENT_ERR_RANGE
-        eng.execute()                                          # the arena holds the payload: plain execute still works
-        assert T.tent_poll(eng.ctx, h, eng.stream) == 0
+
+
+@pytest.mark.parametrize("slots", [1, 2])
+@pytest.mark.parametrize("seed,kw", [(3, {}), (4, dict(n_desc=9, max_len=1_500_000, slice_bytes=65536 + 3)),
+                                     (5, dict(n_desc=40, max_len=90_000, slice_bytes=1, max_ext=7)),
+                                     (6, dict(n_desc=6, max_len=3_000_000, slice_bytes=1 << 20, max_ext=1 << 18)),
+                                     (7, dict(n_desc=30, max_len=300_000, slice_bytes=5000, align=8))])
+def test_bounded_execute_ragged_geometry_bit_exact(H, oracle, seed, kw, slots):
+    # lengths that are no multiple of any tile size (1-byte slices, 1-byte extents, source and destination cut
+    # differently): the chunks are moved byte-exactly in ranges of 1 KiB; arena and destination against the oracle
+    from paper_2604_00368_amd import binding as T
+    w = W.ragged(seed, **kw)
+    R = w.rails.shape[0]
+    chunk = MiB
+    assert chunk < w.payload
+    slot = chunk + 256 * R
+    cap = slots * slot
+    src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    b = oracle.bind(s.len, w.rails)
+    dst_want, staging_want = dst0.copy(), np.zeros(cap, dtype=np.uint8)
+    assert oracle.execute_bounded(w, s, b, [src, dst_want], staging_want, chunk, slots=slots, slot_bytes=slot) == 0
+    print("ragged bounded", seed, "payload", w.payload, "slices", s.n, "chunks", -(-w.payload // chunk), flush=True)
+    with H.Engine(w, src, dst0, flags=T.TENT_FLAG_BOUNDED_STAGING, arena_bytes=cap, arena_skew=seed % 3) as eng:
+        eng.declare()
+        st, info = eng.plan()
+        assert st == 0
+        H.assert_plan_equal(eng.table(), s, b, info)
+        T.tent_execute_bounded(eng.ctx, eng.batch, chunk, eng.stream, slots=slots)
+        eng.stream.synchronize()
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+        assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+        assert np.array_equal(eng.src.cpu().numpy(), src)
+
+
+def test_bounded_execute_ragged_partial_sets(H, oracle):
+    # re-planning epochs on ragged geometry: only the slices that stayed bound move, the rest is re-planned
+    from paper_2604_00368_amd import binding as T
+    w = W.ragged(11, n_desc=16, max_len=600_000, slice_bytes=30_000 + 1)
+    w.rails["health"] = 0
+    R = w.rails.shape[0]
+    chunk = MiB
+    slot = chunk + 256 * R
+    src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    dst_want, staging_want = dst0.copy(), np.zeros(slot, dtype=np.uint8)
+    pending = np.arange(s.n, dtype=np.uint32)
+    rng = np.random.Generator(np.random.PCG64(77))
+    with H.Engine(w, src, dst0, flags=T.TENT_FLAG_BOUNDED_STAGING, arena_bytes=slot) as eng:
+        eng.declare()
+        for epoch in range(12):
+            if pending.shape[0] == 0:
+                break
+            rails = w.rails.copy()
+            rails["queued_bytes"] = rng.integers(0, 1 << 16, size=R)
+            b = oracle.bind(s.len, rails, ids=pending)
+            share = 1.0 if epoch >= 6 else 0.4
+            budget = (rails["queued_bytes"] + (b.T * share).astype(np.uint64)).astype(np.uint64)
+            done = oracle.retire(s, b, rails["queued_bytes"], budget, ids=pending).astype(bool)
+            ids = np.ascontiguousarray(pending[done])
+            if ids.shape[0]:
+                assert oracle.execute_bounded(w, s, b, [src, dst_want], staging_want, chunk, ids=ids, slot_bytes=slot) == 0
+            st, info = eng.plan(rails=rails)
+            assert st == 0 and info.n_slices == pending.shape[0]
+            assert T.tent_sim_advance(eng.ctx, eng.batch, budget, eng.stream) == ids.shape[0]
+            T.tent_execute_bounded(eng.ctx, eng.batch, chunk, eng.stream)
+            eng.stream.synchronize()
+            assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+            assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+            pending = np.ascontiguousarray(pending[~done])
+            assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == pending.shape[0]
+        assert pending.shape[0] == 0
 
 
 def test_bounded_execute_after_dispatch_with_odd_addresses(H, oracle):

@@ -123,8 +123,10 @@ def test_full_size_config_in_the_benchmarks_pool_layout(H, oracle):
     src, arena, dst, lay = placement.place_pools(dev, w.seg_bytes[0], w.staging_bytes, w.seg_bytes[1])
     print("  layout:", lay.mode, lay.note, "".join(str(x) for x in lay.labels), [o >> 30 for o in lay.offsets], flush=True)
     if lay.mode != "regions":
-        del src, arena, dst
-        pytest.skip("no region layout here: " + lay.note)
+        # bench.py would run in these very pools (ordinary allocations): the parity check is the same and is
+        # not skipped; the reason is kept in the test's output
+        import warnings
+        warnings.warn("no region layout in this process, parity checked in ordinary allocations: " + lay.note)
     s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
     b = oracle.bind(s.len, w.rails)
     eng = H.Engine(w, flags=T.TENT_FLAG_PROFILE, pools=(src, arena, dst))

@@ -2,6 +2,7 @@
 import numpy as np
 import pytest
 
+from helpers import expected_destination
 from paper_2604_00368_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -297,12 +298,28 @@ def test_defer_errors_and_reuse(H, oracle):
         se = w.src_ext.copy(); se["len"][0] += 16                                   # source longer than destination
         with pytest.raises(T.TentError):
             declare(w.src_ptr, se, w.dst_ptr, w.dst_ext)
+        # overlaps are found on the device while tent_declare has already returned: the first plan on
+        # the batch delivers the verdict and releases the batch
         de = w.dst_ext.copy(); de["off"][1] = de["off"][0] + 100                    # overlapping destinations
+        hb = declare(w.src_ptr, w.src_ext, w.dst_ptr, de)
+        with pytest.raises(T.TentError) as ei:
+            T.tent_plan(eng.ctx, hb, w.rails, True, eng.stream)
+        assert ei.value.status == T.TENT_ERR_INVALID
         with pytest.raises(T.TentError):
-            declare(w.src_ptr, w.src_ext, w.dst_ptr, de)
+            T.tent_slice_count(eng.ctx, hb)                                         # the handle is dead
         de = w.dst_ext.copy(); de["seg"][:] = 0                                     # destination on top of sources
-        with pytest.raises(T.TentError):
-            declare(w.src_ptr, w.src_ext, w.dst_ptr, de)
+        hb = declare(w.src_ptr, w.src_ext, w.dst_ptr, de)
+        with pytest.raises(T.TentError) as ei:
+            T.tent_plan_dispatch(eng.ctx, hb, w.rails, W.make_dispatch_params(1 << 20), None, True, eng.stream)
+        assert ei.value.status == T.TENT_ERR_INVALID
+        # a health value the header does not define
+        bad = w.rails.copy(); bad["health"][2] = 3
+        with pytest.raises(T.TentError) as ei:
+            eng.plan(rails=bad)
+        assert ei.value.status == T.TENT_ERR_INVALID
+        with pytest.raises(T.TentError) as ei:
+            T.tent_plan_dispatch(eng.ctx, h, bad, W.make_dispatch_params(1 << 20), None, True, eng.stream)
+        assert ei.value.status == T.TENT_ERR_INVALID
         sp = w.src_ptr.copy(); sp[5] = sp[4]                                        # empty transfer
         with pytest.raises(T.TentError):
             declare(sp, w.src_ext, w.dst_ptr, w.dst_ext)
@@ -470,3 +487,72 @@ def test_unaligned_addresses_take_the_fast_paths(H, oracle, skew, arena_skew):
     run_and_compare(H, oracle, w, arena_skew=arena_skew)
     w = W.many_small(n_req=24, layers=2)
     run_and_compare(H, oracle, w, arena_skew=arena_skew)
+
+
+def test_poll_on_another_stream_sees_the_bytes(H, oracle):
+    # Batch-level completion (Section 4.4) holds on every stream: a poll on a stream that never saw the
+    # execute returns 0 only once the copies have ended, so the destination read on that stream is complete.
+    from paper_2604_00368_amd import binding as T
+    w = W.small_variant("kv_migration")
+    src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
+    want = expected_destination(w, src, dst0)
+    other = torch.cuda.Stream()
+    with H.Engine(w, src, dst0) as eng:
+        h = eng.declare()
+        for rep in range(3):
+            st, _ = eng.plan()
+            assert st == 0
+            T.tent_execute(eng.ctx, h, eng.stream)             # no synchronisation of the execute's stream
+            assert T.tent_poll(eng.ctx, h, other) == 0
+            with torch.cuda.stream(other):
+                got = eng.dst.clone()
+            other.synchronize()
+            assert np.array_equal(got.cpu().numpy(), want), rep
+            torch.cuda.synchronize()
+            # release without any wait of the caller's: the library waits for the batch's own work
+            eng.dst.copy_(torch.from_numpy(dst0))
+            torch.cuda.synchronize()
+            T.tent_reset(eng.ctx, h, other)
+            other.synchronize()
+        st, _ = eng.plan()
+        T.tent_execute(eng.ctx, h, eng.stream)
+        T.tent_release(eng.ctx, h)
+        assert np.array_equal(eng.dst.cpu().numpy(), want)
+
+
+def test_declare_release_cycles_reuse_tables(H, oracle):
+    # a loop of declare ... release: later declarations take over the table allocations of released batches,
+    # of equal and of different sizes, and every batch still plans and moves correctly
+    from paper_2604_00368_amd import binding as T
+    ws = [W.small_variant("kv_migration"), W.tiny(), W.small_variant("many_small"), W.tiny(), W.small_variant("kv_migration")]
+    wbig = ws[0]
+    src_big = W.fill_numpy(wbig, 0)
+    with H.Engine(wbig, src_big, np.zeros(wbig.seg_bytes[1], dtype=np.uint8)) as eng:
+        s = oracle.split(wbig.src_ptr, wbig.src_ext, wbig.slice_bytes)
+        b = oracle.bind(s.len, wbig.rails)
+        want = expected_destination(wbig, src_big, np.zeros(wbig.seg_bytes[1], dtype=np.uint8))
+        handles = []
+        for k in range(7):
+            h = eng.declare()
+            st, info = eng.plan()
+            assert st == 0
+            H.assert_plan_equal(eng.table(), s, b, info)
+            eng.dst.zero_()
+            T.tent_execute(eng.ctx, h, eng.stream)
+            if k % 2:
+                T.tent_release(eng.ctx, h)                     # straight after the execute was enqueued
+                assert np.array_equal(eng.dst.cpu().numpy(), want)
+            else:
+                handles.append(h)
+        for h in handles:
+            assert T.tent_poll(eng.ctx, h, eng.stream) == 0
+            T.tent_release(eng.ctx, h)
+    for w in ws:                                              # different geometries through one process
+        src, dst0 = W.fill_numpy(w, 0), W.fill_numpy(w, 1)
+        with H.Engine(w, src, dst0) as eng:
+            for _ in range(2):
+                h = eng.declare()
+                st, _ = eng.plan()
+                eng.execute()
+                assert np.array_equal(eng.dst.cpu().numpy(), expected_destination(w, src, dst0))
+                T.tent_release(eng.ctx, h)
