@@ -58,6 +58,7 @@ typedef enum {
 } tent_status;
 
 enum { TENT_MAX_RAILS = 64 };
+enum { TENT_STATIC_WORKSPACE_BYTES = 64 << 20 };   /* static device array behind tent_declare_static, per GPU */
 
 /* tent_config.flags */
 enum {
@@ -209,6 +210,29 @@ int tent_declare(tent_ctx *ctx, uint32_t n_desc,
                  const uint32_t *src_ptr, const tent_extent *src_ext,
                  const uint32_t *dst_ptr, const tent_extent *dst_ext,
                  tent_batch_t *out);
+
+/*
+ * tent_declare for callers that cannot allocate: code that runs where hipMalloc is forbidden (tight
+ * serving loops, harnesses that ban allocation, set-up phases of graph-driven pipelines).  Same
+ * arguments, same checks and the same batch as tent_declare, but the batch's device tables and the
+ * workspace of the address sort are carved from a static device array of the library
+ * (TENT_STATIC_WORKSPACE_BYTES = 64 MiB per GPU, held by every GPU the library runs on until the
+ * process ends) and the call allocates nothing, neither on the device nor on the host; host arrays
+ * larger than the context's pinned buffer are uploaded through it piece by piece, each piece waited for.
+ * TENT_ERR_RANGE when tables plus workspace exceed the static array (about 75 bytes per extent,
+ * 70 bytes per slice and 60 bytes per 4 KiB tile of payload: batches up to about 2 GiB of payload in
+ * 32 KiB pages fit).
+ * One static batch exists per GPU: the array keeps the last call's contents, and every call clears
+ * what must start at zero.  A new call from the same context waits for and replaces that context's
+ * previous static batch; a call from another context on the same GPU invalidates the other context's
+ * static batch (its handle turns TENT_ERR_INVALID) without waiting for it, so calls that overlap on
+ * one GPU race and are the caller's to order.  The returned handle works with every other entry
+ * point; tent_release gives the array up without freeing anything.
+ */
+int tent_declare_static(tent_ctx *ctx, uint32_t n_desc,
+                        const uint32_t *src_ptr, const tent_extent *src_ext,
+                        const uint32_t *dst_ptr, const tent_extent *dst_ext,
+                        tent_batch_t *out);
 
 /*
  * Split and bind (Section 4.2; Algorithm 1 Stages 1-2; Eq. 1).

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libtent.so")
 TENT_OK, TENT_DEFER = 0, 1
 TENT_ERR_INVALID, TENT_ERR_RANGE, TENT_ERR_STATE, TENT_ERR_NOMEM, TENT_ERR_HIP = -1, -2, -3, -4, -5
 TENT_MAX_RAILS = 64
+TENT_STATIC_WORKSPACE_BYTES = 64 << 20
 TENT_FLAG_SKIP_OVERLAP_CHECK, TENT_FLAG_PROFILE, TENT_FLAG_SERIAL_BINDING, TENT_FLAG_BOUNDED_STAGING = 1, 2, 4, 8
 TENT_SLICE_PENDING, TENT_SLICE_BOUND, TENT_SLICE_DONE = 0, 1, 2
 TENT_T_NAMES = ["extent_scan", "slice_scan", "expand", "compact", "bind", "gather", "scatter", "feedback"]
@@ -27,7 +28,7 @@ EXPORTS = ["tent_create", "tent_destroy", "tent_register_segment", "tent_declare
            "tent_sim_advance", "tent_sim_latency", "tent_update_bandwidth", "tent_get_latencies", "tent_execute", "tent_poll", "tent_reset", "tent_slice_count",
            "tent_get_plan", "tent_get_timings", "tent_release", "tent_strerror",
            "tent_sim_fail", "tent_get_retries", "tent_monitor_init", "tent_monitor_update",
-           "tent_plan_dispatch", "tent_get_modes", "tent_execute_bounded", "tent_probe_copy"]
+           "tent_plan_dispatch", "tent_get_modes", "tent_execute_bounded", "tent_probe_copy", "tent_declare_static"]
 
 
 class tent_config(C.Structure):
@@ -81,6 +82,7 @@ def lib():
         L.tent_register_segment.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint32)]
         L.tent_declare.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.POINTER(C.c_uint64)]
+        L.tent_declare_static.argtypes = L.tent_declare.argtypes
         L.tent_plan.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.POINTER(tent_plan_info),
                                 C.c_void_p]
         L.tent_sim_advance.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.POINTER(C.c_uint64), C.c_void_p]
@@ -155,6 +157,16 @@ def tent_declare(ctx, src_ptr, src_ext, dst_ptr, dst_ext) -> int:
     de, dep = _host(dst_ext, EXTENT_DTYPE)
     h = C.c_uint64()
     _check(lib().tent_declare(ctx, sp.shape[0] - 1, spp, sep, dpp, dep, C.byref(h)), "tent_declare")
+    return h.value
+
+
+def tent_declare_static(ctx, src_ptr, src_ext, dst_ptr, dst_ext) -> int:
+    sp, spp = _host(src_ptr, np.uint32)
+    dp, dpp = _host(dst_ptr, np.uint32)
+    se, sep = _host(src_ext, EXTENT_DTYPE)
+    de, dep = _host(dst_ext, EXTENT_DTYPE)
+    h = C.c_uint64()
+    _check(lib().tent_declare_static(ctx, sp.shape[0] - 1, spp, sep, dpp, dep, C.byref(h)), "tent_declare_static")
     return h.value
 
 

@@ -2,6 +2,7 @@
 // kernel sequencing.  Every step of the hot path itself runs in the HIP kernels of this library.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -9,6 +10,12 @@
 #include "tent_internal.h"
 
 using namespace tent;
+
+// Static workspace of tent_declare_static: callers that must not allocate get their batch's tables
+// here.  One copy per GPU, held until the process ends.  In host code the array's name is only a
+// stand-in: its address on a GPU is looked up once, with that GPU current, and host code uses the
+// looked-up pointer and nothing else.
+static __device__ __align__(256) unsigned char scratch[TENT_STATIC_WORKSPACE_BYTES];
 
 namespace {
 
@@ -44,9 +51,11 @@ struct Batch {
     // overlap check's result.
     bool decl_pending = false;
     uint32_t* overlap_dev = nullptr;
-    // Device memory of the tables: one allocation.
+    // Device memory of the tables: an allocation of the batch's own, or the library's static workspace.
     void* block = nullptr;
     uint64_t block_bytes = 0;
+    bool in_static = false;
+    uint64_t static_generation = 0;
     bool marks_lost = false;     // work was enqueued that no mark covers: waiting for the batch means waiting for the device
     BatchDev dev{};
 
@@ -74,6 +83,7 @@ struct tent_ctx {
     uint64_t* seg_base_dev = nullptr;       // device table of segment base addresses
     uint32_t seg_capacity = 0;
     std::vector<Batch> batches;
+    Batch static_batch;                     // the one batch whose tables live in the static workspace
     PlanState* host_plan = nullptr;         // pinned read-back buffer
     hipStream_t aux_stream = nullptr;       // second stream of the pipelined bounded execute (default priority)
     std::vector<hipEvent_t> sync_events;    // ordering events of the pipelined bounded execute, reused
@@ -97,6 +107,17 @@ constexpr uint32_t kMaxSegments = 4096;
 constexpr size_t kMaxTimedIntervals = 1u << 16;   // per stage, between two tent_get_timings calls
 constexpr size_t kSpareBlocks = 4;                // released table allocations kept for reuse
 constexpr uint64_t kStageInitial = 1ull << 20;    // pinned bytes per staging buffer at tent_create
+constexpr uint32_t kStaticSlot = 0xFFFFFFFFu;     // slot field of a handle whose tables live in the static workspace
+
+constexpr uint64_t kStaticBytes = TENT_STATIC_WORKSPACE_BYTES;
+struct StaticArea {
+    void* ptr = nullptr;         // device address of `scratch` on this GPU
+    uint64_t generation = 0;     // goes up with every tent_declare_static on this GPU: older static batches are dead
+};
+constexpr int kMaxDevices = 64;
+StaticArea g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) return TENT_ERR_HIP; } while (0)
 
 struct DeviceGuard {
@@ -197,7 +218,7 @@ void renew_slot(Batch& b)
 // similar size; what the context cannot keep is freed).  The caller has waited for the batch.
 void free_batch(tent_ctx* ctx, Batch& b)
 {
-    if (b.block) {
+    if (b.block && !b.in_static) {
         bool kept = false;
         if (ctx->spare.size() < kSpareBlocks) {
             try { ctx->spare.push_back({b.block, b.block_bytes}); kept = true; } catch (const std::bad_alloc&) {}
@@ -228,6 +249,18 @@ Batch* find_batch(tent_ctx* ctx, tent_batch_t h)
 {
     const uint64_t idx = (h & 0xFFFFFFFFull);
     const uint32_t gen = (uint32_t)(h >> 32);
+    if (idx == kStaticSlot) {
+        Batch* b = &ctx->static_batch;
+        if (!b->alive || b->generation != gen) return nullptr;
+        // a later tent_declare_static on this GPU (from any context) has taken the workspace over
+        uint64_t now = 0;
+        {
+            std::lock_guard<std::mutex> lk(g_static_mutex);
+            now = ctx->device < kMaxDevices ? g_static[ctx->device].generation : 0;
+        }
+        if (now != b->static_generation) { b->alive = false; return nullptr; }
+        return b;
+    }
     if (idx == 0 || idx > ctx->batches.size()) return nullptr;
     Batch* b = &ctx->batches[idx - 1];
     return (b->alive && b->generation == gen) ? b : nullptr;
@@ -292,8 +325,9 @@ int acquire_block(tent_ctx* ctx, uint64_t need, void** out, uint64_t* out_bytes)
 }
 
 // Pinned buffer for the host arrays of one declaration: the two buffers are used in turn, so a
-// declaration seldom has to wait for the upload of the one before.
-uint8_t* acquire_stage(tent_ctx* ctx, uint64_t need, int* which)
+// declaration seldom has to wait for the upload of the one before.  With `may_grow` unset a buffer
+// that is too small is reported (nullptr) instead of being replaced.
+uint8_t* acquire_stage(tent_ctx* ctx, uint64_t need, bool may_grow, int* which)
 {
     const int k = (int)(ctx->stage_turn & 1);
     if (ctx->stage_busy[k]) {
@@ -301,6 +335,7 @@ uint8_t* acquire_stage(tent_ctx* ctx, uint64_t need, int* which)
         ctx->stage_busy[k] = false;
     }
     if (ctx->stage_bytes[k] < need) {
+        if (!may_grow) return nullptr;
         uint8_t* p = nullptr;
         const uint64_t want = need + need / 4;
         if (hipHostMalloc((void**)&p, want, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
@@ -311,6 +346,27 @@ uint8_t* acquire_stage(tent_ctx* ctx, uint64_t need, int* which)
     ++ctx->stage_turn;
     *which = k;
     return ctx->stage[k];
+}
+
+// Host array -> device through the pinned buffer whose turn it is, one buffer-full at a time, waiting
+// for each piece (used when the buffer cannot hold a declaration's arrays and must not be replaced).
+bool upload_in_pieces(tent_ctx* ctx, void* dev, const void* host, uint64_t bytes)
+{
+    const int k = (int)(ctx->stage_turn & 1);
+    if (ctx->stage_busy[k]) {
+        if (hipEventSynchronize(ctx->stage_event[k]) != hipSuccess) return false;
+        ctx->stage_busy[k] = false;
+    }
+    const uint64_t cap = ctx->stage_bytes[k];
+    if (cap == 0) return false;
+    for (uint64_t at = 0; at < bytes; at += cap) {
+        const uint64_t n = std::min(cap, bytes - at);
+        std::memcpy(ctx->stage[k], static_cast<const uint8_t*>(host) + at, n);
+        if (hipMemcpyAsync(static_cast<uint8_t*>(dev) + at, ctx->stage[k], n, hipMemcpyHostToDevice, ctx->decl_stream) != hipSuccess ||
+            hipStreamSynchronize(ctx->decl_stream) != hipSuccess)
+            return false;
+    }
+    return true;
 }
 
 // CSR pointer arrays: start at 0, strictly increasing (no empty transfer).
@@ -472,8 +528,11 @@ int convert_rails(const tent_rail_state* rails, uint32_t n_rails, uint64_t pendi
     return TENT_OK;
 }
 
+// tent_declare and tent_declare_static.  With `use_static` the tables and the sort's workspace are
+// carved from the static workspace of the context's GPU and nothing is allocated, on the device or
+// on the host.
 int declare_impl(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const tent_extent* src_ext,
-                 const uint32_t* dst_ptr, const tent_extent* dst_ext, tent_batch_t* out)
+                 const uint32_t* dst_ptr, const tent_extent* dst_ext, tent_batch_t* out, bool use_static)
 {
     if (!ctx || !src_ptr || !src_ext || !dst_ptr || !dst_ext || !out || n_desc == 0) return TENT_ERR_INVALID;
     *out = 0;
@@ -491,27 +550,39 @@ int declare_impl(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     const uint64_t o_de = o_se + ns * sizeof(tent_extent), o_self = o_de + nd * sizeof(tent_extent);
     const uint64_t stage_need = o_self + sizeof(BatchDev);
     int which = -1;
-    uint8_t* st = acquire_stage(ctx, stage_need, &which);
-    if (!st) return TENT_ERR_NOMEM;
+    uint8_t* st = acquire_stage(ctx, stage_need, !use_static, &which);
+    if (!st && !use_static) return TENT_ERR_NOMEM;
 
     uint64_t payload = 0, n_slices = 0, len_bits = 0, max_req_slices = 0;
-    int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, (tent_extent*)(st + o_se),
-                      (tent_extent*)(st + o_de), &payload, &n_slices, &len_bits, &max_req_slices);
+    int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, st ? (tent_extent*)(st + o_se) : nullptr,
+                      st ? (tent_extent*)(st + o_de) : nullptr, &payload, &n_slices, &len_bits, &max_req_slices);
     if (rc != TENT_OK) return rc;
     if (n_slices >= 0xFFFFFFFEull) return TENT_ERR_RANGE;
 
-    // reuse a dead slot or append
-    size_t slot = ctx->batches.size();
-    for (size_t k = 0; k < ctx->batches.size(); ++k) if (!ctx->batches[k].alive) { slot = k; break; }
-    if (slot == ctx->batches.size()) {
-        try { ctx->batches.emplace_back(); } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
-        if (!init_slot(ctx->batches[slot])) {
-            destroy_slot(ctx->batches[slot]);
-            ctx->batches.pop_back();
-            return TENT_ERR_NOMEM;
+    Batch* slot_b = nullptr;
+    size_t slot = 0;
+    if (use_static) {
+        slot_b = &ctx->static_batch;
+        if (slot_b->alive) {                              // the context's earlier static batch gives way
+            wait_batch_idle(*slot_b);
+            free_batch(ctx, *slot_b);
         }
+    } else {
+        // reuse a dead slot or append
+        slot = ctx->batches.size();
+        for (size_t k = 0; k < ctx->batches.size(); ++k) if (!ctx->batches[k].alive) { slot = k; break; }
+        if (slot == ctx->batches.size()) {
+            if (slot + 1 >= kStaticSlot) return TENT_ERR_RANGE;
+            try { ctx->batches.emplace_back(); } catch (const std::bad_alloc&) { return TENT_ERR_NOMEM; }
+            if (!init_slot(ctx->batches[slot])) {
+                destroy_slot(ctx->batches[slot]);
+                ctx->batches.pop_back();
+                return TENT_ERR_NOMEM;
+            }
+        }
+        slot_b = &ctx->batches[slot];
     }
-    Batch& b = ctx->batches[slot];
+    Batch& b = *slot_b;
     renew_slot(b);
     b.payload = payload;
     b.max_req_slices = max_req_slices;
@@ -620,7 +691,21 @@ int declare_impl(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     if (order && order_workspace_bytes(nd, ns, check, &ws_need) != hipSuccess) { (void)hipGetLastError(); return TENT_ERR_HIP; }
     const uint64_t table_bytes = cv.total();
     void* workspace = nullptr;
-    {
+    if (use_static) {
+        // both the tables and the sort's workspace must fit the static workspace
+        if (table_bytes + ws_need > kStaticBytes) return TENT_ERR_RANGE;
+        uint8_t* area = nullptr;
+        {
+            std::lock_guard<std::mutex> lk(g_static_mutex);
+            if (ctx->device >= kMaxDevices || !g_static[ctx->device].ptr) return TENT_ERR_STATE;
+            area = static_cast<uint8_t*>(g_static[ctx->device].ptr);
+            b.static_generation = ++g_static[ctx->device].generation;
+        }
+        b.block = area;
+        b.block_bytes = table_bytes;
+        b.in_static = true;
+        workspace = area + table_bytes;
+    } else {
         rc = acquire_block(ctx, table_bytes, &b.block, &b.block_bytes);
         if (rc != TENT_OK) return rc;
         if (ws_need > ctx->order_ws_bytes) {
@@ -646,18 +731,28 @@ int declare_impl(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     d.dst_rank = rank_dev;
     d.self = self_dev;
 
-    // Everything from here on is enqueued on the context's own stream; nothing waits for the device.
+    // Everything from here on is enqueued on the context's own stream; nothing waits for the device
+    // unless the host arrays could not go through the pinned buffer.
     hipStream_t ds = ctx->decl_stream;
-    std::memcpy(st + o_sp, src_ptr, ptr_bytes);
-    std::memcpy(st + o_dp, dst_ptr, ptr_bytes);
-    std::memcpy(st + o_self, &d, sizeof(BatchDev));
-    bool ok = hipMemcpyAsync(sp, st + o_sp, ptr_bytes, hipMemcpyHostToDevice, ds) == hipSuccess &&
-              hipMemcpyAsync(dp, st + o_dp, ptr_bytes, hipMemcpyHostToDevice, ds) == hipSuccess &&
-              hipMemcpyAsync(se, st + o_se, ns * sizeof(tent_extent), hipMemcpyHostToDevice, ds) == hipSuccess &&
-              hipMemcpyAsync(de, st + o_de, nd * sizeof(tent_extent), hipMemcpyHostToDevice, ds) == hipSuccess &&
-              hipMemcpyAsync(self_dev, st + o_self, sizeof(BatchDev), hipMemcpyHostToDevice, ds) == hipSuccess &&
-              hipEventRecord(ctx->stage_event[which], ds) == hipSuccess;
-    if (ok) ctx->stage_busy[which] = true;
+    bool ok = true;
+    if (st) {
+        std::memcpy(st + o_sp, src_ptr, ptr_bytes);
+        std::memcpy(st + o_dp, dst_ptr, ptr_bytes);
+        std::memcpy(st + o_self, &d, sizeof(BatchDev));
+        ok = hipMemcpyAsync(sp, st + o_sp, ptr_bytes, hipMemcpyHostToDevice, ds) == hipSuccess &&
+             hipMemcpyAsync(dp, st + o_dp, ptr_bytes, hipMemcpyHostToDevice, ds) == hipSuccess &&
+             hipMemcpyAsync(se, st + o_se, ns * sizeof(tent_extent), hipMemcpyHostToDevice, ds) == hipSuccess &&
+             hipMemcpyAsync(de, st + o_de, nd * sizeof(tent_extent), hipMemcpyHostToDevice, ds) == hipSuccess &&
+             hipMemcpyAsync(self_dev, st + o_self, sizeof(BatchDev), hipMemcpyHostToDevice, ds) == hipSuccess &&
+             hipEventRecord(ctx->stage_event[which], ds) == hipSuccess;
+        if (ok) ctx->stage_busy[which] = true;
+    } else {
+        // the pinned buffer is too small and may not grow: the arrays go through it piece by piece
+        ok = upload_in_pieces(ctx, sp, src_ptr, ptr_bytes) && upload_in_pieces(ctx, dp, dst_ptr, ptr_bytes) &&
+             upload_in_pieces(ctx, se, src_ext, ns * sizeof(tent_extent)) &&
+             upload_in_pieces(ctx, de, dst_ext, nd * sizeof(tent_extent)) &&
+             upload_in_pieces(ctx, self_dev, &d, sizeof(BatchDev));
+    }
     ok = ok && hipMemsetAsync(d.s_retry, 0, std::max<uint64_t>(n_slices, 1), ds) == hipSuccess &&
          hipMemsetAsync(d.req_mode, 0, n_desc, ds) == hipSuccess &&
          hipMemsetAsync(d.plan, 0, sizeof(PlanState), ds) == hipSuccess &&
@@ -676,7 +771,7 @@ int declare_impl(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     }
     b.decl_pending = true;
     b.alive = true;
-    *out = ((uint64_t)b.generation << 32) | (uint64_t)(slot + 1);
+    *out = ((uint64_t)b.generation << 32) | (use_static ? (uint64_t)kStaticSlot : (uint64_t)(slot + 1));
     return TENT_OK;
 }
 
@@ -715,13 +810,23 @@ int tent_create(tent_ctx** out, const tent_config* cfg)
     try { ctx->spare.reserve(kSpareBlocks); ctx->batches.reserve(16); } catch (const std::bad_alloc&) { ok = false; }
     ok = ok && hipMalloc((void**)&ctx->seg_base_dev, sizeof(uint64_t) * ctx->seg_capacity) == hipSuccess &&
          hipHostMalloc((void**)&ctx->host_plan, sizeof(PlanState), hipHostMallocDefault) == hipSuccess &&
-         hipStreamCreateWithFlags(&ctx->decl_stream, hipStreamNonBlocking) == hipSuccess;
+         hipStreamCreateWithFlags(&ctx->decl_stream, hipStreamNonBlocking) == hipSuccess &&
+         init_slot(ctx->static_batch);
     for (int k = 0; k < 2 && ok; ++k) {
         ok = hipHostMalloc((void**)&ctx->stage[k], kStageInitial, hipHostMallocDefault) == hipSuccess &&
              hipEventCreateWithFlags(&ctx->stage_event[k], hipEventDisableTiming) == hipSuccess;
         if (ok) ctx->stage_bytes[k] = kStageInitial;
     }
-    const int rc = ok ? TENT_OK : TENT_ERR_NOMEM;
+    // the static workspace's address on this GPU, looked up once per device with the device current
+    int rc = ok ? TENT_OK : TENT_ERR_NOMEM;
+    if (ok && ctx->device < kMaxDevices) {
+        std::lock_guard<std::mutex> lk(g_static_mutex);
+        if (!g_static[ctx->device].ptr) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) rc = TENT_ERR_HIP;
+            else g_static[ctx->device].ptr = p;
+        }
+    }
     if (rc != TENT_OK) {
         (void)hipGetLastError();
         (void)tent_destroy(ctx);
@@ -740,6 +845,8 @@ int tent_destroy(tent_ctx* ctx)
         if (b.alive) free_batch(ctx, b);
         destroy_slot(b);
     }
+    if (ctx->static_batch.alive) free_batch(ctx, ctx->static_batch);
+    destroy_slot(ctx->static_batch);
     for (Block& blk : ctx->spare) (void)hipFree(blk.ptr);
     for (Timing& t : ctx->timing)
         for (auto& pr : t.pool) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
@@ -775,7 +882,13 @@ int tent_register_segment(tent_ctx* ctx, void* dev_base, uint64_t len, uint32_t*
 int tent_declare(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const tent_extent* src_ext,
                  const uint32_t* dst_ptr, const tent_extent* dst_ext, tent_batch_t* out)
 {
-    return declare_impl(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, out);
+    return declare_impl(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, out, false);
+}
+
+int tent_declare_static(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const tent_extent* src_ext,
+                        const uint32_t* dst_ptr, const tent_extent* dst_ext, tent_batch_t* out)
+{
+    return declare_impl(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, out, true);
 }
 
 int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, uint32_t n_rails,
