@@ -138,236 +138,387 @@ __device__ __forceinline__ uint32_t slots_upto_fast(const Rail& r, uint64_t A, u
     return k;
 }
 
-// kWide = 16, 32 or 64: lanes that can hold a rail; with 16 every reduction stays inside one DPP row.
-// Runs in the first wavefront of a workgroup (lane = threadIdx.x < 64).
-template <int kWide>
-__device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& rp, int mode)
+// Smallest 32-bit key over the wavefront (keys carry a lane in their low 6 bits), as a uniform value.
+template <int R>
+__device__ __forceinline__ uint32_t wave_min_key(uint32_t key)
 {
-    const bool use_pending = (mode & kBindUsePending) != 0;
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_reduce32(key, R, Min32{}));
+}
+
+// True when p holds in any active lane.  The lane mask passes through a scalar register pair so that the
+// test is a scalar compare (a vector compare feeding a branch costs a lone wavefront several times more).
+__device__ __forceinline__ bool any_lane(bool p)
+{
+    uint64_t mask = __ballot(p);
+    asm volatile("" : "+s"(mask));
+    return mask != 0;
+}
+
+constexpr uint32_t kRelBits = 26;                      // costs within 2^26 ps of the level are compared as 32-bit keys
+constexpr uint64_t kRelSpan = 1ull << kRelBits;
+constexpr uint64_t kNoLevel = ~0ull;
+// The lean path sums slot counts in 32 bits: runs stay below 2^24 slices and a lane whose estimate cannot be
+// used adds 2^25 instead of its count, so that with up to 64 lanes the sum neither wraps nor comes near m.
+constexpr uint32_t kLeanRunMax = 1u << 24;
+constexpr uint32_t kOffMark = 1u << 25;
+
+// ---- step 1b: one record per run ---------------------------------------------------------------
+// Everything the chain needs to know about a run that does not depend on the rails' state, computed
+// in parallel before the chain starts; the chain fetches the records a block at a time.  The cost
+// level comes from the water-filling model: when every admitted rail takes part, all of them end a
+// run at a common cost level, and level(bytes) = (bytes + sum_d(g_d + A_d)) / sum_d G_d with
+// G_d = 65536 / c1_d bytes per picosecond and g_d = c0_d * G_d; the numerator's sum grows by exactly
+// the bytes bound, so the level after every run is known in advance.  It is an estimate: the chain
+// verifies what it derives from it in integers.
+struct PendingLen {
+    const uint32_t* s_len;
+    const uint32_t* pending;      // nullptr: position = slice index
+    const uint64_t* n_pending;
+    __device__ uint64_t operator()(uint64_t q) const
+    {
+        if (q >= *n_pending) return 0;
+        return s_len[pending ? pending[q] : (uint32_t)q];
+    }
+};
+
+__global__ void __launch_bounds__(256) run_records_kernel(BatchDev b, RailParams rp, int mode)
+{
+    const uint64_t n_runs = b.plan->n_runs;
+    const uint64_t r = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r > n_runs) return;
+    RunRec rec{0, 0, kNoLevel, 0.0, 0.0};
+    if (r < n_runs) {
+        const uint32_t start = b.run_start[r];
+        const uint32_t id = (mode & kBindUsePending) ? b.pending[start] : start;
+        rec.len = b.s_len[id];
+        rec.m = b.run_start[r + 1] - start;
+        rec.inv_len = 1.0 / (double)rec.len;
+        double sum_G = 0.0, sum_B = 0.0, n_live = 0.0;
+        for (uint32_t d = 0; d < rp.n_rails; ++d) {
+            if (!((rp.admitted >> d) & 1)) continue;
+            const double G = 65536.0 / (double)(uint32_t)rp.c1[d];      // c1 >= 1 on this path
+            const uint64_t A = rp.A[d] + ((mode & kBindAfterRotation) ? b.plan->Tr[d] : 0);
+            sum_G += G;
+            sum_B += (double)rp.c0[d] * G + (double)A;
+            n_live += 1.0;
+        }
+        const double v = (((double)rec.m + 0.5 * n_live) * (double)rec.len + (sum_B + (double)b.len_pre[start])) / sum_G;
+        if (v >= 0.0 && v < 1.0e14) {
+            rec.level = (uint64_t)v;
+            rec.level_f = (double)rec.level;
+        }
+    }
+    b.run_rec[r] = rec;
+}
+
+// ---- step 2: chain over runs ------------------------------------------------------------------
+// kWide = 16, 32 or 64: lanes that can hold a rail; with 16 every reduction stays inside one DPP row.
+// Runs in lanes 0 .. kWide-1 of the first wavefront of a workgroup; the other lanes leave at once.
+//
+// Per rail the chain keeps the exact product P = A * c1 of the bytes in flight (so that a slot's cost
+// is c0 + ((P + j * l * c1) >> 16) with additions only), the bytes bound T, and a floating-point
+// shadow of A for the estimates.  The loop is a chain of dependent instructions on one wavefront,
+// so what counts is how few it issues per run and that it never waits for memory: run records are
+// fetched kWide at a time, one per lane, a whole block ahead of their use, and handed out with
+// readlane; results leave as one row of K and one of T per run.  The general path sits in a function of
+// its own: inlined, its code and registers made the loop's short paths measurably slower.
+
+// State of one lane of the chain that a run may change, and the slots the lane takes in the run.
+struct ChainVars {
+    uint64_t P, T;
+    double Bd;
+    uint64_t ref_level;
+    uint32_t cnt, all_proven, k;
+};
+
+// A run of m slices of l bytes from any state and with any (or no) level estimate: the level is searched
+// with exact slot counts (bracket, interpolation, bisection) and the split repaired slot by slot.  Kept
+// out of line: the chain's loop calls it only where its short path does not apply.
+template <int kWide>
+__device__ __attribute__((noinline)) ChainVars bind_run_general(ChainVars cv, Rail rail, double G, double g, bool live,
+                                                               uint64_t live_mask, uint64_t A_less_T, int lane, uint32_t l,
+                                                               uint32_t m, uint64_t vi, double level_f, double inv_l)
+{
+    constexpr int R = kWide;
+    uint64_t P = cv.P, T = cv.T;
+    double Bd = cv.Bd;
+    uint64_t ref_level = cv.ref_level;
+    uint32_t cnt = cv.cnt;
+    bool all_proven = cv.all_proven != 0;
+    uint32_t k = 0, taken = 0;
+    const uint64_t A = A_less_T + T;
+    if (!all_proven) all_proven = __ballot(live && cnt > 0) == live_mask;
+    if (m > (uint32_t)kTol) {
+        double v;
+        if (vi != kNoLevel && all_proven) {
+            v = level_f;
+        } else {
+            // rails whose next slot already costs more than the level stay out of the pool
+            const uint64_t head = live ? slot_cost(rail, A, l, 0) : ~0ull;
+            bool wet = live;
+            v = 0.0;
+            for (int pass = 0; pass < 64; ++pass) {
+                const uint64_t wet_mask = __ballot(wet);
+                const double sumG = wave_sum_f64(wet ? G : 0.0, R);
+                const double sumB = wave_sum_f64(wet ? g + (double)A : 0.0, R);
+                const double need = ((double)m + 0.5 * (double)__popcll(wet_mask)) * (double)l;
+                v = __longlong_as_double((long long)uniform64((uint64_t)__double_as_longlong((need + sumB) / sumG)));
+                const bool still = wet && (cnt > 0 || (double)head <= v);
+                const uint64_t still_mask = __ballot(still);
+                if (still_mask == wet_mask || still_mask == 0) break;
+                wet = still;
+            }
+        }
+        // bracket (computed only if the first guess misses):
+        // slots summed over rails stay below m at `lo` and reach at least m at `hi`
+        bool bracketed = false;
+        int64_t lo = 0, hi = 0;
+        for (int iter = 0;; ++iter) {
+            int64_t vg = (v >= 0.0 && v < 9.0e18) ? (int64_t)v : -1;
+            if (!bracketed && vg < 0) {
+                const uint64_t head = live ? slot_cost(rail, A, l, 0) : ~0ull;
+                const uint64_t alone = live ? slot_cost(rail, A, l, m - 1) : ~0ull;
+                lo = (int64_t)uniform64(wave_reduce64(head, R, OpMin{})) - 1;
+                hi = (int64_t)uniform64(wave_reduce64(alone, R, OpMin{}));
+                bracketed = true;
+            }
+            if (bracketed && (iter >= 8 || vg <= lo || vg >= hi)) {   // guess unusable: bisect
+                vg = lo + (hi - lo) / 2;
+                if (vg <= lo) vg = hi;
+            }
+            const uint32_t kk = live ? slots_upto_fast(rail, A, l, inv_l, vg, m) : 0;
+            const uint64_t tt = uniform64(wave_reduce64(kk, R, OpAdd{}));
+            const int64_t miss = (int64_t)m - (int64_t)tt;
+            if (miss <= kTol && miss >= -kTol) { k = kk; taken = (uint32_t)tt; break; }
+            if (!bracketed) {
+                const uint64_t head = live ? slot_cost(rail, A, l, 0) : ~0ull;
+                const uint64_t alone = live ? slot_cost(rail, A, l, m - 1) : ~0ull;
+                lo = (int64_t)uniform64(wave_reduce64(head, R, OpMin{})) - 1;
+                hi = (int64_t)uniform64(wave_reduce64(alone, R, OpMin{}));
+                bracketed = true;
+            }
+            if (miss > 0) { if (vg > lo) lo = vg; } else { if (vg < hi) hi = vg; }
+            if (hi - lo == 1) {
+                // the whole deficit sits at cost `hi`: hand it out in rail order
+                const uint32_t k_lo = live ? slots_upto(rail, A, l, inv_l, lo, m) : 0;
+                const uint32_t k_hi = live ? slots_upto(rail, A, l, inv_l, hi, m) : 0;
+                const uint64_t below = uniform64(wave_reduce64(k_lo, R, OpAdd{}));
+                uint64_t tie = k_hi - k_lo, inc = tie;
+#pragma unroll
+                for (int d = 1; d < kWide; d <<= 1) {
+                    uint64_t up = (uint64_t)__shfl_up((unsigned long long)inc, d, 64);
+                    if (lane >= d) inc += up;
+                }
+                const uint64_t before = inc - tie;                 // ties on lower rails
+                const uint64_t rem = (uint64_t)m - below;
+                const uint64_t take = before >= rem ? 0 : (rem - before < tie ? rem - before : tie);
+                k = k_lo + (uint32_t)take;
+                taken = m;
+                break;
+            }
+            const bool near = live && (kk > 0 || slot_cost(rail, A, l, 0) <= (uint64_t)(vg < 0 ? 0 : vg) + 1);
+            double rate = wave_sum_f64(near ? G : 0.0, R);
+            if (!(rate > 0.0)) rate = wave_sum_f64(G, R);
+            v = __longlong_as_double((long long)uniform64(
+                (uint64_t)__double_as_longlong((double)vg + (double)miss * (double)l / rate)));
+        }
+    }
+    // repair: add the cheapest free slot / drop the dearest taken slot
+    while (taken < m) {
+        const int win = argmin_cost(slot_cost(rail, A, l, k), live && k < m, lane, R);
+        k += lane == win;
+        ++taken;
+    }
+    while (taken > m) {
+        const int win = argmax_cost(slot_cost(rail, A, l, k > 0 ? k - 1 : 0), live && k > 0, lane, R);
+        k -= lane == win;
+        --taken;
+    }
+    const uint64_t bytes = (uint64_t)k * l;
+    T += bytes;
+    cnt += k;
+    Bd = fma(-(double)k, (double)l, Bd);
+    P = (A + bytes) * (uint64_t)rail.c1;
+    ref_level = kNoLevel;
+    return ChainVars{P, T, Bd, ref_level, cnt, all_proven ? 1u : 0u, k};
+}
+
+typedef uint32_t Quad __attribute__((ext_vector_type(4)));       // half a run record: {len, m, level} or {level_f, inv_len}
+static_assert(sizeof(RunRec) == 32, "a run record is two 16-byte halves");
+
+template <int kWide>
+__device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& rp, int mode,
+                                           const RunRec* __restrict__ recs)
+{
     const int lane = threadIdx.x;
+    if (lane >= kWide) return;
     constexpr int R = kWide;                                  // reduction width
     const int n_rails = (int)rp.n_rails;
     const bool live = lane < n_rails && ((rp.admitted >> lane) & 1);
     const uint64_t live_mask = __ballot(live);
-    const double n_live = (double)__popcll(live_mask);
     Rail rail;
     rail.c0 = rp.c0[lane];
     rail.c1 = live ? (uint32_t)rp.c1[lane] : 1u;
     rail.inv_c1 = 1.0 / (double)rail.c1;
     const double G = live ? 65536.0 * rail.inv_c1 : 0.0;      // bytes the rail absorbs per picosecond
     const double g = (double)rail.c0 * G;                     // its fixed latency expressed in bytes
-    const double c0d1 = 1.0 - (double)rail.c0;               // 1 - c0 as a double (c0 < 2^53)
-    uint64_t A = rp.A[lane], T = 0, cnt = 0;
+    uint64_t T = 0;
+    uint32_t cnt = 0;                                         // a batch holds fewer than 2^32 - 1 slices
     uint64_t n_before = 0;
     if (mode & kBindAfterRotation) {          // the rotation pass went first: its bytes are queued and staged ahead
         T = b.plan->Tr[lane];
-        cnt = b.plan->cr[lane];
-        A += T;
+        cnt = (uint32_t)b.plan->cr[lane];
         n_before = b.plan->n_retry;
     }
-    double Ad = (double)A;                                    // floating-point shadow of A, estimates only
+    const uint64_t A_less_T = rp.A[lane];                     // A = A_less_T + T at any time
+    uint64_t P = (A_less_T + T) * (uint64_t)rail.c1;          // exact: (max A + pending bytes) * max c1 < 2^63
+    // xmax(v) - A, the bytes the rail may still take up to cost level v, is estimated as v * G + Bd
+    double Bd = (1.0 - (double)rail.c0) * G - (double)(A_less_T + T);
     const uint64_t n_runs = b.plan->n_runs;
     const uint32_t stride = b.run_stride;
+    uint64_t* row_T = b.run_T + lane;
+    uint32_t* row_K = b.run_K + lane;
 
-    // Water-filling model: once every admitted rail has received a slot, all of them sit at the
-    // common cost level, and level(bytes) = (bytes + sum_d(g_d + A_d)) / sum_d G_d needs no
-    // cross-lane work: the second sum grows by exactly the bytes bound.
-    bool all_proven = false;
-    double pool_G = 0.0, pool_B = 0.0, inv_pool_G = 0.0;
+    bool all_proven = false;                                  // every admitted rail has received a slot
+    // cost level of the last run that went down the lean path: single slices that follow are compared
+    // relative to it with 32-bit keys
+    uint64_t ref_level = kNoLevel;
+    const uint32_t lane_rev = 63u - (uint32_t)lane;
 
-    // run descriptors are fetched 64 at a time, one per lane, the next block prefetched
-    uint32_t nx_start = 0, nx_m = 0, nx_len = 1, nx_id = 0;
-    auto fetch = [&](uint64_t r) {
-        if (r < n_runs) {
-            nx_start = b.run_start[r];
-            nx_m = b.run_start[r + 1] - nx_start;
-            nx_id = use_pending ? b.pending[nx_start] : nx_start;
-            nx_len = b.s_len[nx_id];
+    // One slice of l bytes: plain argmin.  Near a known level the costs are compared as 32-bit keys
+    // (cost - level + 2^25) << 6 | lane; a rail outside that window enters key 0, and a winning key below 64
+    // sends the slice to the 64-bit compare, as does an unknown level.  Returns 1 in the winning lane.
+    auto bind_single = [&](uint32_t l) -> uint32_t {
+        const uint64_t p_one = P + (uint64_t)l * rail.c1;
+        const uint64_t cost = rail.c0 + (p_one >> 16);
+        int win = 0;
+        bool keyed = ref_level != kNoLevel;
+        if (__builtin_expect(keyed, 1)) {
+            const uint64_t rel = cost - ref_level + (kRelSpan >> 1);
+            const uint32_t key = live ? (rel < kRelSpan ? (((uint32_t)rel << 6) | (uint32_t)lane) : 0u) : 0xFFFFFFFFu;
+            const uint32_t best = wave_min_key<R>(key);
+            win = (int)(best & 63u);
+            keyed = best >= 64u;
         }
+        if (__builtin_expect(!keyed, 0)) win = argmin_cost(cost, live, lane, R);
+        const bool mine = lane == win;
+        P = mine ? p_one : P;
+        T += mine ? l : 0u;
+        cnt += mine ? 1u : 0u;
+        Bd -= mine ? (double)l : 0.0;
+        return mine ? 1u : 0u;
     };
-    fetch(lane);
-    for (uint64_t blk = 0; blk < n_runs; blk += 64) {
-        const uint32_t my_m = nx_m, my_len = nx_len, my_id = nx_id;
-        const double my_inv_len = 1.0 / (double)my_len;       // one division per lane serves 64 runs
-        fetch(blk + 64 + lane);
-        const int in_blk = (int)(n_runs - blk < 64 ? n_runs - blk : 64);
-        // results of single-slice runs wait in the lane that fetched the run and leave after the block
-        uint32_t single_rail = 0xFFFFFFFFu;
-        uint64_t single_off = 0;
-        for (int t = 0; t < in_blk; ++t) {
-            const uint32_t l = __builtin_amdgcn_readlane((int)my_len, t);
-            const uint32_t m = __builtin_amdgcn_readlane((int)my_m, t);
-            const uint64_t row = (blk + t) * stride;
-            uint32_t k = 0;
 
-            const double ld = (double)l;
-            if (m == 1) {
-                // a single slice: plain argmin
-                const int win = argmin_cost(slot_cost(rail, A, l, 0), live, lane, R);
-                const uint64_t T_win = read_lane64(T, win);
-                if (lane == t) { single_rail = (uint32_t)win; single_off = T_win; }
-                k = lane == win;
-            } else {
-                if (lane < n_rails) b.run_T[row + lane] = T;
-                const double inv_l = __longlong_as_double((long long)read_lane64(
-                    (uint64_t)__double_as_longlong(my_inv_len), t));
-                uint32_t taken = 0;
-                bool solved = false;
-                if (__builtin_expect(all_proven && m > (uint32_t)kTol, 1)) {
-                    // Steady state, lean path: level from the incremental water-filling sums, slot
-                    // counts from a floating-point estimate confirmed by the integer cost of the
-                    // slot below and the slot above, repair with incrementally updated costs.
-                    const double v = (((double)m + 0.5 * n_live) * ld + pool_B) * inv_pool_G;
-                    if (__builtin_expect(v >= 0.0 && v < 1.0e15, 1)) {
-                        const double vfl = floor(v);
-                        const uint64_t vi = (uint64_t)vfl;
-                        double kf = ((vfl + c0d1) * G - Ad) * inv_l;
-                        kf = kf > 0.0 ? kf : 0.0;
-                        kf = kf < (double)m ? kf : (double)m;
-                        uint32_t kk = (uint32_t)kf;
-                        const uint64_t lc1 = (uint64_t)l * rail.c1;
-                        uint64_t p_prev = (A + (uint64_t)kk * l) * (uint64_t)rail.c1;   // slot kk-1 ends here
-                        uint64_t p_next = p_prev + lc1;                                  // slot kk ends here
-                        uint64_t c_prev = rail.c0 + (p_prev >> 16);
-                        uint64_t c_next = rail.c0 + (p_next >> 16);
-                        const bool off = live && ((kk < m && c_next <= vi) || (kk > 0 && c_prev > vi));
-                        if (__builtin_expect(__ballot(off) == 0, 1)) {
-                            const uint32_t tt = __builtin_amdgcn_readfirstlane((int)wave_reduce32(kk, R, Add32{}));
-                            int miss = (int)m - (int)tt;
-                            if (__builtin_expect(miss <= kTol && miss >= -kTol, 1)) {
-                                while (miss > 0) {            // add the cheapest free slot
-                                    const int win = argmin_cost(c_next, live && kk < m, lane, R);
-                                    if (lane == win) {
-                                        ++kk;
-                                        p_prev = p_next; c_prev = c_next;
-                                        p_next += lc1;   c_next = rail.c0 + (p_next >> 16);
-                                    }
-                                    --miss;
-                                }
-                                while (miss < 0) {            // drop the dearest taken slot
-                                    const int win = argmax_cost(c_prev, live && kk > 0, lane, R);
-                                    if (lane == win) {
-                                        --kk;
-                                        p_next = p_prev; c_next = c_prev;
-                                        p_prev -= lc1;   c_prev = rail.c0 + (p_prev >> 16);
-                                    }
-                                    ++miss;
-                                }
-                                k = kk;
-                                taken = m;
-                                solved = true;
-                            }
+    // A run of m >= 2 slices of l bytes with estimated end level vi: slots per rail.
+    auto bind_run = [&](uint32_t l, uint32_t m, uint64_t vi, double level_f, double inv_l) -> uint32_t {
+        const uint64_t lc1 = (uint64_t)l * rail.c1;           // cost numerator of one slice on this rail
+        if (__builtin_expect(vi != kNoLevel && m - (uint32_t)(kTol + 1) < kLeanRunMax - (uint32_t)(kTol + 1), 1)) {
+            // Lean path.  Slots at or below the level, per rail: slot j is iff j + 1 < kf, so the count is
+            // ceil(kf) - 1, taken as trunc(kf - 1e-6) (an exactly integer kf, common when all lengths are
+            // multiples of a power of two, must not count, hence the small bias against rounding noise).  The
+            // estimate is confirmed by the integer cost of the slot below (last one taken) and of the slot above
+            // (first one free), which must both lie within 2^26 ps of the level so that the repair can compare
+            // them as 32-bit keys; a count beyond the run's length fails the same test.
+            const double kf = fma(fma(level_f, G, Bd), inv_l, -1.0e-6);
+            uint32_t kk;                                                          // trunc(kf); below zero gives 0, above 2^32 - 1 saturates
+            asm("v_cvt_u32_f64_e32 %0, %1" : "=v"(kk) : "v"(kf));
+            uint64_t p_prev = P + (uint64_t)kk * lc1;                            // slot kk-1 ends here
+            uint64_t p_next = p_prev + lc1;                                       // slot kk ends here
+            uint64_t up = rail.c0 + (p_next >> 16) - vi;                          // first free slot above the level: must be >= 1
+            uint64_t down = vi - (rail.c0 + (p_prev >> 16));                      // level above the last taken slot: must be >= 0
+            const bool off = live & ((kk > m) | ((kk < m) & (up - 1 >= kRelSpan - 1)) | ((kk > 0) & (down >= kRelSpan)));
+            {   // a lane that is off adds kOffMark to the slot sum, which then misses m by more than any repair covers
+                // three reductions side by side: slots taken, cheapest free slot, dearest taken slot
+                // (ties: the free slot of the lowest rail is next, the taken slot of the highest rail is last)
+                uint32_t key_up = (live & (kk < m)) ? (((uint32_t)up << 6) | (uint32_t)lane) : 0xFFFFFFFFu;
+                uint32_t key_down = (live & (kk > 0)) ? (((uint32_t)down << 6) | lane_rev) : 0xFFFFFFFFu;
+                const uint32_t sum_r = wave_reduce32(off ? kOffMark : kk, R, Add32{});
+                uint32_t up_r = wave_reduce32(key_up, R, Min32{});
+                uint32_t down_r = wave_reduce32(key_down, R, Min32{});
+                int miss = (int)m - (int)(uint32_t)__builtin_amdgcn_readfirstlane((int)sum_r);
+                if (__builtin_expect(miss >= -kTol && miss <= kTol, 1)) {
+                    // repair one slot at a time: add the cheapest free slot / drop the dearest taken slot; the
+                    // first step's winners are already known, further steps redo one reduction each
+                    bool exact = true;                    // false: a cost left the 32-bit window, start over in the general path
+                    while (miss > 0) {
+                        const int win = (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)up_r) & 63u);
+                        if (lane == win) {
+                            ++kk;
+                            p_prev = p_next;
+                            p_next += lc1;
+                            up = rail.c0 + (p_next >> 16) - vi;
+                            key_up = kk < m ? (((uint32_t)up << 6) | (uint32_t)lane) : 0xFFFFFFFFu;
                         }
+                        if (--miss == 0) break;
+                        if (any_lane((lane == win) & (kk < m) & (up >= kRelSpan))) { exact = false; break; }
+                        up_r = wave_reduce32(key_up, R, Min32{});
+                    }
+                    while (miss < 0) {
+                        const int win = 63 - (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)down_r) & 63u);
+                        if (lane == win) {
+                            --kk;
+                            p_next = p_prev;
+                            p_prev -= lc1;
+                            down = vi - (rail.c0 + (p_prev >> 16));
+                            key_down = kk > 0 ? (((uint32_t)down << 6) | lane_rev) : 0xFFFFFFFFu;
+                        }
+                        if (++miss == 0) break;
+                        if (any_lane((lane == win) & (kk > 0) & (down >= kRelSpan))) { exact = false; break; }
+                        down_r = wave_reduce32(key_down, R, Min32{});
+                    }
+                    if (__builtin_expect(exact, 1)) {
+                        P = p_prev;
+                        T += (uint64_t)kk * l;
+                        cnt += kk;
+                        Bd = fma(-(double)kk, (double)l, Bd);
+                        ref_level = vi;
+                        return kk;
                     }
                 }
-                if (__builtin_expect(!solved && m > (uint32_t)kTol, 0)) {
-                    double v;
-                    if (all_proven) {
-                        v = (((double)m + 0.5 * n_live) * (double)l + pool_B) * inv_pool_G;
-                    } else {
-                        // rails whose next slot already costs more than the level stay out of the pool
-                        const uint64_t head = live ? slot_cost(rail, A, l, 0) : ~0ull;
-                        bool wet = live;
-                        v = 0.0;
-                        for (int pass = 0; pass < 64; ++pass) {
-                            const uint64_t wet_mask = __ballot(wet);
-                            const double sumG = wave_sum_f64(wet ? G : 0.0, R);
-                            const double sumB = wave_sum_f64(wet ? g + (double)A : 0.0, R);
-                            const double need = ((double)m + 0.5 * (double)__popcll(wet_mask)) * (double)l;
-                            v = __longlong_as_double((long long)uniform64((uint64_t)__double_as_longlong((need + sumB) / sumG)));
-                            const bool still = wet && (cnt > 0 || (double)head <= v);
-                            const uint64_t still_mask = __ballot(still);
-                            if (still_mask == wet_mask || still_mask == 0) break;
-                            wet = still;
-                        }
-                    }
-                    // bracket (computed only if the first guess misses):
-                    // slots summed over rails stay below m at `lo` and reach at least m at `hi`
-                    bool bracketed = false;
-                    int64_t lo = 0, hi = 0;
-                    for (int iter = 0;; ++iter) {
-                        int64_t vi = (v >= 0.0 && v < 9.0e18) ? (int64_t)v : -1;
-                        if (!bracketed && vi < 0) {
-                            const uint64_t head = live ? slot_cost(rail, A, l, 0) : ~0ull;
-                            const uint64_t alone = live ? slot_cost(rail, A, l, m - 1) : ~0ull;
-                            lo = (int64_t)uniform64(wave_reduce64(head, R, OpMin{})) - 1;
-                            hi = (int64_t)uniform64(wave_reduce64(alone, R, OpMin{}));
-                            bracketed = true;
-                        }
-                        if (bracketed && (iter >= 8 || vi <= lo || vi >= hi)) {   // guess unusable: bisect
-                            vi = lo + (hi - lo) / 2;
-                            if (vi <= lo) vi = hi;
-                        }
-                        const uint32_t kk = live ? slots_upto_fast(rail, A, l, inv_l, vi, m) : 0;
-                        const uint64_t tt = uniform64(wave_reduce64(kk, R, OpAdd{}));
-                        const int64_t miss = (int64_t)m - (int64_t)tt;
-                        if (miss <= kTol && miss >= -kTol) { k = kk; taken = (uint32_t)tt; break; }
-                        if (!bracketed) {
-                            const uint64_t head = live ? slot_cost(rail, A, l, 0) : ~0ull;
-                            const uint64_t alone = live ? slot_cost(rail, A, l, m - 1) : ~0ull;
-                            lo = (int64_t)uniform64(wave_reduce64(head, R, OpMin{})) - 1;
-                            hi = (int64_t)uniform64(wave_reduce64(alone, R, OpMin{}));
-                            bracketed = true;
-                        }
-                        if (miss > 0) { if (vi > lo) lo = vi; } else { if (vi < hi) hi = vi; }
-                        if (hi - lo == 1) {
-                            // the whole deficit sits at cost `hi`: hand it out in rail order
-                            const uint32_t k_lo = live ? slots_upto(rail, A, l, inv_l, lo, m) : 0;
-                            const uint32_t k_hi = live ? slots_upto(rail, A, l, inv_l, hi, m) : 0;
-                            const uint64_t below = uniform64(wave_reduce64(k_lo, R, OpAdd{}));
-                            uint64_t tie = k_hi - k_lo, inc = tie;
-#pragma unroll
-                            for (int d = 1; d < 64; d <<= 1) {
-                                uint64_t up = (uint64_t)__shfl_up((unsigned long long)inc, d, 64);
-                                if (lane >= d) inc += up;
-                            }
-                            const uint64_t before = inc - tie;                 // ties on lower rails
-                            const uint64_t rem = (uint64_t)m - below;
-                            const uint64_t take = before >= rem ? 0 : (rem - before < tie ? rem - before : tie);
-                            k = k_lo + (uint32_t)take;
-                            taken = m;
-                            break;
-                        }
-                        const bool near = live && (kk > 0 || slot_cost(rail, A, l, 0) <= (uint64_t)(vi < 0 ? 0 : vi) + 1);
-                        double rate = wave_sum_f64(near ? G : 0.0, R);
-                        if (!(rate > 0.0)) rate = wave_sum_f64(G, R);
-                        v = __longlong_as_double((long long)uniform64(
-                            (uint64_t)__double_as_longlong((double)vi + (double)miss * (double)l / rate)));
-                    }
-                }
-                // repair: add the cheapest free slot / drop the dearest taken slot
-                while (taken < m) {
-                    const int win = argmin_cost(slot_cost(rail, A, l, k), live && k < m, lane, R);
-                    k += lane == win;
-                    ++taken;
-                }
-                while (taken > m) {
-                    const int win = argmax_cost(slot_cost(rail, A, l, k > 0 ? k - 1 : 0), live && k > 0, lane, R);
-                    k -= lane == win;
-                    --taken;
-                }
-                if (lane < n_rails) b.run_K[row + lane] = k;
-            }
-            const uint64_t bytes = (uint64_t)k * l;
-            A += bytes;
-            T += bytes;
-            cnt += k;
-            Ad = fma((double)k, ld, Ad);
-            if (all_proven) {
-                pool_B += (double)m * ld;
-            } else if (__ballot(live && cnt > 0) == live_mask) {
-                all_proven = true;
-                pool_G = wave_sum_f64(G, R);
-                pool_B = wave_sum_f64(live ? g + (double)A : 0.0, R);
-                pool_G = __longlong_as_double((long long)uniform64((uint64_t)__double_as_longlong(pool_G)));
-                pool_B = __longlong_as_double((long long)uniform64((uint64_t)__double_as_longlong(pool_B)));
-                inv_pool_G = 1.0 / pool_G;
             }
         }
-        if (single_rail != 0xFFFFFFFFu) {
-            b.s_rail[my_id] = single_rail;
-            b.s_stage_off[my_id] = single_off;
-            b.s_state[my_id] = TENT_SLICE_BOUND;
+        // General path (any state, any level), kept out of line so that the loop stays short.
+        const ChainVars cv = bind_run_general<kWide>(ChainVars{P, T, Bd, ref_level, cnt, all_proven ? 1u : 0u, 0u}, rail, G, g, live,
+                                                     live_mask, A_less_T, lane, l, m, vi, level_f, inv_l);
+        P = cv.P; T = cv.T; Bd = cv.Bd; ref_level = cv.ref_level; cnt = cv.cnt; all_proven = cv.all_proven != 0;
+        return cv.k;
+    };
+
+    auto put_row = [&](uint64_t T_before, uint32_t k) {
+        *row_T = T_before;
+        *row_K = k;
+        row_T += stride;
+        row_K += stride;
+    };
+
+    auto pair64 = [](uint32_t lo, uint32_t hi, int t) -> uint64_t {
+        return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, t) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)lo, t);
+    };
+
+    // Records are fetched kWide at a time, one per lane, a block ahead of their use.
+    auto record_at = [&](uint64_t r, Quad& lo, Quad& hi) {                    // the table ends with a spare record
+        const Quad* src = reinterpret_cast<const Quad*>(recs + (r < n_runs ? r : n_runs));
+        lo = src[0];
+        hi = src[1];
+    };
+    Quad next_lo, next_hi;
+    record_at((uint64_t)lane, next_lo, next_hi);
+    for (uint64_t blk = 0; blk < n_runs; blk += kWide) {
+        const Quad mine_lo = next_lo, mine_hi = next_hi;
+        record_at(blk + kWide + lane, next_lo, next_hi);
+        const int in_blk = (int)(n_runs - blk < (uint64_t)kWide ? n_runs - blk : (uint64_t)kWide);
+        for (int t = 0; t < in_blk; ++t) {
+            const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)mine_lo.x, t);
+            const uint32_t m = (uint32_t)__builtin_amdgcn_readlane((int)mine_lo.y, t);
+            const uint64_t T_before = T;
+            uint32_t k;
+            if (m == 1) {
+                k = bind_single(l);
+            } else {
+                k = bind_run(l, m, pair64(mine_lo.z, mine_lo.w, t), __longlong_as_double((long long)pair64(mine_hi.x, mine_hi.y, t)),
+                             __longlong_as_double((long long)pair64(mine_hi.z, mine_hi.w, t)));
+            }
+            put_row(T_before, k);
         }
     }
 
@@ -375,32 +526,34 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
     const uint64_t rounded = (T + 255) & ~255ull;
     uint64_t inc = rounded;
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
+    for (int d = 1; d < kWide; d <<= 1) {
         uint64_t up = (uint64_t)__shfl_up((unsigned long long)inc, d, 64);
         if (lane >= d) inc += up;
     }
     PlanState* ps = b.plan;
     ps->T[lane] = T;
     ps->cnt[lane] = cnt;
-    ps->A_after[lane] = A;
+    ps->A_after[lane] = A_less_T + T;
     ps->base[lane] = inc - rounded;
     if (lane == 0) ps->n_bound = ps->n_pending + n_before;
 }
 
 template <int kWide>
-__global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams rp, int mode)
+__global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams rp, int mode,
+                                                        const RunRec* __restrict__ recs)
 {
-    bind_chain<kWide>(b, rp, mode);
+    bind_chain<kWide>(b, rp, mode, recs);
 }
 
 // The chain is one wavefront; the tile tables of the copy kernels depend on the slice table only, not
 // on the binding.  On a first plan both go into one launch: workgroup 0 walks the chain, the others
 // build the tables, so the tables cost no time of their own.
 template <int kWide>
-__global__ void __launch_bounds__(256) bind_chain_tables_kernel(BatchDev b, RailParams rp, int mode)
+__global__ void __launch_bounds__(256) bind_chain_tables_kernel(BatchDev b, RailParams rp, int mode,
+                                                                const RunRec* __restrict__ recs)
 {
     if (blockIdx.x == 0) {
-        if (threadIdx.x < 64) bind_chain<kWide>(b, rp, mode);
+        if (threadIdx.x < 64) bind_chain<kWide>(b, rp, mode, recs);
         return;
     }
     build_tile_tables(b, blockIdx.x - 1, gridDim.x - 1);
@@ -434,8 +587,6 @@ __global__ void __launch_bounds__(256) bind_emit_kernel(BatchDev b, RailParams r
             if (!head) r -= 1;
         }
         const uint32_t start = b.run_start[r];
-        const uint32_t m = b.run_start[r + 1] - start;
-        if (m == 1) continue;                                   // bound by the chain kernel
         const uint32_t l = b.s_len[id_q];
         const double inv_l = 1.0 / (double)l;
         const uint64_t row = r * stride;
@@ -483,15 +634,20 @@ hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, h
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(run_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, up);
+    // bytes bound before every pending position, then one record per run for the chain
+    PendingLen plen{b.s_len, use_pending ? b.pending : nullptr, &b.plan->n_pending};
+    e = exclusive_scan(plen, b.n_slices, b.len_pre, b.scan_partials, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(run_records_kernel, dim3((b.run_capacity + 1 + 255) / 256), dim3(256), 0, s, b, rp, mode);
     if (mode & kBindBuildTables) {
         const dim3 grid(1 + tile_table_blocks(b)), block(256);
-        if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_tables_kernel<16>, grid, block, 0, s, b, rp, mode);
-        else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_tables_kernel<32>, grid, block, 0, s, b, rp, mode);
-        else                       hipLaunchKernelGGL(bind_chain_tables_kernel<64>, grid, block, 0, s, b, rp, mode);
+        if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_tables_kernel<16>, grid, block, 0, s, b, rp, mode, b.run_rec);
+        else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_tables_kernel<32>, grid, block, 0, s, b, rp, mode, b.run_rec);
+        else                       hipLaunchKernelGGL(bind_chain_tables_kernel<64>, grid, block, 0, s, b, rp, mode, b.run_rec);
     } else {
-        if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, mode);
-        else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, mode);
-        else                       hipLaunchKernelGGL(bind_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, mode);
+        if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, mode, b.run_rec);
+        else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, mode, b.run_rec);
+        else                       hipLaunchKernelGGL(bind_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, mode, b.run_rec);
     }
     hipLaunchKernelGGL(bind_emit_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, rp, up);
     return hipGetLastError();

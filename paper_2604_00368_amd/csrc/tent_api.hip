@@ -644,10 +644,12 @@ int declare_impl(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
         cv.want(&d.dst_tile, n_tiles);
     }
     d.run_capacity = 2u * n_desc;
-    d.run_stride = ctx->max_rails;
+    d.run_stride = ctx->max_rails <= 16 ? 16u : ctx->max_rails <= 32 ? 32u : 64u;   // a row per run, one entry per lane of the chain
     cv.want(&d.run_start, (uint64_t)d.run_capacity + 1);
     cv.want(&d.run_T, (uint64_t)d.run_capacity * d.run_stride);
     cv.want(&d.run_K, (uint64_t)d.run_capacity * d.run_stride);
+    cv.want(&d.run_rec, (uint64_t)d.run_capacity + 1);
+    cv.want(&d.len_pre, n_slices + 1);
     cv.want(&order_dev, nd);
     cv.want(&rank_dev, nd);
     if (d.n_sc_tiles) {

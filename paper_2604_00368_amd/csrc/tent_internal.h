@@ -86,6 +86,15 @@ struct PlanState {
     uint64_t compact_overflow;            // nonzero: more tiles move than the launch was sized for (nothing is marked DONE)
 };
 
+// What the binding chain needs to know about a run of equal-length slices: 32 bytes, read as two 16-byte halves.
+struct RunRec {
+    uint32_t len;                  // slice length of the run
+    uint32_t m;                    // slices in the run
+    uint64_t level;                // estimated cost level at the end of the run, ~0 = no estimate
+    double   level_f;              // the same as a double
+    double   inv_len;              // 1.0 / len
+};
+
 // What a copy workgroup needs to know about its slice, in one 16-byte scalar load.
 struct SliceRec {
     uint64_t lin;                  // staging address of the slice's first byte
@@ -164,7 +173,9 @@ struct BatchDev {
     uint64_t* run_T;               // [run_capacity * run_stride] bytes bound per rail before the run
     uint32_t* run_K;               // [run_capacity * run_stride] slots each rail takes in the run
     uint32_t  run_capacity;        // 2 * n_desc
-    uint32_t  run_stride;          // rails per row
+    uint32_t  run_stride;          // entries per row: the context's rail limit rounded up to 16, 32 or 64
+    RunRec*   run_rec;             // [run_capacity + 1] one record per run (the last one is a spare the chain's look-ahead may read)
+    uint64_t* len_pre;             // [n_slices + 1] bytes of the pending slices before every pending position
 
     uint32_t* pending;             // [n_slices] ascending ids of slices not DONE and never failed (re-planning)
     uint32_t* retry_ids;           // [n_slices] ascending ids of slices not DONE with a retry count > 0
