@@ -26,7 +26,7 @@
  *     DONE -- and may then run beside its copies, which read none of what a re-plan writes.
  *     That is what overlaps the re-planning of the unfinished slices with the data movement of
  *     the finished ones.  The next tent_execute must still come after that plan (the
- *     host-side wait of tent_sim_advance, or an event).
+ *     host-side wait of tent_sim_advance with n_done != NULL, or an event).
  *   - HIP graphs: tent_reset, tent_plan with info = NULL and tent_execute allocate nothing, copy
  *     nothing from or to the host and enqueue kernels only (no memset nodes), so a caller may
  *     record them on a capturing stream and replay the graph.  The host-side bookkeeping of a
@@ -300,8 +300,11 @@ int tent_get_modes(tent_ctx *ctx, tent_batch_t batch, uint8_t *host_out, uint64_
  * to it by the last tent_plan.  A BOUND slice stays BOUND iff
  * queued_bytes_d + stage_off + len <= budget_bytes[d]; otherwise it returns to
  * PENDING and will be re-planned (Section 4.3, idempotent retry).
- * `budget_bytes` is host memory with n_rails entries.  Waits for the stream;
- * *n_done (host, may be NULL) receives the number of slices that stayed BOUND.
+ * `budget_bytes` is host memory with n_rails entries.  With n_done != NULL the call waits for
+ * the stream and *n_done (host) receives the number of slices that stayed BOUND; with
+ * n_done == NULL it only enqueues.  Either way the next tent_execute sizes its copy launches by
+ * what can have stayed BOUND (at most budget_d - queued_bytes_d bytes per rail, and the count
+ * when it was read back).
  */
 int tent_sim_advance(tent_ctx *ctx, tent_batch_t batch, const uint64_t *budget_bytes,
                      uint64_t *n_done, void *stream);

@@ -179,8 +179,12 @@ def tent_plan(ctx, batch: int, rails, want_info: bool = True, stream=None):
     return st, info
 
 
-def tent_sim_advance(ctx, batch: int, budget_bytes, stream=None) -> int:
+def tent_sim_advance(ctx, batch: int, budget_bytes, stream=None, want_done: bool = True):
+    """Returns the number of slices that stayed BOUND, or None (and only enqueues) when it is not asked for."""
     b, bp = _host(budget_bytes, np.uint64)
+    if not want_done:
+        _check(lib().tent_sim_advance(ctx, batch, bp, None, _stream(stream)), "tent_sim_advance")
+        return None
     n = C.c_uint64()
     _check(lib().tent_sim_advance(ctx, batch, bp, C.byref(n), _stream(stream)), "tent_sim_advance")
     return n.value

@@ -36,6 +36,7 @@ struct Batch {
     bool has_retry = false;      // a rail failed since declare / reset: slices with a retry count may exist
     bool broken = false;         // an execute failed after its slices were marked DONE: only reset or release help
     uint64_t bound_hint = 0;     // upper bound on the number of BOUND slices, as far as the host knows
+    uint64_t tile_hint = ~0ull;  // upper bound on the copy tiles of the BOUND slices, as far as the host knows
     uint32_t generation = 0;
     uint64_t payload = 0;
     uint64_t max_req_slices = 0; // most slices any one transfer has
@@ -971,6 +972,7 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     }
     b->planned = true;
     b->bound_hint = b->dev.n_slices;
+    b->tile_hint = ~0ull;
     b->last_rails = rp;
     for (uint32_t r = 0; r < n_rails; ++r) b->last_lat_ns[r] = rails[r].lat_ns;
 
@@ -1075,6 +1077,7 @@ int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state*
     }
     b->planned = true;
     b->bound_hint = b->dev.n_slices;
+    b->tile_hint = ~0ull;
     b->last_rails = rp;
     for (uint32_t r = 0; r < n_rails; ++r) b->last_lat_ns[r] = rails[r].lat_ns;
 
@@ -1129,11 +1132,19 @@ int tent_sim_advance(tent_ctx* ctx, tent_batch_t batch, const uint64_t* budget_b
         bp.queued[d] = b->last_rails.A[d];
         bp.budget[d] = budget_bytes[d];
     }
+    StreamNote note(*b, s);
     HIP_TRY(launch_retire(b->dev, bp, s));
+    // What stays BOUND on rail d fits in budget_d - queued_d bytes, which bounds the tiles the next execute
+    // copies without asking the device (slices of a tiled batch are whole tiles).
+    uint64_t tiles = 0;
+    for (uint32_t d = 0; d < b->last_rails.n_rails; ++d)
+        if (bp.budget[d] > bp.queued[d]) tiles += (bp.budget[d] - bp.queued[d]) / (b->dev.tile_bytes ? b->dev.tile_bytes : 1u);
+    b->tile_hint = tiles;
+    if (!n_done) return TENT_OK;
     HIP_TRY(hipMemcpyAsync(ctx->host_plan, b->dev.plan, sizeof(PlanState), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     b->bound_hint = ctx->host_plan->n_done;
-    if (n_done) *n_done = ctx->host_plan->n_done;
+    *n_done = ctx->host_plan->n_done;
     return TENT_OK;
 }
 
@@ -1268,7 +1279,8 @@ int tent_execute(tent_ctx* ctx, tent_batch_t batch, void* stream)
     StreamNote note(*b, s);
     // When the host knows that only a small part of the batch is BOUND (after the rail simulator), the
     // copies run over a list of the tiles of the BOUND slices and their launches are sized by that part.
-    const uint64_t max_tiles = b->bound_hint * b->dev.tiles_per_slice;
+    uint64_t max_tiles = b->bound_hint * b->dev.tiles_per_slice;
+    if (b->tile_hint < max_tiles) max_tiles = b->tile_hint;
     const bool compact = b->dev.n_sc_tiles != 0 && max_tiles * 2 <= b->dev.n_sc_tiles;
     HIP_TRY(launch_finalize(b->dev, static_cast<uint8_t*>(ctx->cfg.staging_arena), compact, max_tiles, s));
     // The copies below are driven by the tables just written and read no slice state, so the slices

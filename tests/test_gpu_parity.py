@@ -212,6 +212,38 @@ def test_replanning_epochs_plan_beside_copies(H, oracle):
     run_epochs_plan_beside_copies(H, oracle, W.small_variant("replanning"), flags=T.TENT_FLAG_SERIAL_BINDING)
 
 
+def test_replanning_epochs_enqueued_without_a_host_wait(H, oracle):
+    # the whole sequence of epochs is enqueued at once: the rail simulator reads nothing back, an event orders
+    # each execute after its plan, and the execute sizes its launches by the budgets alone
+    import torch
+    from paper_2604_00368_amd import binding as T
+    w = W.small_variant("replanning")
+    src = W.fill_numpy(w, 0)
+    dst0 = W.fill_numpy(w, 1)
+    s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
+    dst_want = dst0.copy()
+    staging_want = np.zeros(w.staging_bytes, dtype=np.uint8)
+    records, left = oracle.run_epochs(w, s, [src, dst_want], staging_want)
+    assert left.shape[0] == 0
+    with H.Engine(w, src, dst0) as eng:
+        eng.declare()
+        side = torch.cuda.Stream(eng.dev)
+        side.wait_stream(eng.stream)
+        for ep in list(w.epochs) + [w.drain]:
+            st, _ = T.tent_plan(eng.ctx, eng.batch, ep.rails, False, side)
+            assert st == 0
+            assert T.tent_sim_advance(eng.ctx, eng.batch, ep.budget, side, want_done=False) is None
+            ev = torch.cuda.Event()
+            ev.record(side)
+            eng.stream.wait_event(ev)
+            T.tent_execute(eng.ctx, eng.batch, eng.stream)
+        assert T.tent_poll(eng.ctx, eng.batch, eng.stream) == 0
+        torch.cuda.synchronize(eng.dev)
+        assert (eng.table()["state"] == 2).all()
+        assert np.array_equal(eng.dst.cpu().numpy(), dst_want)
+        assert np.array_equal(eng.arena.cpu().numpy(), staging_want)
+
+
 @pytest.mark.parametrize("seed", range(10))
 def test_partial_executes_random_tiled_geometry(H, oracle, seed):
     # lengths in multiples of 1-4 KiB, source and destination cut differently, a few epochs with random budgets:
