@@ -354,7 +354,7 @@ def ceilings(args):
     out = {"bytes": n, "unit": "GB/s, bytes read plus bytes written", "placement": layout.mode,
            "plain_copy_torch_bitwise_not": round(2 * n / (timed(lambda: torch.bitwise_not(a, out=b)) * 1e-3) / 1e9, 1),
            "write_only_torch_fill": round(n / (timed(lambda: b.fill_(7)) * 1e-3) / 1e9, 1),
-           "read_only_torch_sum_int32": round(n / (timed(lambda: a.view(torch.int32).sum()) * 1e-3) / 1e9, 1)}
+           "read_only_torch_sum_int64": round(n / (timed(lambda: a.view(torch.int64).sum()) * 1e-3) / 1e9, 1)}
     stream = torch.cuda.current_stream(dev)
     for name, w in ws.items():
         r = Run(T, W, torch, dev, w, (src, arena, dst), 4, 1, T.TENT_FLAG_PROFILE)

@@ -124,7 +124,7 @@ def test_two_rail_worked_example(oracle):
 
 @pytest.mark.parametrize("seed", range(6))
 def test_greedy_choice_brute_force(oracle, seed):
-    # Section 4.2: each slice goes to the rail expected to complete it fastest under live telemetry.
+    # Section 4.2, opening rule: a slice is bound to the rail whose predicted completion, from current telemetry, is earliest.
     w = W.ragged(seed, n_desc=10, max_len=60_000, slice_bytes=4096 + 7 * seed, n_rails=3 + seed)
     s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
     b = oracle.bind(s.len, w.rails)
@@ -327,7 +327,7 @@ def test_replanning_epochs(oracle):
 
 
 def test_degraded_rail_costs_twice(oracle):
-    # Section 4.3: a DEGRADED rail "receives a 0.5x weight penalty but remains eligible"
+    # Section 4.3: a DEGRADED rail keeps half its weight and can still be chosen
     healthy = W.make_rails([50000, 50000])
     degraded = W.make_rails([50000, 50000], health=[1, 0])
     c0h, c1h, exh, _ = oracle.coeffs(healthy)
