@@ -19,6 +19,8 @@
 //   3. emit          one lane per slot (d, k): its rank in the run is
 //                    k + sum_{d' < d} count_d'(f) + sum_{d' > d} count_d'(f - 1),  f = f_d(k),
 //                    which gives the slice it belongs to; staging offset = T_d at run start + k l.
+#include <type_traits>
+
 #include "scan.h"
 #include "tile_tables.h"
 #include "wave.h"
@@ -145,17 +147,13 @@ __device__ __forceinline__ uint32_t wave_min_key(uint32_t key)
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_reduce32(key, R, Min32{}));
 }
 
-// True when p holds in any active lane.  The lane mask passes through a scalar register pair so that the
-// test is a scalar compare (a vector compare feeding a branch costs a lone wavefront several times more).
-__device__ __forceinline__ bool any_lane(bool p)
-{
-    uint64_t mask = __ballot(p);
-    asm volatile("" : "+s"(mask));
-    return mask != 0;
-}
-
-constexpr uint32_t kRelBits = 26;                      // costs within 2^26 ps of the level are compared as 32-bit keys
+// Costs within 2^25 ps of the level are compared as 32-bit keys (offset << 6 | lane, below 2^31); a cost farther
+// on the harmless side (a free slot far above the level, a taken slot far below it) gets the key kFarKey | lane,
+// which loses against every near key; a winner at or above kFarKey means "no near candidate" and is never used.
+constexpr uint32_t kRelBits = 25;
 constexpr uint64_t kRelSpan = 1ull << kRelBits;
+constexpr uint32_t kFarKey = 0x80000000u;
+constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 constexpr uint64_t kNoLevel = ~0ull;
 // The lean path sums slot counts in 32 bits: runs stay below 2^24 slices and a lane whose estimate cannot be
 // used adds 2^25 instead of its count, so that with up to 64 lanes the sum neither wraps nor comes near m.
@@ -165,11 +163,11 @@ constexpr uint32_t kOffMark = 1u << 25;
 // ---- step 1b: one record per run ---------------------------------------------------------------
 // Everything the chain needs to know about a run that does not depend on the rails' state, computed
 // in parallel before the chain starts; the chain fetches the records a block at a time.  The cost
-// level comes from the water-filling model: when every admitted rail takes part, all of them end a
-// run at a common cost level, and level(bytes) = (bytes + sum_d(g_d + A_d)) / sum_d G_d with
-// G_d = 65536 / c1_d bytes per picosecond and g_d = c0_d * G_d; the numerator's sum grows by exactly
-// the bytes bound, so the level after every run is known in advance.  It is an estimate: the chain
-// verifies what it derives from it in integers.
+// level comes from the water-filling model: the rails that take part end a run at a common cost level,
+// level(bytes) = (bytes + sum_d h_d G_d) / sum_d G_d over those rails, with G_d = 65536 / c1_d bytes per
+// picosecond and h_d the rail's head cost; a rail takes part once the level has passed its head cost.  The
+// bytes bound before a run are known in advance (a prefix sum of the pending lengths), so the level after
+// every run is too.  It is an estimate: the chain verifies what it derives from it in integers.
 struct PendingLen {
     const uint32_t* s_len;
     const uint32_t* pending;      // nullptr: position = slice index
@@ -183,6 +181,39 @@ struct PendingLen {
 
 __global__ void __launch_bounds__(256) run_records_kernel(BatchDev b, RailParams rp, int mode)
 {
+    // Admitted rails in ascending order of their head cost h_d = c0_d + A_d c1_d / 65536 (what the rail's next byte
+    // would cost): sh_h[j] the j-th smallest, sh_G[j] and sh_hG[j] the sums of G_d and of h_d G_d over the first j + 1.
+    // At cost level v the rails with h_d < v hold sum (v - h_d) G_d bytes, so the level that holds B bytes is
+    // (B + sh_hG[j]) / sh_G[j] for the first j at which it does not reach the next rail's head cost.
+    __shared__ double sh_h[TENT_MAX_RAILS], sh_G[TENT_MAX_RAILS], sh_hG[TENT_MAX_RAILS];
+    __shared__ uint32_t sh_live;
+    const uint32_t t = threadIdx.x;
+    if (t < TENT_MAX_RAILS) {
+        auto head = [&](uint32_t d, double* G) -> double {
+            const double c1 = (double)(uint32_t)rp.c1[d];                       // c1 >= 1 on this path
+            const uint64_t A = rp.A[d] + ((mode & kBindAfterRotation) ? b.plan->Tr[d] : 0);
+            *G = 65536.0 / c1;
+            return (double)rp.c0[d] + (double)A * c1 * (1.0 / 65536.0);
+        };
+        const bool live = t < rp.n_rails && ((rp.admitted >> t) & 1);
+        double G = 0.0;
+        const double h = live ? head(t, &G) : 0.0;
+        uint32_t rank = 0, n_live = 0;
+        for (uint32_t d = 0; d < rp.n_rails; ++d) {
+            if (!((rp.admitted >> d) & 1)) continue;
+            ++n_live;
+            double Gd;
+            const double hd = head(d, &Gd);
+            rank += (hd < h || (hd == h && d < t)) ? 1u : 0u;
+        }
+        if (live) { sh_h[rank] = h; sh_G[rank] = G; sh_hG[rank] = h * G; }
+        if (t == 0) sh_live = n_live;
+    }
+    __syncthreads();
+    if (t == 0) {
+        for (uint32_t j = 1; j < sh_live; ++j) { sh_G[j] += sh_G[j - 1]; sh_hG[j] += sh_hG[j - 1]; }
+    }
+    __syncthreads();
     const uint64_t n_runs = b.plan->n_runs;
     const uint64_t r = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r > n_runs) return;
@@ -193,16 +224,14 @@ __global__ void __launch_bounds__(256) run_records_kernel(BatchDev b, RailParams
         rec.len = b.s_len[id];
         rec.m = b.run_start[r + 1] - start;
         rec.inv_len = 1.0 / (double)rec.len;
-        double sum_G = 0.0, sum_B = 0.0, n_live = 0.0;
-        for (uint32_t d = 0; d < rp.n_rails; ++d) {
-            if (!((rp.admitted >> d) & 1)) continue;
-            const double G = 65536.0 / (double)(uint32_t)rp.c1[d];      // c1 >= 1 on this path
-            const uint64_t A = rp.A[d] + ((mode & kBindAfterRotation) ? b.plan->Tr[d] : 0);
-            sum_G += G;
-            sum_B += (double)rp.c0[d] * G + (double)A;
-            n_live += 1.0;
+        const double bytes = (double)rec.m * (double)rec.len + (double)b.len_pre[start];
+        const uint32_t n_live = sh_live;
+        double v = -1.0;
+        for (uint32_t j = 0; j < n_live; ++j) {
+            // half a slice per participating rail on top: the slot counts are rounded down
+            v = (bytes + 0.5 * (double)(j + 1) * (double)rec.len + sh_hG[j]) / sh_G[j];
+            if (j + 1 == n_live || v <= sh_h[j + 1]) break;
         }
-        const double v = (((double)rec.m + 0.5 * n_live) * (double)rec.len + (sum_B + (double)b.len_pre[start])) / sum_G;
         if (v >= 0.0 && v < 1.0e14) {
             rec.level = (uint64_t)v;
             rec.level_f = (double)rec.level;
@@ -346,7 +375,7 @@ __device__ __attribute__((noinline)) ChainVars bind_run_general(ChainVars cv, Ra
 typedef uint32_t Quad __attribute__((ext_vector_type(4)));       // half a run record: {len, m, level} or {level_f, inv_len}
 static_assert(sizeof(RunRec) == 32, "a run record is two 16-byte halves");
 
-template <int kWide>
+template <int kWide, bool kFar>
 __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& rp, int mode,
                                            const RunRec* __restrict__ recs)
 {
@@ -386,8 +415,9 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
     const uint32_t lane_rev = 63u - (uint32_t)lane;
 
     // One slice of l bytes: plain argmin.  Near a known level the costs are compared as 32-bit keys
-    // (cost - level + 2^25) << 6 | lane; a rail outside that window enters key 0, and a winning key below 64
-    // sends the slice to the 64-bit compare, as does an unknown level.  Returns 1 in the winning lane.
+    // (cost - level + 2^24) << 6 | lane; a rail far above the window gets a far key, a rail below it key 0, and a
+    // winning key below 64 or a far one sends the slice to the 64-bit compare, as does an unknown level.
+    // Returns 1 in the winning lane.
     auto bind_single = [&](uint32_t l) -> uint32_t {
         const uint64_t p_one = P + (uint64_t)l * rail.c1;
         const uint64_t cost = rail.c0 + (p_one >> 16);
@@ -395,10 +425,16 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
         bool keyed = ref_level != kNoLevel;
         if (__builtin_expect(keyed, 1)) {
             const uint64_t rel = cost - ref_level + (kRelSpan >> 1);
-            const uint32_t key = live ? (rel < kRelSpan ? (((uint32_t)rel << 6) | (uint32_t)lane) : 0u) : 0xFFFFFFFFu;
+            uint32_t key;
+            if constexpr (kFar) {
+                const uint32_t near_key = rel < kRelSpan ? (((uint32_t)rel << 6) | (uint32_t)lane) : kFarKey | (uint32_t)lane;
+                key = live ? ((int64_t)rel < 0 ? 0u : near_key) : kNoKey;
+            } else {
+                key = live ? (rel < kRelSpan ? (((uint32_t)rel << 6) | (uint32_t)lane) : 0u) : kNoKey;
+            }
             const uint32_t best = wave_min_key<R>(key);
             win = (int)(best & 63u);
-            keyed = best >= 64u;
+            keyed = best - 64u < kFarKey - 64u;
         }
         if (__builtin_expect(!keyed, 0)) win = argmin_cost(cost, live, lane, R);
         const bool mine = lane == win;
@@ -416,9 +452,10 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
             // Lean path.  Slots at or below the level, per rail: slot j is iff j + 1 < kf, so the count is
             // ceil(kf) - 1, taken as trunc(kf - 1e-6) (an exactly integer kf, common when all lengths are
             // multiples of a power of two, must not count, hence the small bias against rounding noise).  The
-            // estimate is confirmed by the integer cost of the slot below (last one taken) and of the slot above
-            // (first one free), which must both lie within 2^26 ps of the level so that the repair can compare
-            // them as 32-bit keys; a count beyond the run's length fails the same test.
+            // estimate is confirmed by the integer cost of the slot below (last one taken), which must not exceed
+            // the level, and of the slot above (first one free), which must; a count beyond the run's length
+            // fails the same test.  A rail whose first slot lies far above the level (a long queue) takes no
+            // slot and stays out of the repair through its far key.
             const double kf = fma(fma(level_f, G, Bd), inv_l, -1.0e-6);
             uint32_t kk;                                                          // trunc(kf); below zero gives 0, above 2^32 - 1 saturates
             asm("v_cvt_u32_f64_e32 %0, %1" : "=v"(kk) : "v"(kf));
@@ -426,12 +463,17 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
             uint64_t p_next = p_prev + lc1;                                       // slot kk ends here
             uint64_t up = rail.c0 + (p_next >> 16) - vi;                          // first free slot above the level: must be >= 1
             uint64_t down = vi - (rail.c0 + (p_prev >> 16));                      // level above the last taken slot: must be >= 0
-            const bool off = live & ((kk > m) | ((kk < m) & (up - 1 >= kRelSpan - 1)) | ((kk > 0) & (down >= kRelSpan)));
+            // kFar: a rail may lie far on the harmless side of the level (far keys); otherwise every rail must
+            // lie within the window, which saves the two selects per run where all rails stay close to the level
+            const bool off = kFar ? live & ((kk > m) | ((kk < m) & ((int64_t)up < 1)) | ((kk > 0) & ((int64_t)down < 0)))
+                                  : live & ((kk > m) | ((kk < m) & (up - 1 >= kRelSpan - 1)) | ((kk > 0) & (down >= kRelSpan)));
+            auto up_key = [&]() -> uint32_t { return up < kRelSpan ? (((uint32_t)up << 6) | (uint32_t)lane) : kFarKey | (uint32_t)lane; };
+            auto down_key = [&]() -> uint32_t { return down < kRelSpan ? (((uint32_t)down << 6) | lane_rev) : kFarKey | lane_rev; };
             {   // a lane that is off adds kOffMark to the slot sum, which then misses m by more than any repair covers
                 // three reductions side by side: slots taken, cheapest free slot, dearest taken slot
                 // (ties: the free slot of the lowest rail is next, the taken slot of the highest rail is last)
-                uint32_t key_up = (live & (kk < m)) ? (((uint32_t)up << 6) | (uint32_t)lane) : 0xFFFFFFFFu;
-                uint32_t key_down = (live & (kk > 0)) ? (((uint32_t)down << 6) | lane_rev) : 0xFFFFFFFFu;
+                uint32_t key_up = (live & (kk < m)) ? (kFar ? up_key() : (((uint32_t)up << 6) | (uint32_t)lane)) : kNoKey;
+                uint32_t key_down = (live & (kk > 0)) ? (kFar ? down_key() : (((uint32_t)down << 6) | lane_rev)) : kNoKey;
                 const uint32_t sum_r = wave_reduce32(off ? kOffMark : kk, R, Add32{});
                 uint32_t up_r = wave_reduce32(key_up, R, Min32{});
                 uint32_t down_r = wave_reduce32(key_down, R, Min32{});
@@ -439,31 +481,31 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
                 if (__builtin_expect(miss >= -kTol && miss <= kTol, 1)) {
                     // repair one slot at a time: add the cheapest free slot / drop the dearest taken slot; the
                     // first step's winners are already known, further steps redo one reduction each
-                    bool exact = true;                    // false: a cost left the 32-bit window, start over in the general path
+                    bool exact = true;                    // false: no near candidate, start over in the general path
                     while (miss > 0) {
-                        const int win = (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)up_r) & 63u);
-                        if (lane == win) {
+                        const uint32_t best = (uint32_t)__builtin_amdgcn_readfirstlane((int)up_r);
+                        if (best >= kFarKey) { exact = false; break; }
+                        if (lane == (int)(best & 63u)) {
                             ++kk;
                             p_prev = p_next;
                             p_next += lc1;
                             up = rail.c0 + (p_next >> 16) - vi;
-                            key_up = kk < m ? (((uint32_t)up << 6) | (uint32_t)lane) : 0xFFFFFFFFu;
+                            key_up = kk < m ? up_key() : kNoKey;
                         }
                         if (--miss == 0) break;
-                        if (any_lane((lane == win) & (kk < m) & (up >= kRelSpan))) { exact = false; break; }
                         up_r = wave_reduce32(key_up, R, Min32{});
                     }
                     while (miss < 0) {
-                        const int win = 63 - (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)down_r) & 63u);
-                        if (lane == win) {
+                        const uint32_t best = (uint32_t)__builtin_amdgcn_readfirstlane((int)down_r);
+                        if (best >= kFarKey) { exact = false; break; }
+                        if (lane == 63 - (int)(best & 63u)) {
                             --kk;
                             p_next = p_prev;
                             p_prev -= lc1;
                             down = vi - (rail.c0 + (p_prev >> 16));
-                            key_down = kk > 0 ? (((uint32_t)down << 6) | lane_rev) : 0xFFFFFFFFu;
+                            key_down = kk > 0 ? down_key() : kNoKey;
                         }
                         if (++miss == 0) break;
-                        if (any_lane((lane == win) & (kk > 0) & (down >= kRelSpan))) { exact = false; break; }
                         down_r = wave_reduce32(key_down, R, Min32{});
                     }
                     if (__builtin_expect(exact, 1)) {
@@ -538,22 +580,22 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
     if (lane == 0) ps->n_bound = ps->n_pending + n_before;
 }
 
-template <int kWide>
+template <int kWide, bool kFar>
 __global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams rp, int mode,
                                                         const RunRec* __restrict__ recs)
 {
-    bind_chain<kWide>(b, rp, mode, recs);
+    bind_chain<kWide, kFar>(b, rp, mode, recs);
 }
 
 // The chain is one wavefront; the tile tables of the copy kernels depend on the slice table only, not
 // on the binding.  On a first plan both go into one launch: workgroup 0 walks the chain, the others
 // build the tables, so the tables cost no time of their own.
-template <int kWide>
+template <int kWide, bool kFar>
 __global__ void __launch_bounds__(256) bind_chain_tables_kernel(BatchDev b, RailParams rp, int mode,
                                                                 const RunRec* __restrict__ recs)
 {
     if (blockIdx.x == 0) {
-        if (threadIdx.x < 64) bind_chain<kWide>(b, rp, mode, recs);
+        if (threadIdx.x < 64) bind_chain<kWide, kFar>(b, rp, mode, recs);
         return;
     }
     build_tile_tables(b, blockIdx.x - 1, gridDim.x - 1);
@@ -639,16 +681,38 @@ hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, h
     e = exclusive_scan(plen, b.n_slices, b.len_pre, b.scan_partials, s);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(run_records_kernel, dim3((b.run_capacity + 1 + 255) / 256), dim3(256), 0, s, b, rp, mode);
-    if (mode & kBindBuildTables) {
-        const dim3 grid(1 + tile_table_blocks(b)), block(256);
-        if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_tables_kernel<16>, grid, block, 0, s, b, rp, mode, b.run_rec);
-        else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_tables_kernel<32>, grid, block, 0, s, b, rp, mode, b.run_rec);
-        else                       hipLaunchKernelGGL(bind_chain_tables_kernel<64>, grid, block, 0, s, b, rp, mode, b.run_rec);
-    } else {
-        if (rp.n_rails <= 16)      hipLaunchKernelGGL(bind_chain_kernel<16>, dim3(1), dim3(64), 0, s, b, rp, mode, b.run_rec);
-        else if (rp.n_rails <= 32) hipLaunchKernelGGL(bind_chain_kernel<32>, dim3(1), dim3(64), 0, s, b, rp, mode, b.run_rec);
-        else                       hipLaunchKernelGGL(bind_chain_kernel<64>, dim3(1), dim3(64), 0, s, b, rp, mode, b.run_rec);
+    // Which variant of the chain: when the rails' head costs lie close together at the start (idle rails, short
+    // queues) and no rail's slots are far apart, all rails stay close to the common level throughout and the
+    // variant without far keys is a few percent faster; otherwise (long queues, bytes of a rotation pass ahead,
+    // large slices on a slow rail) rails may sit far from the level.  Either variant is exact for any input.
+    bool far_keys = (mode & kBindAfterRotation) != 0;
+    {
+        uint64_t lo = ~0ull, hi = 0;
+        for (uint32_t d = 0; d < rp.n_rails; ++d) {
+            if (!((rp.admitted >> d) & 1)) continue;
+            const uint64_t h = rp.c0[d] + ((rp.A[d] * rp.c1[d]) >> 16);       // in range by the plan's precondition
+            lo = h < lo ? h : lo;
+            hi = h > hi ? h : hi;
+            // a rail whose slots are a large part of the window apart often has its next slot outside it
+            if (((b.slice_bytes * rp.c1[d]) >> 16) >= (kRelSpan >> 2)) far_keys = true;
+        }
+        if (hi >= lo && hi - lo >= (kRelSpan >> 1)) far_keys = true;
     }
+    auto launch_chain = [&](auto wide, auto far) {
+        constexpr int kW = decltype(wide)::value;
+        constexpr bool kF = decltype(far)::value;
+        if (mode & kBindBuildTables)
+            hipLaunchKernelGGL((bind_chain_tables_kernel<kW, kF>), dim3(1 + tile_table_blocks(b)), dim3(256), 0, s, b, rp, mode, b.run_rec);
+        else
+            hipLaunchKernelGGL((bind_chain_kernel<kW, kF>), dim3(1), dim3(64), 0, s, b, rp, mode, b.run_rec);
+    };
+    auto launch_width = [&](auto far) {
+        if (rp.n_rails <= 16)      launch_chain(std::integral_constant<int, 16>{}, far);
+        else if (rp.n_rails <= 32) launch_chain(std::integral_constant<int, 32>{}, far);
+        else                       launch_chain(std::integral_constant<int, 64>{}, far);
+    };
+    if (far_keys) launch_width(std::true_type{});
+    else          launch_width(std::false_type{});
     hipLaunchKernelGGL(bind_emit_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, rp, up);
     return hipGetLastError();
 }
