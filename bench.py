@@ -443,7 +443,10 @@ def main():
     ctx, batches, stream, src, arena, dst = run.ctx, run.batches, run.stream, run.src, run.arena, run.dst
     n_slices, declare_ms = run.n_slices, run.declare_host_ms
 
-    plan_stream = torch.cuda.Stream(dev)               # default priority
+    # default priority; created one after the other so that, with the process's four hardware queues dealt to
+    # streams in turn, the two plan streams and the first stream sit on three different queues
+    plan_stream = torch.cuda.Stream(dev)
+    plan_stream2 = torch.cuda.Stream(dev)
 
     def step_pipelined(h):
         run.step_pipelined(h, plan_stream)
@@ -470,7 +473,7 @@ def main():
         # Third pass, reported beside the headline only: plans alternate between two plan streams, so the (mostly
         # one-wavefront) binding chains of two later steps run side by side under the copies of an earlier one.
         run.reset_all()
-        plan_streams = [plan_stream, torch.cuda.Stream(dev)]
+        plan_streams = [plan_stream, plan_stream2]
         turn = [0]
 
         def step_two_plan_streams(h):
@@ -735,7 +738,7 @@ def main():
         rec.update(summarize(wo, ro.n_slices, steps_o, e1, t1, e2, t2))
         # plans alternating between two plan streams: the one-wavefront binding chains of two later steps side by side
         ro.reset_all()
-        pair, turn_o = [plan_stream, torch.cuda.Stream(dev)], [0]
+        pair, turn_o = [plan_stream, plan_stream2], [0]
 
         def step_two_plan_streams_o(h):
             turn_o[0] += 1

@@ -98,6 +98,24 @@ def _runs_workload(rng, kind):
         lat = rng.integers(0, 2**32 - 1, size=R)
     if kind == 4:                                              # long queues
         queued = rng.integers(0, 1 << 31, size=R)                # (max A + payload) * max c1 stays below 2^63
+    if kind in (6, 7, 8):
+        # many transfers on rails that start level with each other (the chain's short path and its near keys);
+        # kind 7: some rails behind queues so long that they join late or never; kind 8: up to 64 rails
+        S = int(rng.choice([4096, 16384, 65536])) + (int(rng.integers(0, 64)) if rng.random() < 0.3 else 0)
+        pages = rng.integers(2, 80, size=int(rng.integers(60, 260)))
+        page = int(rng.choice([2048, 18432, 32768]))
+        lens = (pages * page).astype(np.uint64)
+        off = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.uint64)
+        ptr = np.arange(len(lens) + 1, dtype=np.uint32)
+        total = int(lens.sum())
+        R = int(rng.integers(2, 17)) if kind != 8 else int(rng.integers(17, 65))
+        bw = rng.choice([25000, 50000, 100000, 400000], size=R)
+        lat = np.full(R, 5000)
+        queued = rng.integers(0, 1 << 12, size=R)
+        b1, pen = np.full(R, 256), np.full(R, 256)
+        if kind == 7:
+            far = rng.random(R) < 0.4
+            queued = np.where(far, rng.integers(1 << 20, 1 << 30, size=R), queued)
     u = rng.random(R)
     health = np.where(u < 0.2, 2, np.where(u < 0.4, 1, 0)).astype(np.uint8)       # excluded / degraded / healthy
     if (health == 2).all():
@@ -109,11 +127,11 @@ def _runs_workload(rng, kind):
                       W._extents(1, off, lens), rails, "u8")
 
 
-@pytest.mark.parametrize("kind", range(6))
+@pytest.mark.parametrize("kind", range(9))
 def test_run_parallel_binding_matches_oracle(H, oracle, kind):
     # plan-only: degenerate telemetry (ties, sub-picosecond steps, huge latencies and queues)
     rng = np.random.Generator(np.random.PCG64(1000 + kind))
-    for trial in range(25):
+    for trial in range(25 if kind < 6 else 12):
         w = _runs_workload(rng, kind)
         print("runs kind", kind, "trial", trial, "S", w.slice_bytes, "D", w.n_desc, "R", w.rails.shape[0], flush=True)
         s = oracle.split(w.src_ptr, w.src_ext, w.slice_bytes)
