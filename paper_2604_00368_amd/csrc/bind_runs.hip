@@ -372,12 +372,52 @@ __device__ __attribute__((noinline)) ChainVars bind_run_general(ChainVars cv, Ra
     return ChainVars{P, T, Bd, ref_level, cnt, all_proven ? 1u : 0u, k};
 }
 
-typedef uint32_t Quad __attribute__((ext_vector_type(4)));       // half a run record: {len, m, level} or {level_f, inv_len}
+// Run records reach the chain through a ring of blocks in LDS, kWide records a block, one per lane, each as
+// two 16-byte halves {len, m, level} and {level_f, inv_len}.  A second wavefront of the workgroup, the feeder,
+// copies them there from global memory several blocks ahead.  A load that the chain issued itself would have to
+// be awaited through the counter its row stores also use, that is, at once and at full memory latency per block,
+// which is long while another batch's copies saturate the memory.  `filled` counts the blocks the feeder has
+// written, `taken` those the chain has read; the feeder stays at most kRingBlocks ahead, the chain waits only
+// for a block that is not there yet.  Neither wait depends on the waiting wavefront itself, and both loops end
+// with the run table.
+typedef uint32_t Quad __attribute__((ext_vector_type(4)));
+constexpr int kRingBlocks = 8;
 static_assert(sizeof(RunRec) == 32, "a run record is two 16-byte halves");
 
+template <int kWide>
+struct RecordRing {
+    Quad lo[kRingBlocks][kWide];
+    Quad hi[kRingBlocks][kWide];
+    uint32_t filled;
+    uint32_t taken;
+};
+
+// First instruction of both roles, before the workgroup's barrier.
+template <int kWide>
+__device__ __forceinline__ void ring_reset(RecordRing<kWide>& ring)
+{
+    if (threadIdx.x == 0) { ring.filled = 0; ring.taken = 0; }
+}
+
+template <int kWide>
+__device__ __forceinline__ void feed_records(const BatchDev& b, const RunRec* __restrict__ recs, RecordRing<kWide>& ring, int lane)
+{
+    if (lane >= kWide) return;
+    const uint64_t n_runs = b.plan->n_runs;
+    const Quad* src = reinterpret_cast<const Quad*>(recs);
+    for (uint64_t j = 0; j * kWide < n_runs; ++j) {
+        while (__hip_atomic_load(&ring.taken, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) + (uint32_t)kRingBlocks <= (uint32_t)j)
+            __builtin_amdgcn_s_sleep(4);
+        const uint64_t r = j * kWide + lane < n_runs ? j * kWide + lane : n_runs;      // the table ends with a spare record
+        const Quad lo = src[2 * r], hi = src[2 * r + 1];
+        ring.lo[j % kRingBlocks][lane] = lo;
+        ring.hi[j % kRingBlocks][lane] = hi;
+        __hip_atomic_store(&ring.filled, (uint32_t)j + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+}
+
 template <int kWide, bool kFar>
-__device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& rp, int mode,
-                                           const RunRec* __restrict__ recs)
+__device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& rp, int mode, RecordRing<kWide>& ring)
 {
     const int lane = threadIdx.x;
     if (lane >= kWide) return;
@@ -537,17 +577,17 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
         return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, t) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)lo, t);
     };
 
-    // Records are fetched kWide at a time, one per lane, a block ahead of their use.
-    auto record_at = [&](uint64_t r, Quad& lo, Quad& hi) {                    // the table ends with a spare record
-        const Quad* src = reinterpret_cast<const Quad*>(recs + (r < n_runs ? r : n_runs));
-        lo = src[0];
-        hi = src[1];
+    // Block j of kWide records, one per lane, from the ring the feeder wavefront keeps filled.
+    auto take_block = [&](uint64_t j, Quad& lo, Quad& hi) {
+        while (__hip_atomic_load(&ring.filled, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) <= (uint32_t)j)
+            __builtin_amdgcn_s_sleep(1);
+        lo = ring.lo[j % kRingBlocks][lane];
+        hi = ring.hi[j % kRingBlocks][lane];
+        if (lane == 0) __hip_atomic_store(&ring.taken, (uint32_t)j + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
     };
-    Quad next_lo, next_hi;
-    record_at((uint64_t)lane, next_lo, next_hi);
+    Quad mine_lo = {0, 0, 0, 0}, mine_hi = {0, 0, 0, 0};
     for (uint64_t blk = 0; blk < n_runs; blk += kWide) {
-        const Quad mine_lo = next_lo, mine_hi = next_hi;
-        record_at(blk + kWide + lane, next_lo, next_hi);
+        take_block(blk / kWide, mine_lo, mine_hi);
         const int in_blk = (int)(n_runs - blk < (uint64_t)kWide ? n_runs - blk : (uint64_t)kWide);
         for (int t = 0; t < in_blk; ++t) {
             const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)mine_lo.x, t);
@@ -580,11 +620,16 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
     if (lane == 0) ps->n_bound = ps->n_pending + n_before;
 }
 
+// Wavefront 0 walks the chain, wavefront 1 feeds it the run records.
 template <int kWide, bool kFar>
-__global__ void __launch_bounds__(64) bind_chain_kernel(BatchDev b, RailParams rp, int mode,
-                                                        const RunRec* __restrict__ recs)
+__global__ void __launch_bounds__(128) bind_chain_kernel(BatchDev b, RailParams rp, int mode,
+                                                         const RunRec* __restrict__ recs)
 {
-    bind_chain<kWide, kFar>(b, rp, mode, recs);
+    __shared__ RecordRing<kWide> ring;
+    ring_reset(ring);
+    __syncthreads();
+    if (threadIdx.x < 64) bind_chain<kWide, kFar>(b, rp, mode, ring);
+    else feed_records<kWide>(b, recs, ring, (int)threadIdx.x - 64);
 }
 
 // The chain is one wavefront; the tile tables of the copy kernels depend on the slice table only, not
@@ -594,8 +639,12 @@ template <int kWide, bool kFar>
 __global__ void __launch_bounds__(256) bind_chain_tables_kernel(BatchDev b, RailParams rp, int mode,
                                                                 const RunRec* __restrict__ recs)
 {
+    __shared__ RecordRing<kWide> ring;
     if (blockIdx.x == 0) {
-        if (threadIdx.x < 64) bind_chain<kWide, kFar>(b, rp, mode, recs);
+        ring_reset(ring);
+        __syncthreads();
+        if (threadIdx.x < 64) bind_chain<kWide, kFar>(b, rp, mode, ring);
+        else if (threadIdx.x < 128) feed_records<kWide>(b, recs, ring, (int)threadIdx.x - 64);
         return;
     }
     build_tile_tables(b, blockIdx.x - 1, gridDim.x - 1);
@@ -704,7 +753,7 @@ hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, h
         if (mode & kBindBuildTables)
             hipLaunchKernelGGL((bind_chain_tables_kernel<kW, kF>), dim3(1 + tile_table_blocks(b)), dim3(256), 0, s, b, rp, mode, b.run_rec);
         else
-            hipLaunchKernelGGL((bind_chain_kernel<kW, kF>), dim3(1), dim3(64), 0, s, b, rp, mode, b.run_rec);
+            hipLaunchKernelGGL((bind_chain_kernel<kW, kF>), dim3(1), dim3(128), 0, s, b, rp, mode, b.run_rec);
     };
     auto launch_width = [&](auto far) {
         if (rp.n_rails <= 16)      launch_chain(std::integral_constant<int, 16>{}, far);
