@@ -719,16 +719,15 @@ hipError_t launch_bind_runs(const BatchDev& b, const RailParams& rp, int mode, h
     const bool use_pending = (mode & kBindUsePending) != 0;
     const int up = use_pending ? 1 : 0;
     if (!use_pending) hipLaunchKernelGGL(set_pending_all_kernel, dim3(1), dim3(1), 0, s, b);
+    // run ids (a scan of the run heads) and the bytes bound before every pending position, in the same launches
     RunHead head{b.s_len, use_pending ? b.pending : nullptr, &b.plan->n_pending};
-    hipError_t e = exclusive_scan(head, b.n_slices, b.scan_tmp, b.scan_partials, s);
+    PendingLen plen{b.s_len, use_pending ? b.pending : nullptr, &b.plan->n_pending};
+    hipError_t e = exclusive_scan2(head, plen, b.n_slices, b.n_slices, b.scan_tmp, b.len_pre, b.scan_partials, b.scan_partials2, s);
     if (e != hipSuccess) return e;
     uint64_t blocks = (b.n_slices + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(run_table_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, b, up);
-    // bytes bound before every pending position, then one record per run for the chain
-    PendingLen plen{b.s_len, use_pending ? b.pending : nullptr, &b.plan->n_pending};
-    e = exclusive_scan(plen, b.n_slices, b.len_pre, b.scan_partials, s);
-    if (e != hipSuccess) return e;
+    // one record per run for the chain
     hipLaunchKernelGGL(run_records_kernel, dim3((b.run_capacity + 1 + 255) / 256), dim3(256), 0, s, b, rp, mode);
     // Which variant of the chain: when the rails' head costs lie close together at the start (idle rails, short
     // queues) and no rail's slots are far apart, all rails stay close to the common level throughout and the

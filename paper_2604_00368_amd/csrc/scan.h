@@ -119,4 +119,86 @@ hipError_t exclusive_scan(F f, uint64_t n, uint64_t* out, uint64_t* partials, hi
     return hipGetLastError();
 }
 
+// Two independent sum scans in the same three launches (a launch of a small kernel costs more than its
+// work): out1[i] = sum f1(0..i-1) for i in [0, n1], out2 likewise over n2; partials1 and partials2 each
+// need scan_partials_capacity(max(n1, n2)) entries.
+template <class F1, class F2>
+__global__ void __launch_bounds__(kScanBlock) scan_reduce2_kernel(F1 f1, F2 f2, uint64_t n1, uint64_t n2,
+                                                                 uint64_t* partials1, uint64_t* partials2)
+{
+    const uint64_t base = (uint64_t)blockIdx.x * kScanTile + (uint64_t)threadIdx.x * kScanItems;
+    uint64_t sum1 = 0, sum2 = 0;
+#pragma unroll
+    for (int k = 0; k < (int)kScanItems; ++k) {
+        if (base + k < n1) sum1 += f1(base + k);
+        if (base + k < n2) sum2 += f2(base + k);
+    }
+    uint64_t total1, total2;
+    block_exclusive_scan(sum1, &total1, ScanSum{});
+    block_exclusive_scan(sum2, &total2, ScanSum{});
+    if (threadIdx.x == 0) { partials1[blockIdx.x] = total1; partials2[blockIdx.x] = total2; }
+}
+
+// (a template for the same reason as scan_spine_kernel: internal linkage without an unused-function warning)
+template <class Op>
+static __global__ void __launch_bounds__(kScanBlock) scan_spine2_kernel(Op, uint64_t* partials1, uint64_t* partials2, uint64_t nb)
+{
+    uint64_t carry1 = 0, carry2 = 0;
+    for (uint64_t lo = 0; lo < nb; lo += kScanBlock) {
+        const uint64_t i = lo + threadIdx.x;
+        uint64_t total1, total2;
+        const uint64_t ex1 = block_exclusive_scan(i < nb ? partials1[i] : 0, &total1, ScanSum{});
+        const uint64_t ex2 = block_exclusive_scan(i < nb ? partials2[i] : 0, &total2, ScanSum{});
+        if (i < nb) { partials1[i] = carry1 + ex1; partials2[i] = carry2 + ex2; }
+        carry1 += total1;
+        carry2 += total2;
+    }
+    if (threadIdx.x == 0) { partials1[nb] = carry1; partials2[nb] = carry2; }
+}
+
+template <class F1, class F2>
+__global__ void __launch_bounds__(kScanBlock) scan_down2_kernel(F1 f1, F2 f2, uint64_t n1, uint64_t n2,
+                                                               const uint64_t* partials1, const uint64_t* partials2,
+                                                               uint64_t* out1, uint64_t* out2)
+{
+    const uint64_t base = (uint64_t)blockIdx.x * kScanTile + (uint64_t)threadIdx.x * kScanItems;
+    uint64_t v1[kScanItems], v2[kScanItems];
+    uint64_t sum1 = 0, sum2 = 0;
+#pragma unroll
+    for (int k = 0; k < (int)kScanItems; ++k) {
+        v1[k] = base + k < n1 ? f1(base + k) : 0;
+        v2[k] = base + k < n2 ? f2(base + k) : 0;
+        sum1 += v1[k];
+        sum2 += v2[k];
+    }
+    uint64_t total1, total2;
+    uint64_t run1 = partials1[blockIdx.x] + block_exclusive_scan(sum1, &total1, ScanSum{});
+    uint64_t run2 = partials2[blockIdx.x] + block_exclusive_scan(sum2, &total2, ScanSum{});
+    // entry n of either output is its grand total: it is written by the lane that reaches index n
+#pragma unroll
+    for (int k = 0; k < (int)kScanItems; ++k) {
+        if (base + k <= n1) out1[base + k] = run1;
+        if (base + k <= n2) out2[base + k] = run2;
+        run1 += v1[k];
+        run2 += v2[k];
+    }
+    if (base + kScanItems == n1) out1[n1] = run1;
+    if (base + kScanItems == n2) out2[n2] = run2;
+}
+
+template <class F1, class F2>
+hipError_t exclusive_scan2(F1 f1, F2 f2, uint64_t n1, uint64_t n2, uint64_t* out1, uint64_t* out2, uint64_t* partials1,
+                           uint64_t* partials2, hipStream_t s)
+{
+    if (n1 == 0 || n2 == 0) return hipErrorInvalidValue;
+    const uint64_t n = n1 > n2 ? n1 : n2;
+    const uint64_t nb = (n + kScanTile - 1) / kScanTile;
+    if (nb > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((scan_reduce2_kernel<F1, F2>), dim3((uint32_t)nb), dim3(kScanBlock), 0, s, f1, f2, n1, n2, partials1, partials2);
+    hipLaunchKernelGGL((scan_spine2_kernel<ScanSum>), dim3(1), dim3(kScanBlock), 0, s, ScanSum{}, partials1, partials2, nb);
+    hipLaunchKernelGGL((scan_down2_kernel<F1, F2>), dim3((uint32_t)nb), dim3(kScanBlock), 0, s, f1, f2, n1, n2, partials1, partials2,
+                       out1, out2);
+    return hipGetLastError();
+}
+
 }  // namespace tent

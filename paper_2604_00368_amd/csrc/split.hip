@@ -22,6 +22,13 @@ hipError_t launch_extent_scan(const tent_extent* ext, uint64_t n_ext, uint64_t* 
     return exclusive_scan(ExtentLen{ext}, n_ext, pre, partials, s);
 }
 
+// both sides' prefixes in the same three launches
+hipError_t launch_extent_scans(const BatchDev& b, hipStream_t s)
+{
+    return exclusive_scan2(ExtentLen{b.src_ext}, ExtentLen{b.dst_ext}, b.n_src_ext, b.n_dst_ext, b.src_pre, b.dst_pre,
+                           b.scan_partials, b.scan_partials2, s);
+}
+
 // ---- S2: slices per transfer, exclusive scan -> first slice index of every transfer ---------
 struct SliceCount {
     const uint32_t* ptr;

@@ -684,6 +684,7 @@ int declare_impl(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
     cv.want(&d.rot_cnt, rot_chunks * TENT_MAX_RAILS);
     cv.want(&d.scan_tmp, scan_n + 1);
     cv.want(&d.scan_partials, scan_partials_capacity(scan_n));
+    cv.want(&d.scan_partials2, scan_partials_capacity(scan_n));
     cv.want(&d.plan, 1);
     if (cv.overflow) return TENT_ERR_NOMEM;
 
@@ -940,8 +941,7 @@ int tent_plan(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state* rails, u
     if (!replan) {
         {
             StageTimer t(ctx, TENT_T_EXTENT_SCAN, s);
-            HIP_TRY(launch_extent_scan(d.src_ext, d.n_src_ext, d.src_pre, d.scan_partials, s));
-            HIP_TRY(launch_extent_scan(d.dst_ext, d.n_dst_ext, d.dst_pre, d.scan_partials, s));
+            HIP_TRY(launch_extent_scans(d, s));
         }
         {
             StageTimer t(ctx, TENT_T_SLICE_SCAN, s);
@@ -1058,8 +1058,7 @@ int tent_plan_dispatch(tent_ctx* ctx, tent_batch_t batch, const tent_rail_state*
     if (first_plan) {
         {
             StageTimer t(ctx, TENT_T_EXTENT_SCAN, s);
-            HIP_TRY(launch_extent_scan(d.src_ext, d.n_src_ext, d.src_pre, d.scan_partials, s));
-            HIP_TRY(launch_extent_scan(d.dst_ext, d.n_dst_ext, d.dst_pre, d.scan_partials, s));
+            HIP_TRY(launch_extent_scans(d, s));
         }
         {
             StageTimer t(ctx, TENT_T_SLICE_SCAN, s);

@@ -183,6 +183,7 @@ struct BatchDev {
     uint32_t* rot_cnt;             // same shape: slices per chunk and rail
     uint64_t* scan_tmp;            // [max(n_ext, n_slices, n_desc)+1] scan workspace
     uint64_t* scan_partials;       // per-block partial sums of the scans
+    uint64_t* scan_partials2;      // the same for the second of two scans that share their launches
     PlanState* plan;               // one result block
     const uint64_t* seg_base;      // context-wide table of segment base addresses
 };
@@ -198,6 +199,7 @@ enum : uint32_t { kRotChunk = 1024 };                // retried slices one rotat
 enum : int { kBindUsePending = 1, kBindAfterRotation = 2, kBindBuildTables = 4 };
 
 // ---- launch wrappers (each enqueues on `s` and returns the launch status) -------------------
+hipError_t launch_extent_scans(const BatchDev& b, hipStream_t s);
 hipError_t launch_extent_scan(const tent_extent* ext, uint64_t n_ext, uint64_t* pre, uint64_t* partials,
                               hipStream_t s);
 hipError_t launch_slice_scan(const BatchDev& b, hipStream_t s);
