@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cstring>
 #include <mutex>
+#include <thread>
 #include <new>
 #include <utility>
 #include <vector>
@@ -379,42 +380,102 @@ bool pointers_ok(uint32_t n_desc, const uint32_t* p)
     return true;
 }
 
-// Walk both extent lists of every transfer: structure, bounds, equal lengths; every extent is copied
-// to `se_out` / `de_out` (if not null) on the way.  Also returns the payload and the number of slices
-// the device splitter will produce.
-int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const tent_extent* se,
-             const uint32_t* dp, const tent_extent* de, tent_extent* se_out, tent_extent* de_out,
-             uint64_t* payload, uint64_t* n_slices, uint64_t* len_bits, uint64_t* max_req_slices)
+// Walk both extent lists of the transfers [j0, j1): structure, bounds, equal lengths; every extent is
+// copied to `se_out` / `de_out` (if not null) on the way.
+struct WalkResult {
+    int rc = TENT_OK;
+    uint64_t total = 0, slices = 0, bits = 0, most = 0;
+};
+
+void validate_range(const tent_ctx* ctx, uint32_t j0, uint32_t j1, const uint32_t* sp, const tent_extent* se,
+                    const uint32_t* dp, const tent_extent* de, tent_extent* se_out, tent_extent* de_out, WalkResult* out)
 {
     const uint64_t S = ctx->cfg.slice_bytes;
     const size_t n_seg = ctx->segments.size();
     const Segment* seg = ctx->segments.data();
-    uint64_t total = 0, slices = 0, bits = 0, most = 0;
-    for (uint32_t j = 0; j < n_desc; ++j) {
+    WalkResult r;
+    for (uint32_t j = j0; j < j1; ++j) {
         uint64_t ls = 0, ld = 0;
         for (uint32_t e = sp[j]; e < sp[j + 1]; ++e) {
             const tent_extent x = se[e];
-            if (x.len == 0 || x.seg >= n_seg) return TENT_ERR_INVALID;
+            if (x.len == 0 || x.seg >= n_seg) { r.rc = TENT_ERR_INVALID; *out = r; return; }
             const uint64_t seg_len = seg[x.seg].len;
-            if (x.off > seg_len || x.len > seg_len - x.off) return TENT_ERR_INVALID;
+            if (x.off > seg_len || x.len > seg_len - x.off) { r.rc = TENT_ERR_INVALID; *out = r; return; }
             if (se_out) se_out[e] = x;
             ls += x.len;
-            bits |= x.len;
+            r.bits |= x.len;
         }
         for (uint32_t e = dp[j]; e < dp[j + 1]; ++e) {
             const tent_extent x = de[e];
-            if (x.len == 0 || x.seg >= n_seg) return TENT_ERR_INVALID;
+            if (x.len == 0 || x.seg >= n_seg) { r.rc = TENT_ERR_INVALID; *out = r; return; }
             const uint64_t seg_len = seg[x.seg].len;
-            if (x.off > seg_len || x.len > seg_len - x.off) return TENT_ERR_INVALID;
+            if (x.off > seg_len || x.len > seg_len - x.off) { r.rc = TENT_ERR_INVALID; *out = r; return; }
             if (de_out) de_out[e] = x;
             ld += x.len;
-            bits |= x.len;
+            r.bits |= x.len;
         }
-        if (ls != ld) return TENT_ERR_INVALID;
-        total += ls;
+        if (ls != ld) { r.rc = TENT_ERR_INVALID; *out = r; return; }
+        r.total += ls;
         const uint64_t cnt = (ls + S - 1) / S;
-        slices += cnt;
-        most = std::max(most, cnt);
+        r.slices += cnt;
+        r.most = std::max(r.most, cnt);
+    }
+    *out = r;
+}
+
+// The whole batch; also returns the payload and the number of slices the device splitter will produce.
+// Large batches are walked by a few threads, each over a range of transfers with about the same number of
+// extents: the walk streams some tens of megabytes and is the longest part of a declaration.
+int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const tent_extent* se,
+             const uint32_t* dp, const tent_extent* de, tent_extent* se_out, tent_extent* de_out,
+             uint64_t* payload, uint64_t* n_slices, uint64_t* len_bits, uint64_t* max_req_slices)
+{
+    constexpr uint32_t kMaxWalkers = 4;
+    constexpr uint64_t kExtentsPerWalker = 1ull << 16;
+    const uint64_t n_ext = (uint64_t)sp[n_desc] + dp[n_desc];
+    uint32_t walkers = (uint32_t)std::min<uint64_t>(kMaxWalkers, n_ext / kExtentsPerWalker);
+    walkers = std::min(walkers, std::max(1u, std::thread::hardware_concurrency()));
+    WalkResult part[kMaxWalkers];
+    uint32_t used = 1;
+    if (walkers >= 2) {
+        // cut points: transfers at which the running count of extents passes k / walkers of the total
+        uint32_t cut[kMaxWalkers + 1];
+        cut[0] = 0;
+        for (uint32_t k = 1; k < walkers; ++k) {
+            const uint64_t want = n_ext * k / walkers;
+            uint32_t lo = cut[k - 1], hi = n_desc;
+            while (lo < hi) {
+                const uint32_t mid = lo + (hi - lo) / 2;
+                if ((uint64_t)sp[mid] + dp[mid] < want) lo = mid + 1; else hi = mid;
+            }
+            cut[k] = lo;
+        }
+        cut[walkers] = n_desc;
+        std::thread th[kMaxWalkers];
+        uint32_t started = 0;
+        try {
+            for (uint32_t k = 1; k < walkers; ++k) {
+                th[k] = std::thread(validate_range, ctx, cut[k], cut[k + 1], sp, se, dp, de, se_out, de_out, &part[k]);
+                ++started;
+            }
+        } catch (...) {
+            // no more threads to be had: the ranges not handed out are walked here
+        }
+        validate_range(ctx, cut[0], cut[1], sp, se, dp, de, se_out, de_out, &part[0]);
+        for (uint32_t k = 1; k <= started; ++k) th[k].join();
+        for (uint32_t k = started + 1; k < walkers; ++k)
+            validate_range(ctx, cut[k], cut[k + 1], sp, se, dp, de, se_out, de_out, &part[k]);
+        used = walkers;
+    } else {
+        validate_range(ctx, 0, n_desc, sp, se, dp, de, se_out, de_out, &part[0]);
+    }
+    uint64_t total = 0, slices = 0, bits = 0, most = 0;
+    for (uint32_t k = 0; k < used; ++k) {
+        if (part[k].rc != TENT_OK) return part[k].rc;
+        total += part[k].total;
+        slices += part[k].slices;
+        bits |= part[k].bits;
+        most = std::max(most, part[k].most);
     }
     *payload = total;
     *n_slices = slices;
