@@ -8,14 +8,18 @@
 // are nondecreasing in k, so picking the cheapest rail m times is a merge of R sorted sequences: the
 // run takes the m smallest triples (f_d(k), d, k) in lexicographic order, and the slice at position
 // p of the run gets the triple of rank p.  Three steps follow from that:
-//   1. run table     maximal runs of equal-length pending slices (flag heads, exclusive scan);
+//   1. run table     maximal runs of equal-length pending slices (flag heads, exclusive scan), and one record
+//                    per run with everything that does not depend on the rails' state, among it the cost level
+//                    at which the run will end according to a floating-point water-filling model;
 //   2. chain         one wavefront, lane = rail, walks the runs in order and finds, per run, how many
-//                    slots k_d each rail takes.  The split is found by evaluating
-//                    count_d(v) = #{k : f_d(k) <= v} (closed form, two integer divisions) at a cost
-//                    level v guessed from a floating-point water-filling model, then repaired one
-//                    slot at a time (add the cheapest free slot / drop the dearest taken slot) until
-//                    exactly m slots are taken.  Floating point only steers the guess; the counts
-//                    and repairs are integer and exact.  Runs of one slice (tails) are a plain argmin.
+//                    slots k_d each rail takes.  The split is found from the record's level (slot count per
+//                    rail from a floating-point estimate, confirmed against the integer costs of the two
+//                    neighbouring slots) and repaired one slot at a time (add the cheapest free slot / drop
+//                    the dearest taken slot) until exactly m slots are taken; where the estimate does not
+//                    hold, count_d(v) = #{k : f_d(k) <= v} (closed form, two integer divisions) is evaluated
+//                    at bracketed levels instead.  Floating point only steers the guess; the counts and
+//                    repairs are integer and exact.  Runs of one slice (tails) are a plain argmin.  A second
+//                    wavefront feeds the run records to the chain through a ring in LDS.
 //   3. emit          one lane per slot (d, k): its rank in the run is
 //                    k + sum_{d' < d} count_d'(f) + sum_{d' > d} count_d'(f - 1),  f = f_d(k),
 //                    which gives the slice it belongs to; staging offset = T_d at run start + k l.
@@ -247,9 +251,9 @@ __global__ void __launch_bounds__(256) run_records_kernel(BatchDev b, RailParams
 // Per rail the chain keeps the exact product P = A * c1 of the bytes in flight (so that a slot's cost
 // is c0 + ((P + j * l * c1) >> 16) with additions only), the bytes bound T, and a floating-point
 // shadow of A for the estimates.  The loop is a chain of dependent instructions on one wavefront,
-// so what counts is how few it issues per run and that it never waits for memory: run records are
-// fetched kWide at a time, one per lane, a whole block ahead of their use, and handed out with
-// readlane; results leave as one row of K and one of T per run.  The general path sits in a function of
+// so what counts is how few it issues per run and that it never waits for memory: run records come
+// kWide at a time, one per lane, out of a ring in LDS that a second wavefront fills ahead of their use,
+// and are handed out with readlane; results leave as one row of K and one of T per run.  The general path sits in a function of
 // its own: inlined, its code and registers made the loop's short paths measurably slower.
 
 // State of one lane of the chain that a run may change, and the slots the lane takes in the run.
