@@ -194,8 +194,9 @@ int tent_register_segment(tent_ctx *ctx, void *dev_base, uint64_t len, uint32_t 
  * Errors: TENT_ERR_INVALID for null pointers, n_desc = 0, an empty transfer, a
  * zero-length extent, an extent outside its segment, or unequal source and
  * destination lengths; TENT_ERR_RANGE when the batch holds more than 2^32-2 slices.
- * The call returns as soon as the host arrays are copied (Section 4.1: submitting a transfer
- * returns immediately): the upload of the descriptors, the ordering of the destination extents by
+ * The call returns as soon as the host arrays are checked and copied (Section 4.1: submitting a
+ * transfer returns immediately; batches of more than 128 Ki extents are walked by up to four host
+ * threads that end with the call): the upload of the descriptors, the ordering of the destination extents by
  * address and the overlap check run on a stream of the library's own (default priority) and hold up
  * none of the caller's streams.  Unless TENT_FLAG_SKIP_OVERLAP_CHECK is set, a destination extent
  * that overlaps another destination extent or any source extent of the batch makes the batch

@@ -428,13 +428,14 @@ void validate_range(const tent_ctx* ctx, uint32_t j0, uint32_t j1, const uint32_
 // extents: the walk streams some tens of megabytes and is the longest part of a declaration.
 int validate(const tent_ctx* ctx, uint32_t n_desc, const uint32_t* sp, const tent_extent* se,
              const uint32_t* dp, const tent_extent* de, tent_extent* se_out, tent_extent* de_out,
-             uint64_t* payload, uint64_t* n_slices, uint64_t* len_bits, uint64_t* max_req_slices)
+             uint64_t* payload, uint64_t* n_slices, uint64_t* len_bits, uint64_t* max_req_slices, bool may_spawn)
 {
     constexpr uint32_t kMaxWalkers = 4;
     constexpr uint64_t kExtentsPerWalker = 1ull << 16;
     const uint64_t n_ext = (uint64_t)sp[n_desc] + dp[n_desc];
     uint32_t walkers = (uint32_t)std::min<uint64_t>(kMaxWalkers, n_ext / kExtentsPerWalker);
     walkers = std::min(walkers, std::max(1u, std::thread::hardware_concurrency()));
+    if (!may_spawn) walkers = 1;                       // a thread's stack is an allocation: not for callers that forbid them
     WalkResult part[kMaxWalkers];
     uint32_t used = 1;
     if (walkers >= 2) {
@@ -617,7 +618,7 @@ int declare_impl(tent_ctx* ctx, uint32_t n_desc, const uint32_t* src_ptr, const 
 
     uint64_t payload = 0, n_slices = 0, len_bits = 0, max_req_slices = 0;
     int rc = validate(ctx, n_desc, src_ptr, src_ext, dst_ptr, dst_ext, st ? (tent_extent*)(st + o_se) : nullptr,
-                      st ? (tent_extent*)(st + o_de) : nullptr, &payload, &n_slices, &len_bits, &max_req_slices);
+                      st ? (tent_extent*)(st + o_de) : nullptr, &payload, &n_slices, &len_bits, &max_req_slices, !use_static);
     if (rc != TENT_OK) return rc;
     if (n_slices >= 0xFFFFFFFEull) return TENT_ERR_RANGE;
 
