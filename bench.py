@@ -40,11 +40,11 @@ ALL_LEGS = ("configs", "declare", "concurrent", "feedback", "recovery", "replann
 # sources changes they are reported as null until the counters are taken again.
 PMC_SOURCES = ("copy.hip", "copy_generic.h", "split.hip", "tile_tables.h")
 PMC_TRAFFIC = {
-    "copy_sources_sha256": "31834b06bd39d6de362eb16aeaa347f0e6d338936f595c19ae63823851903d75",
+    "copy_sources_sha256": "40cb27ddb00ff4ebb63f4a50cccb998e176129192c040f14719fefbf480c15aa",
     # bytes read + bytes written per launch (profiles/copy_kernels_hbm_traffic.txt)
-    "kv_migration": {"gather": 43019355975, "scatter": 43019360711},
-    "rl_params": {"gather": 30488266590, "scatter": 30488272094},
-    "many_small_x6": {"gather": 33592918596, "scatter": 33592913604},
+    "kv_migration": {"gather": 43019356871, "scatter": 43019353287},
+    "rl_params": {"gather": 30488282590, "scatter": 30488290142},
+    "many_small_x6": {"gather": 33592918724, "scatter": 33592915140},
 }
 
 
