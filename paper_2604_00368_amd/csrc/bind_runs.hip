@@ -268,15 +268,13 @@ struct ChainVars {
 // with exact slot counts (bracket, interpolation, bisection) and the split repaired slot by slot.  Kept
 // out of line: the chain's loop calls it only where its short path does not apply.
 template <int kWide>
-__device__ __attribute__((noinline)) ChainVars bind_run_general(ChainVars cv, Rail rail, double G, double g, bool live,
+__device__ __attribute__((noinline)) uint64_t bind_run_general(ChainVars cv, Rail rail, double G, double g, bool live,
                                                                uint64_t live_mask, uint64_t A_less_T, int lane, uint32_t l,
                                                                uint32_t m, uint64_t vi, double level_f, double inv_l)
 {
     constexpr int R = kWide;
-    uint64_t P = cv.P, T = cv.T;
-    double Bd = cv.Bd;
-    uint64_t ref_level = cv.ref_level;
-    uint32_t cnt = cv.cnt;
+    const uint64_t T = cv.T;
+    const uint32_t cnt = cv.cnt;
     bool all_proven = cv.all_proven != 0;
     uint32_t k = 0, taken = 0;
     const uint64_t A = A_less_T + T;
@@ -367,13 +365,9 @@ __device__ __attribute__((noinline)) ChainVars bind_run_general(ChainVars cv, Ra
         k -= lane == win;
         --taken;
     }
-    const uint64_t bytes = (uint64_t)k * l;
-    T += bytes;
-    cnt += k;
-    Bd = fma(-(double)k, (double)l, Bd);
-    P = (A + bytes) * (uint64_t)rail.c1;
-    ref_level = kNoLevel;
-    return ChainVars{P, T, Bd, ref_level, cnt, all_proven ? 1u : 0u, k};
+    // only the slot count (low half) and the "every rail has a slot" flag (bit 32) go back: the caller derives its
+    // state from the count, so that the loop's registers are not tied to those of the calling convention
+    return (uint64_t)k | ((uint64_t)(all_proven ? 1u : 0u) << 32);
 }
 
 // Run records reach the chain through a ring of blocks in LDS, kWide records a block, one per lane, each as
@@ -564,10 +558,16 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
             }
         }
         // General path (any state, any level), kept out of line so that the loop stays short.
-        const ChainVars cv = bind_run_general<kWide>(ChainVars{P, T, Bd, ref_level, cnt, all_proven ? 1u : 0u, 0u}, rail, G, g, live,
+        const uint64_t res = bind_run_general<kWide>(ChainVars{P, T, Bd, ref_level, cnt, all_proven ? 1u : 0u, 0u}, rail, G, g, live,
                                                      live_mask, A_less_T, lane, l, m, vi, level_f, inv_l);
-        P = cv.P; T = cv.T; Bd = cv.Bd; ref_level = cv.ref_level; cnt = cv.cnt; all_proven = cv.all_proven != 0;
-        return cv.k;
+        const uint32_t k = (uint32_t)res;
+        all_proven = (res >> 32) != 0;
+        T += (uint64_t)k * l;
+        cnt += k;
+        Bd = fma(-(double)k, (double)l, Bd);
+        P = (A_less_T + T) * (uint64_t)rail.c1;
+        ref_level = kNoLevel;
+        return k;
     };
 
     auto put_row = [&](uint64_t T_before, uint32_t k) {
