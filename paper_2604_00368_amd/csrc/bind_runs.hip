@@ -476,10 +476,12 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
         }
         if (__builtin_expect(!keyed, 0)) win = argmin_cost(cost, live, lane, R);
         const bool mine = lane == win;
-        P = mine ? p_one : P;
-        T += mine ? l : 0u;
-        cnt += mine ? 1u : 0u;
-        Bd -= mine ? (double)l : 0.0;
+        if (mine) {
+            P = p_one;
+            T += l;
+            cnt += 1u;
+            Bd -= (double)l;
+        }
         return mine ? 1u : 0u;
     };
 
