@@ -570,6 +570,40 @@ def test_poll_on_another_stream_sees_the_bytes(H, oracle):
         assert np.array_equal(eng.dst.cpu().numpy(), want)
 
 
+def test_declare_of_a_large_batch_finds_a_bad_extent_anywhere(H, oracle):
+    # large descriptor lists are walked by several host threads, each over a range of transfers: a malformed
+    # extent must be found in whichever range it lies, and the sound batch must count its slices right
+    import torch
+    from paper_2604_00368_amd import binding as T
+    n, piece = 300_000, 48
+    off = (np.arange(n, dtype=np.uint64) * np.uint64(piece))
+    ptr = np.arange(n + 1, dtype=np.uint32)
+    seg_bytes = n * piece
+    dev = torch.device("cuda:0")
+    src = torch.zeros(seg_bytes, dtype=torch.uint8, device=dev)
+    dst = torch.zeros(seg_bytes, dtype=torch.uint8, device=dev)
+    arena = torch.zeros(seg_bytes + 256 * 4, dtype=torch.uint8, device=dev)
+    ctx = T.tent_create(32, arena.data_ptr(), arena.numel(), T.TENT_FLAG_SKIP_OVERLAP_CHECK)
+    try:
+        T.tent_register_segment(ctx, src.data_ptr(), src.numel())
+        T.tent_register_segment(ctx, dst.data_ptr(), dst.numel())
+        se, de = W._extents(0, off, piece), W._extents(1, off, piece)
+        h = T.tent_declare(ctx, ptr, se, ptr, de)
+        assert T.tent_slice_count(ctx, h) == 2 * n                 # 48 bytes = a slice of 32 and a tail of 16
+        T.tent_release(ctx, h)
+        for where in (5, n // 4 + 7, n // 2 + 1, (3 * n) // 4 + 3, n - 1):
+            for side, field, value in ((0, "len", 0), (1, "off", seg_bytes), (0, "seg", 9), (1, "len", piece - 1)):
+                bad_s, bad_d = se.copy(), de.copy()
+                (bad_s if side == 0 else bad_d)[field][where] = value
+                with pytest.raises(T.TentError) as ei:
+                    T.tent_declare(ctx, ptr, bad_s, ptr, bad_d)
+                assert ei.value.status == T.TENT_ERR_INVALID, (where, side, field)
+        h = T.tent_declare(ctx, ptr, se, ptr, de)                  # the context is still sound
+        assert T.tent_slice_count(ctx, h) == 2 * n
+    finally:
+        T.tent_destroy(ctx)
+
+
 def test_declare_release_cycles_reuse_tables(H, oracle):
     # a loop of declare ... release: later declarations take over the table allocations of released batches,
     # of equal and of different sizes, and every batch still plans and moves correctly
