@@ -599,14 +599,19 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
             const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)mine_lo.x, t);
             const uint32_t m = (uint32_t)__builtin_amdgcn_readlane((int)mine_lo.y, t);
             const uint64_t T_before = T;
-            uint32_t k;
             if (m == 1) {
-                k = bind_single(l);
-            } else {
-                k = bind_run(l, m, pair64(mine_lo.z, mine_lo.w, t), __longlong_as_double((long long)pair64(mine_hi.x, mine_hi.y, t)),
-                             __longlong_as_double((long long)pair64(mine_hi.z, mine_hi.w, t)));
+                put_row(T_before, bind_single(l));
+                continue;
             }
-            put_row(T_before, k);
+            put_row(T_before, bind_run(l, m, pair64(mine_lo.z, mine_lo.w, t), __longlong_as_double((long long)pair64(mine_hi.x, mine_hi.y, t)),
+                                       __longlong_as_double((long long)pair64(mine_hi.z, mine_hi.w, t))));
+            // the single slice that usually follows a run (a transfer's tail) is bound in the same round
+            if (t + 1 < in_blk && (uint32_t)__builtin_amdgcn_readlane((int)mine_lo.y, t + 1) == 1u) {
+                ++t;
+                const uint32_t l_tail = (uint32_t)__builtin_amdgcn_readlane((int)mine_lo.x, t);
+                const uint64_t T_mid = T;
+                put_row(T_mid, bind_single(l_tail));
+            }
         }
     }
 
