@@ -521,33 +521,38 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
                 if (__builtin_expect(miss >= -kTol && miss <= kTol, 1)) {
                     // repair one slot at a time: add the cheapest free slot / drop the dearest taken slot; the
                     // first step's winners are already known, further steps redo one reduction each
-                    bool exact = true;                    // false: no near candidate, start over in the general path
-                    while (miss > 0) {
-                        const uint32_t best = (uint32_t)__builtin_amdgcn_readfirstlane((int)up_r);
-                        if (best >= kFarKey) { exact = false; break; }
-                        if (lane == (int)(best & 63u)) {
-                            ++kk;
-                            p_prev = p_next;
-                            p_next += lc1;
-                            up = rail.c0 + (p_next >> 16) - vi;
-                            key_up = kk < m ? up_key() : kNoKey;
+                    // (true: done; false: no near candidate, start over in the general path)
+                    auto repair = [&]() -> bool {
+                        if (miss > 0) {
+                            for (int need = miss;;) {
+                                const uint32_t best = (uint32_t)__builtin_amdgcn_readfirstlane((int)up_r);
+                                if (best >= kFarKey) return false;
+                                if (lane == (int)(best & 63u)) {
+                                    ++kk;
+                                    p_prev = p_next;
+                                    p_next += lc1;
+                                    up = rail.c0 + (p_next >> 16) - vi;
+                                    key_up = kk < m ? up_key() : kNoKey;
+                                }
+                                if (--need == 0) return true;
+                                up_r = wave_reduce32(key_up, R, Min32{});
+                            }
                         }
-                        if (--miss == 0) break;
-                        up_r = wave_reduce32(key_up, R, Min32{});
-                    }
-                    while (miss < 0) {
-                        const uint32_t best = (uint32_t)__builtin_amdgcn_readfirstlane((int)down_r);
-                        if (best >= kFarKey) { exact = false; break; }
-                        if (lane == 63 - (int)(best & 63u)) {
-                            --kk;
-                            p_next = p_prev;
-                            p_prev -= lc1;
-                            down = vi - (rail.c0 + (p_prev >> 16));
-                            key_down = kk > 0 ? down_key() : kNoKey;
+                        for (int drop = -miss;;) {
+                            const uint32_t best = (uint32_t)__builtin_amdgcn_readfirstlane((int)down_r);
+                            if (best >= kFarKey) return false;
+                            if (lane == 63 - (int)(best & 63u)) {
+                                --kk;
+                                p_next = p_prev;
+                                p_prev -= lc1;
+                                down = vi - (rail.c0 + (p_prev >> 16));
+                                key_down = kk > 0 ? down_key() : kNoKey;
+                            }
+                            if (--drop == 0) return true;
+                            down_r = wave_reduce32(key_down, R, Min32{});
                         }
-                        if (++miss == 0) break;
-                        down_r = wave_reduce32(key_down, R, Min32{});
-                    }
+                    };
+                    const bool exact = miss == 0 || repair();
                     if (__builtin_expect(exact, 1)) {
                         P = p_prev;
                         T += (uint64_t)kk * l;
