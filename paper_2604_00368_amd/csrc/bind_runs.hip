@@ -236,7 +236,9 @@ __global__ void __launch_bounds__(256) run_records_kernel(BatchDev b, RailParams
             v = (bytes + 0.5 * (double)(j + 1) * (double)rec.len + sh_hG[j]) / sh_G[j];
             if (j + 1 == n_live || v <= sh_h[j + 1]) break;
         }
-        if (v >= 0.0 && v < 1.0e14) {
+        // no level (the chain then takes its general path) for runs too short to gain from one or too long for
+        // the short path's 32-bit slot sums
+        if (v >= 0.0 && v < 1.0e14 && rec.m > (uint32_t)kTol && rec.m < kLeanRunMax) {
             rec.level = (uint64_t)v;
             rec.level_f = (double)rec.level;
         }
@@ -488,7 +490,7 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
     // A run of m >= 2 slices of l bytes with estimated end level vi: slots per rail.
     auto bind_run = [&](uint32_t l, uint32_t m, uint64_t vi, double level_f, double inv_l) -> uint32_t {
         const uint64_t lc1 = (uint64_t)l * rail.c1;           // cost numerator of one slice on this rail
-        if (__builtin_expect(vi != kNoLevel && m - (uint32_t)(kTol + 1) < kLeanRunMax - (uint32_t)(kTol + 1), 1)) {
+        if (__builtin_expect(vi != kNoLevel, 1)) {          // a record carries a level only for kTol < m < kLeanRunMax
             // Lean path.  Slots at or below the level, per rail: slot j is iff j + 1 < kf, so the count is
             // ceil(kf) - 1, taken as trunc(kf - 1e-6) (an exactly integer kf, common when all lengths are
             // multiples of a power of two, must not count, hence the small bias against rounding noise).  The
@@ -499,21 +501,32 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
             const double kf = fma(fma(level_f, G, Bd), inv_l, -1.0e-6);
             uint32_t kk;                                                          // trunc(kf); below zero gives 0, above 2^32 - 1 saturates
             asm("v_cvt_u32_f64_e32 %0, %1" : "=v"(kk) : "v"(kf));
-            uint64_t p_prev = P + (uint64_t)kk * lc1;                            // slot kk-1 ends here
+            // kk * lc1 from a 32 x 32 -> 64 product and one 32-bit product for the high half (sums are modulo 2^64,
+            // as the exact value fits by the plan's precondition whenever kk is a count that the test below accepts)
+            uint64_t p_prev = P + (uint64_t)kk * (uint32_t)lc1;                  // slot kk-1 ends here
+            p_prev += (uint64_t)((uint32_t)(lc1 >> 32) * kk) << 32;
             uint64_t p_next = p_prev + lc1;                                       // slot kk ends here
-            uint64_t up = rail.c0 + (p_next >> 16) - vi;                          // first free slot above the level: must be >= 1
-            uint64_t down = vi - (rail.c0 + (p_prev >> 16));                      // level above the last taken slot: must be >= 0
+            // costs relative to the level, signed: the first free slot must lie above it (up >= 1), the last taken
+            // slot not above it (below <= 0)
+            const int64_t cv = (int64_t)(rail.c0 - vi);
+            int64_t up = (int64_t)(p_next >> 16) + cv;
+            int64_t below = (int64_t)(p_prev >> 16) + cv;
             // kFar: a rail may lie far on the harmless side of the level (far keys); otherwise every rail must
             // lie within the window, which saves the two selects per run where all rails stay close to the level
-            const bool off = kFar ? live & ((kk > m) | ((kk < m) & ((int64_t)up < 1)) | ((kk > 0) & ((int64_t)down < 0)))
-                                  : live & ((kk > m) | ((kk < m) & (up - 1 >= kRelSpan - 1)) | ((kk > 0) & (down >= kRelSpan)));
-            auto up_key = [&]() -> uint32_t { return up < kRelSpan ? (((uint32_t)up << 6) | (uint32_t)lane) : kFarKey | (uint32_t)lane; };
-            auto down_key = [&]() -> uint32_t { return down < kRelSpan ? (((uint32_t)down << 6) | lane_rev) : kFarKey | lane_rev; };
+            const bool off = kFar ? live & ((kk > m) | ((kk < m) & (up < 1)) | ((kk > 0) & (below > 0)))
+                                  : live & ((kk > m) | ((kk < m) & ((uint64_t)(up - 1) >= kRelSpan - 1)) |
+                                            ((kk > 0) & ((uint64_t)(below + (int64_t)(kRelSpan - 1)) >= kRelSpan)));
+            auto up_key = [&]() -> uint32_t {
+                return up < (int64_t)kRelSpan ? (((uint32_t)up << 6) | (uint32_t)lane) : kFarKey | (uint32_t)lane;
+            };
+            auto down_key = [&]() -> uint32_t {
+                return below > -(int64_t)kRelSpan ? (((0u - (uint32_t)below) << 6) | lane_rev) : kFarKey | lane_rev;
+            };
             {   // a lane that is off adds kOffMark to the slot sum, which then misses m by more than any repair covers
                 // three reductions side by side: slots taken, cheapest free slot, dearest taken slot
                 // (ties: the free slot of the lowest rail is next, the taken slot of the highest rail is last)
                 uint32_t key_up = (live & (kk < m)) ? (kFar ? up_key() : (((uint32_t)up << 6) | (uint32_t)lane)) : kNoKey;
-                uint32_t key_down = (live & (kk > 0)) ? (kFar ? down_key() : (((uint32_t)down << 6) | lane_rev)) : kNoKey;
+                uint32_t key_down = (live & (kk > 0)) ? (kFar ? down_key() : (((0u - (uint32_t)below) << 6) | lane_rev)) : kNoKey;
                 const uint32_t sum_r = wave_reduce32(off ? kOffMark : kk, R, Add32{});
                 uint32_t up_r = wave_reduce32(key_up, R, Min32{});
                 uint32_t down_r = wave_reduce32(key_down, R, Min32{});
@@ -531,7 +544,7 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
                                     ++kk;
                                     p_prev = p_next;
                                     p_next += lc1;
-                                    up = rail.c0 + (p_next >> 16) - vi;
+                                    up = (int64_t)(p_next >> 16) + cv;
                                     key_up = kk < m ? up_key() : kNoKey;
                                 }
                                 if (--need == 0) return true;
@@ -545,7 +558,7 @@ __device__ __forceinline__ void bind_chain(const BatchDev& b, const RailParams& 
                                 --kk;
                                 p_next = p_prev;
                                 p_prev -= lc1;
-                                down = vi - (rail.c0 + (p_prev >> 16));
+                                below = (int64_t)(p_prev >> 16) + cv;
                                 key_down = kk > 0 ? down_key() : kNoKey;
                             }
                             if (--drop == 0) return true;
